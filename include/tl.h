@@ -1,0 +1,155 @@
+/*
+ * tl.h -- C ABI of the ternary-linear library for MI355X (gfx950).
+ *
+ * The library computes the inference form of the ternary linear layer of
+ * Spectra-1.1 (arXiv 2506.23025):
+ *
+ *     Y = X * (gamma * What)^T          (paper App. B, "Inference", steps 1-3)
+ *
+ * with X fp16 [M][K], What in {-1,0,+1} [N][K] kept in one of the packed forms
+ * of paper Sec. 3 and a single fp16 scale gamma per matrix (paper Sec. 2.1).
+ * Accumulation is fp32 and the output is fp16 with round-to-nearest-even
+ * (paper App. G, "Precision-Preserving Accumulation").
+ *
+ * Conventions shared by every entry point
+ *   - All functions return a tl_status and never throw, abort or print.
+ *   - "host" pointers are ordinary CPU memory; "device" pointers are HBM
+ *     addresses valid on the current HIP device.  The caller owns every
+ *     buffer; the library allocates nothing and keeps no state between calls.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Device entry points only enqueue work on that stream and return; they
+ *     never synchronise.  Errors reported by the launch come back as
+ *     TL_ERR_HIP.
+ *   - Matrices are dense row-major.  Packed weights are row-major too: row n
+ *     occupies tl_row_stride_bytes(fmt, K) bytes starting at
+ *     n * tl_row_stride_bytes(fmt, K).
+ */
+#ifndef TL_H_
+#define TL_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum tl_status {
+    TL_OK = 0,
+    TL_ERR_NULL = 1,        /* a required pointer is NULL                         */
+    TL_ERR_SHAPE = 2,       /* M, N or K < 1, or a size product overflows          */
+    TL_ERR_VALUE = 3,       /* weight outside {-1,0,1}, or an invalid packed code  */
+    TL_ERR_ALIGN = 4,       /* device pointer not 16-byte aligned                  */
+    TL_ERR_UNSUPPORTED = 5, /* unknown format / path, or path cannot run the shape */
+    TL_ERR_HIP = 6          /* the HIP runtime reported an error on launch         */
+} tl_status;
+
+typedef enum tl_format {
+    TL_FMT_2BIT = 0,   /* paper Sec. 3.1 with k = 16 digits per 32-bit word      */
+    TL_FMT_1P6BIT = 1  /* 5 trits per byte, plain base 3 (see tl_pack_1p6bit)    */
+} tl_format;
+
+/* Kernel choice for tl_ternary_gemm_path.  AUTO is what tl_ternary_gemm uses. */
+typedef enum tl_path {
+    TL_PATH_AUTO = 0,
+    TL_PATH_GENERIC = 1, /* plain VALU kernel, any M, N, K                        */
+    TL_PATH_GEMV = 2,    /* weight-streaming small-M kernel: M <= 16 per pass     */
+    TL_PATH_MFMA = 3     /* LDS-tiled fp16 MFMA prefill kernel                    */
+} tl_path;
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char* tl_status_str(tl_status s);
+
+/*
+ * Bytes from the start of one packed row to the next.
+ *   TL_FMT_2BIT  : 4 * ceil(K / 16)                  (one uint32 per 16 weights)
+ *   TL_FMT_1P6BIT: ceil(K / 5) rounded up to 16      (one byte per 5 weights;
+ *                  the bytes after the last code byte are zero and never decoded)
+ * Returns 0 for K < 1 or an unknown format.
+ */
+size_t tl_row_stride_bytes(tl_format fmt, int64_t K);
+
+/* N * tl_row_stride_bytes(fmt, K); 0 on bad arguments. */
+size_t tl_packed_bytes(tl_format fmt, int64_t N, int64_t K);
+
+/*
+ * 2-bit packing P of paper Sec. 3.1 with k = 16: digit d' = w + 1 in {0,1,2};
+ * word i of a row holds weights 16i .. 16i+15, weight 16i+j in bits [2j+1:2j].
+ * A short last word is filled with weight 0 (digit 1), as the paper prescribes.
+ *   W   host, int8 [N][K] row-major, every value in {-1,0,1}
+ *   out host, uint32 [N][ceil(K/16)], written completely
+ * TL_ERR_VALUE if any weight is outside {-1,0,1} (out is then unspecified).
+ */
+tl_status tl_pack_2bit(const int8_t* W, int64_t N, int64_t K, uint32_t* out);
+
+/*
+ * 1.6-bit packing: the base-3 block code of paper Sec. 3.2 (k = 5 digits in one
+ * byte) in its plain, unscaled little-endian form: byte b of a row holds weights
+ * 5b .. 5b+4 as sum_i (w[5b+i] + 1) * 3^i, a value in [0, 242].  Missing weights
+ * of the last byte count as 0 (digit 1).  Rows are tl_row_stride_bytes apart and
+ * the stride padding is written as zero.
+ *   W   host, int8 [N][K];  out host, uint8 [N][stride]
+ */
+tl_status tl_pack_1p6bit(const int8_t* W, int64_t N, int64_t K, uint8_t* out);
+
+/*
+ * The fixed-point 1.6-bit code exactly as printed in paper Sec. 3.2 / App. E
+ * (k = 5, p = 8): digits big-endian, Nval = sum_j d'_j 3^(4-j), byte =
+ * floor((Nval * 256 + 242) / 243).  Same row geometry as tl_pack_1p6bit.
+ * Decoded by tl_unpack_1p6bit_fx with the multiply-by-3 digit extraction of
+ * paper App. F, Alg. 1.  Host only.
+ */
+tl_status tl_pack_1p6bit_fx(const int8_t* W, int64_t N, int64_t K, uint8_t* out);
+tl_status tl_unpack_1p6bit_fx(const uint8_t* packed, int64_t N, int64_t K, int8_t* W_out);
+
+/*
+ * Unpacking U (paper Sec. 3.1 "Unpacking/Decoding"; Sec. 3.2 for base 3) on the
+ * host.  packed: host, layout as written by the packers.  W_out: host int8
+ * [N][K].  TL_ERR_VALUE on a 2-bit code 3 or a 1.6-bit byte > 242.
+ */
+tl_status tl_unpack(tl_format fmt, const void* packed, int64_t N, int64_t K, int8_t* W_out);
+
+/*
+ * The same decode on the GPU: packed and W_out are device pointers.  Invalid
+ * codes are not reported; a 2-bit code 3 decodes to +2 and a byte > 242 to the
+ * digits of its value modulo 243.  Exists so that the device decode can be
+ * compared byte for byte with the host one.
+ */
+tl_status tl_unpack_dev(tl_format fmt, const void* packed, int64_t N, int64_t K,
+                        int8_t* W_out, void* stream);
+
+/*
+ * y[m][n] = fp16_rne( float(gamma) * sum_k x[m][k] * w[n][k] ),  fp32 accumulation.
+ *   x       device, fp16 [M][K] row-major, 16-byte aligned
+ *   Wpacked device, TL_FMT_2BIT layout, 16-byte aligned
+ *   gamma_fp16_bits  the per-matrix scale as raw IEEE binary16 bits
+ *   y       device, fp16 [M][N] row-major, 16-byte aligned; fully overwritten
+ * Any M, N, K >= 1 is accepted; the library picks the kernel from the shape
+ * (small M: weight-streaming kernel; large M: LDS-tiled MFMA kernel; shapes the
+ * fast kernels cannot take: the generic kernel).  Results are deterministic:
+ * no atomics, fixed reduction order.  Behaviour on a 2-bit code 3 is memory-safe
+ * but otherwise unspecified.
+ */
+tl_status tl_ternary_gemm(const void* x, const void* Wpacked, uint16_t gamma_fp16_bits,
+                          void* y, int64_t M, int64_t N, int64_t K, void* stream);
+
+/* Same, with the kernel forced.  TL_ERR_UNSUPPORTED if `path` cannot run the shape. */
+tl_status tl_ternary_gemm_path(const void* x, const void* Wpacked, uint16_t gamma_fp16_bits,
+                               void* y, int64_t M, int64_t N, int64_t K, void* stream,
+                               tl_path path);
+
+/* Same contract for weights in the TL_FMT_1P6BIT layout of tl_pack_1p6bit. */
+tl_status tl_ternary_gemm_1p6(const void* x, const void* Wpacked, uint16_t gamma_fp16_bits,
+                              void* y, int64_t M, int64_t N, int64_t K, void* stream);
+
+/*
+ * Bandwidth calibration: a plain streaming copy dst[i] = src[i] of `bytes` bytes
+ * (multiple of 16, both device pointers 16-byte aligned).  Not part of the
+ * method; it gives the HBM counters and timers a kernel of known traffic.
+ */
+tl_status tl_probe_copy(void* dst, const void* src, size_t bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TL_H_ */

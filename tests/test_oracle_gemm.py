@@ -1,0 +1,120 @@
+"""Pins for the oracle's number conversion and GEMM (CPU only)."""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+import synth_inputs as si
+
+
+def test_half_to_double_matches_numpy_on_all_65536_patterns():
+    bits = np.arange(65536, dtype=np.uint16)
+    ref = bits.view(np.float16).astype(np.float64)
+    got = np.array([oracle.half_to_double(int(b)) for b in bits])
+    nan = np.isnan(ref)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan], ref[~nan])
+    assert np.array_equal(np.signbit(got[~nan]), np.signbit(ref[~nan]))
+
+
+def _tiny(seed, M, N, K):
+    rng = np.random.default_rng(seed)
+    x = (rng.standard_normal((M, K)) * 3).astype(np.float16)
+    W = rng.integers(-1, 2, size=(N, K)).astype(np.int8)
+    g = np.float16(rng.uniform(0.01, 0.05))
+    return x, W, g
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (2, 3, 5), (3, 2, 32), (4, 4, 17)])
+def test_gemm_brute_force_exact_rationals(M, N, K):
+    # the definition, evaluated in exact rational arithmetic, element by element
+    x, W, g = _tiny(10 + K, M, N, K)
+    y = oracle.gemm(x, W, g)
+    for m in range(M):
+        for n in range(N):
+            s = sum(Fraction(float(x[m, k])) * int(W[n, k]) for k in range(K))
+            exact = Fraction(float(g)) * s
+            # gamma and S are exact in fp64 and so is their product here (11 + <40 bits)
+            assert Fraction(y[m, n]) == exact
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 7, 64), (5, 9, 100), (3, 33, 4096), (2, 4, 11008)])
+def test_gemm_matches_numpy_fp64_matmul(M, N, K):
+    # a library routine on the textbook formula; non-square and asymmetric so that a
+    # transposed operand or swapped index cannot pass
+    x, W, g = si.layer(77 + K, M, N, K)
+    y = oracle.gemm(x, W, g)
+    ref = (x.astype(np.float64) @ W.astype(np.float64).T) * float(g)
+    assert y.shape == (M, N)
+    assert np.array_equal(y, ref)      # every partial sum is exact in fp64, so no tolerance
+
+
+def test_gemm_fixed_point_form_agrees_bit_for_bit():
+    x, W, g = si.layer(5, 3, 11, 4096)
+    x[0, :8] = np.array([0, 6e-8, -6e-8, 6.1e-5, -65504, 65504, 1e-3, -0.0], dtype=np.float16)
+    y = oracle.gemm(x, W, g)
+    S24 = oracle.gemm_fixed(x, W)
+    y2 = float(g) * (S24.astype(np.float64) * 2.0 ** -24)
+    assert np.array_equal(y, y2)
+
+
+def test_gemm_identities():
+    M, N, K = 3, 24, 160
+    x, W, g = si.layer(9, M, N, K)
+    y = oracle.gemm(x, W, g)
+    # y(-W) = -y, y(0) = 0, exactly
+    assert np.array_equal(oracle.gemm(x, -W, g), -y)
+    assert not oracle.gemm(x, np.zeros_like(W), g).any()
+    # scaling x by 2 doubles y exactly; rows of x are independent
+    assert np.array_equal(oracle.gemm((x * np.float16(2)), W, g), 2 * y)
+    for m in range(M):
+        assert np.array_equal(oracle.gemm(x[m:m + 1], W, g), y[m:m + 1])
+    # additivity over a split of K
+    k1 = 48
+    y1 = oracle.gemm(np.ascontiguousarray(x[:, :k1]), np.ascontiguousarray(W[:, :k1]), np.float16(1))
+    y2 = oracle.gemm(np.ascontiguousarray(x[:, k1:]), np.ascontiguousarray(W[:, k1:]), np.float16(1))
+    assert np.array_equal(oracle.gemm(x, W, np.float16(1)), y1 + y2)
+
+
+def test_gemm_identity_and_permutation_weights_return_gamma_x():
+    K = 96
+    rng = np.random.default_rng(3)
+    x = si.activations(rng, 4, K)
+    g = np.float16(0.02)
+    I = np.eye(K, dtype=np.int8)
+    y = oracle.gemm(x, I, g)
+    assert np.array_equal(y, float(g) * x.astype(np.float64))
+    perm = rng.permutation(K)
+    P = np.zeros((K, K), dtype=np.int8)
+    P[np.arange(K), perm] = -1
+    assert np.array_equal(oracle.gemm(x, P, g), -float(g) * x.astype(np.float64)[:, perm])
+    # fp16 product of two fp16 numbers is exact in fp32: the rounded output is fp16(g * x)
+    y16 = oracle.to_fp16(y)
+    assert np.array_equal(y16, (x.astype(np.float32) * np.float32(g)).astype(np.float16))
+
+
+def test_gemm_packed_equals_unpacked_and_padding_contributes_nothing():
+    M, N, K = 2, 9, 100                      # 100 = 6 words + a 4-digit tail
+    x, W, g = si.layer(21, M, N, K)
+    y = oracle.gemm(x, W, g)
+    assert np.array_equal(oracle.gemm_packed2(x, oracle.pack2(W), g, K), y)
+    assert np.array_equal(oracle.gemm_packed3le(x, oracle.pack3le(W), g, K), y)
+    # Sec. 3.1 pads with d = 0: widening K to the word boundary with zero weights and
+    # arbitrary activations leaves y unchanged
+    Kp = 112
+    Wp = np.zeros((N, Kp), dtype=np.int8)
+    Wp[:, :K] = W
+    xp = si.activations(np.random.default_rng(4), M, Kp)
+    xp[:, :K] = x
+    assert np.array_equal(oracle.gemm(xp, Wp, g), y)
+
+
+def test_gamma_is_the_fp16_value():
+    x, W, _ = si.layer(2, 1, 4, 64)
+    g = np.float16(0.02)                     # 0.02 is not representable: fp16 holds 0.0200042724609375
+    assert float(g) == 0.0200042724609375
+    y = oracle.gemm(x, W, g)
+    y1 = oracle.gemm(x, W, np.float16(1))
+    assert np.array_equal(y, 0.0200042724609375 * y1)
+    assert np.array_equal(oracle.gemm(x, W, si.gamma_bits(g)), y)
