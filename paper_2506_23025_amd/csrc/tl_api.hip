@@ -1,0 +1,115 @@
+// C-ABI entry points that touch the device: argument checks, kernel choice, launch.
+#include "tl_internal.hpp"
+
+#include <cmath>
+
+namespace tl {
+
+float half_bits_to_float(uint16_t h)
+{
+    const int sign = (h >> 15) & 1;
+    const int e = (h >> 10) & 0x1F;
+    const int f = h & 0x3FF;
+    float v;
+    if (e == 0) v = std::ldexp(static_cast<float>(f), -24);
+    else if (e == 31) v = f ? NAN : INFINITY;
+    else v = std::ldexp(static_cast<float>(1024 + f), e - 25);
+    return sign ? -v : v;
+}
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline bool dims_ok(int64_t M, int64_t N, int64_t K)
+{
+    const int64_t lim = int64_t(1) << 31;
+    return M >= 1 && N >= 1 && K >= 1 && M < lim && N < lim && K < lim &&
+           M * N < (int64_t(1) << 40) && N * K < (int64_t(1) << 42) && M * K < (int64_t(1) << 40);
+}
+
+inline tl_status from_hip(hipError_t e) { return e == hipSuccess ? TL_OK : TL_ERR_HIP; }
+
+// M at and below which the weight-streaming kernel is used when both fast kernels fit.
+constexpr int64_t kGemvMaxM = 64;
+
+}  // namespace
+}  // namespace tl
+
+extern "C" {
+
+tl_status tl_unpack_dev(tl_format fmt, const void* packed, int64_t N, int64_t K, int8_t* W_out,
+                        void* stream)
+{
+    if (!packed || !W_out) return TL_ERR_NULL;
+    if (!tl::dims_ok(1, N, K)) return TL_ERR_SHAPE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (fmt == TL_FMT_2BIT)
+        return tl::from_hip(tl::launch_unpack2(static_cast<const uint32_t*>(packed), N, K, W_out, s));
+    if (fmt == TL_FMT_1P6BIT)
+        return tl::from_hip(tl::launch_unpack3(static_cast<const uint8_t*>(packed), N, K,
+                                               static_cast<int64_t>(tl_row_stride_bytes(fmt, K)),
+                                               W_out, s));
+    return TL_ERR_UNSUPPORTED;
+}
+
+tl_status tl_ternary_gemm_path(const void* x, const void* Wpacked, uint16_t gamma_fp16_bits, void* y,
+                               int64_t M, int64_t N, int64_t K, void* stream, tl_path path)
+{
+    if (!x || !Wpacked || !y) return TL_ERR_NULL;
+    if (!tl::dims_ok(M, N, K)) return TL_ERR_SHAPE;
+    if (!tl::aligned16(x) || !tl::aligned16(Wpacked) || !tl::aligned16(y)) return TL_ERR_ALIGN;
+    const float gamma = tl::half_bits_to_float(gamma_fp16_bits);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const __half* xh = static_cast<const __half*>(x);
+    const uint32_t* wp = static_cast<const uint32_t*>(Wpacked);
+    __half* yh = static_cast<__half*>(y);
+
+    if (path == TL_PATH_AUTO) {
+        if (M <= tl::kGemvMaxM && tl::gemv_supports(M, N, K)) path = TL_PATH_GEMV;
+        else if (tl::mfma_supports(M, N, K)) path = TL_PATH_MFMA;
+        else if (tl::gemv_supports(M, N, K)) path = TL_PATH_GEMV;
+        else path = TL_PATH_GENERIC;
+    }
+    switch (path) {
+        case TL_PATH_GENERIC:
+            return tl::from_hip(tl::launch_gemm_generic(xh, wp, gamma, yh, M, N, K, s));
+        case TL_PATH_GEMV:
+            if (!tl::gemv_supports(M, N, K)) return TL_ERR_UNSUPPORTED;
+            return tl::from_hip(tl::launch_gemv(xh, wp, gamma, yh, M, N, K, s));
+        case TL_PATH_MFMA:
+            if (!tl::mfma_supports(M, N, K)) return TL_ERR_UNSUPPORTED;
+            return tl::from_hip(tl::launch_mfma(xh, wp, gamma, yh, M, N, K, s));
+        default:
+            return TL_ERR_UNSUPPORTED;
+    }
+}
+
+tl_status tl_ternary_gemm(const void* x, const void* Wpacked, uint16_t gamma_fp16_bits, void* y,
+                          int64_t M, int64_t N, int64_t K, void* stream)
+{
+    return tl_ternary_gemm_path(x, Wpacked, gamma_fp16_bits, y, M, N, K, stream, TL_PATH_AUTO);
+}
+
+tl_status tl_ternary_gemm_1p6(const void* x, const void* Wpacked, uint16_t gamma_fp16_bits, void* y,
+                              int64_t M, int64_t N, int64_t K, void* stream)
+{
+    if (!x || !Wpacked || !y) return TL_ERR_NULL;
+    if (!tl::dims_ok(M, N, K)) return TL_ERR_SHAPE;
+    if (!tl::aligned16(x) || !tl::aligned16(Wpacked) || !tl::aligned16(y)) return TL_ERR_ALIGN;
+    const float gamma = tl::half_bits_to_float(gamma_fp16_bits);
+    return tl::from_hip(tl::launch_gemm3_generic(
+        static_cast<const __half*>(x), static_cast<const uint8_t*>(Wpacked),
+        static_cast<int64_t>(tl_row_stride_bytes(TL_FMT_1P6BIT, K)), gamma, static_cast<__half*>(y),
+        M, N, K, static_cast<hipStream_t>(stream)));
+}
+
+tl_status tl_probe_copy(void* dst, const void* src, size_t bytes, void* stream)
+{
+    if (!dst || !src) return TL_ERR_NULL;
+    if (bytes % 16 != 0) return TL_ERR_SHAPE;
+    if (!tl::aligned16(dst) || !tl::aligned16(src)) return TL_ERR_ALIGN;
+    return tl::from_hip(tl::launch_probe_copy(dst, src, bytes, static_cast<hipStream_t>(stream)));
+}
+
+}  // extern "C"

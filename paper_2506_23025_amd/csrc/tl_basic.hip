@@ -1,0 +1,183 @@
+// Device decode (byte-exact twin of the host decoders), the bandwidth probe and the
+// generic VALU GEMM that accepts every shape.
+#include "tl_internal.hpp"
+
+namespace tl {
+
+namespace {
+
+// ---- Sec. 3.1 decode: one thread per 32-bit word, 16 weights out -------------------
+__global__ void __launch_bounds__(256)
+unpack2_kernel(const uint32_t* __restrict__ packed, int64_t N, int64_t K, int64_t words,
+               int8_t* __restrict__ out)
+{
+    const int64_t gid = blockIdx.x * int64_t(256) + threadIdx.x;
+    if (gid >= N * words) return;
+    const int64_t n = gid / words;
+    const int64_t i = gid - n * words;
+    uint32_t word = packed[gid];
+    const int64_t base = 16 * i;
+    int8_t* dst = out + n * K + base;
+    const int len = (K - base < 16) ? int(K - base) : 16;
+    for (int j = 0; j < len; ++j, word >>= 2) dst[j] = int8_t(int(word & 3u) - 1);
+}
+
+// ---- base-3 byte decode: one thread per byte, up to 5 weights out ------------------
+__global__ void __launch_bounds__(256)
+unpack3_kernel(const uint8_t* __restrict__ packed, int64_t N, int64_t K, int64_t stride,
+               int64_t nbytes, int8_t* __restrict__ out)
+{
+    const int64_t gid = blockIdx.x * int64_t(256) + threadIdx.x;
+    if (gid >= N * nbytes) return;
+    const int64_t n = gid / nbytes;
+    const int64_t b = gid - n * nbytes;
+    unsigned v = packed[n * stride + b];
+    v = (v >= 243u) ? v - 243u : v;
+    const int64_t base = 5 * b;
+    int8_t* dst = out + n * K + base;
+    for (int i = 0; i < 5 && base + i < K; ++i) {
+        const unsigned q = v / 3u;
+        dst[i] = int8_t(int(v - 3u * q) - 1);
+        v = q;
+    }
+}
+
+__global__ void __launch_bounds__(256)
+probe_copy_kernel(u32x4* __restrict__ dst, const u32x4* __restrict__ src, size_t n16)
+{
+    size_t i = blockIdx.x * size_t(256) + threadIdx.x;
+    const size_t step = size_t(gridDim.x) * 256;
+    for (; i < n16; i += step) dst[i] = __builtin_nontemporal_load(src + i);
+}
+
+// ---- generic GEMM ---------------------------------------------------------------
+// One wavefront per output row n and per group of MB activation rows.  Lane l walks the
+// words l, l+64, ... of the packed row, decodes each code with shift-and-mask exactly as
+// Sec. 3.1 states it, and adds or subtracts x (no multiply); fp32 partial sums are folded
+// across the wave with a shuffle butterfly.
+constexpr int MB = 4;
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+__global__ void __launch_bounds__(256)
+gemm_generic_kernel(const __half* __restrict__ x, const uint32_t* __restrict__ Wp, float gamma,
+                    __half* __restrict__ y, int64_t M, int64_t N, int64_t K, int64_t words)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t n = blockIdx.x * int64_t(4) + (threadIdx.x >> 6);
+    const int64_t m0 = blockIdx.y * int64_t(MB);
+    if (n >= N) return;                               // whole wave leaves together
+    float acc[MB];
+    for (int r = 0; r < MB; ++r) acc[r] = 0.f;
+    const uint32_t* row = Wp + n * words;
+    for (int64_t i = lane; i < words; i += 64) {
+        uint32_t word = row[i];
+        const int64_t base = 16 * i;
+        const int len = (K - base < 16) ? int(K - base) : 16;
+        for (int j = 0; j < len; ++j, word >>= 2) {
+            const int w = int(word & 3u) - 1;
+            for (int r = 0; r < MB; ++r) {
+                if (m0 + r < M) {
+                    const float xv = __half2float(x[(m0 + r) * K + base + j]);
+                    acc[r] += (w > 0) ? xv : ((w < 0) ? -xv : 0.f);
+                }
+            }
+        }
+    }
+    for (int r = 0; r < MB; ++r) {
+        const float s = wave_sum(acc[r]);
+        if (lane == 0 && m0 + r < M) y[(m0 + r) * N + n] = __float2half_rn(gamma * s);
+    }
+}
+
+__global__ void __launch_bounds__(256)
+gemm3_generic_kernel(const __half* __restrict__ x, const uint8_t* __restrict__ Wp, int64_t stride,
+                     float gamma, __half* __restrict__ y, int64_t M, int64_t N, int64_t K)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t n = blockIdx.x * int64_t(4) + (threadIdx.x >> 6);
+    const int64_t m0 = blockIdx.y * int64_t(MB);
+    if (n >= N) return;
+    float acc[MB];
+    for (int r = 0; r < MB; ++r) acc[r] = 0.f;
+    const uint8_t* row = Wp + n * stride;
+    const int64_t nbytes = (K + 4) / 5;
+    for (int64_t b = lane; b < nbytes; b += 64) {
+        unsigned v = row[b];
+        v = (v >= 243u) ? v - 243u : v;
+        const int64_t base = 5 * b;
+        for (int i = 0; i < 5 && base + i < K; ++i) {
+            const unsigned q = v / 3u;
+            const int w = int(v - 3u * q) - 1;
+            v = q;
+            for (int r = 0; r < MB; ++r) {
+                if (m0 + r < M) {
+                    const float xv = __half2float(x[(m0 + r) * K + base + i]);
+                    acc[r] += (w > 0) ? xv : ((w < 0) ? -xv : 0.f);
+                }
+            }
+        }
+    }
+    for (int r = 0; r < MB; ++r) {
+        const float s = wave_sum(acc[r]);
+        if (lane == 0 && m0 + r < M) y[(m0 + r) * N + n] = __float2half_rn(gamma * s);
+    }
+}
+
+inline unsigned blocks_for(int64_t items, int per_block)
+{
+    return static_cast<unsigned>((items + per_block - 1) / per_block);
+}
+
+}  // namespace
+
+hipError_t launch_unpack2(const uint32_t* packed, int64_t N, int64_t K, int8_t* out, hipStream_t s)
+{
+    const int64_t words = (K + 15) / 16;
+    hipLaunchKernelGGL(unpack2_kernel, dim3(blocks_for(N * words, 256)), dim3(256), 0, s,
+                       packed, N, K, words, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_unpack3(const uint8_t* packed, int64_t N, int64_t K, int64_t stride, int8_t* out,
+                          hipStream_t s)
+{
+    const int64_t nbytes = (K + 4) / 5;
+    hipLaunchKernelGGL(unpack3_kernel, dim3(blocks_for(N * nbytes, 256)), dim3(256), 0, s,
+                       packed, N, K, stride, nbytes, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_probe_copy(void* dst, const void* src, size_t bytes, hipStream_t s)
+{
+    const size_t n16 = bytes / 16;
+    if (n16 == 0) return hipSuccess;
+    size_t blocks = (n16 + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    hipLaunchKernelGGL(probe_copy_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s,
+                       static_cast<u32x4*>(dst), static_cast<const u32x4*>(src), n16);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_generic(const __half* x, const uint32_t* Wp, float gamma, __half* y,
+                               int64_t M, int64_t N, int64_t K, hipStream_t s)
+{
+    const int64_t words = (K + 15) / 16;
+    dim3 grid(blocks_for(N, 4), blocks_for(M, MB));
+    hipLaunchKernelGGL(gemm_generic_kernel, grid, dim3(256), 0, s, x, Wp, gamma, y, M, N, K, words);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm3_generic(const __half* x, const uint8_t* Wp, int64_t stride, float gamma,
+                                __half* y, int64_t M, int64_t N, int64_t K, hipStream_t s)
+{
+    dim3 grid(blocks_for(N, 4), blocks_for(M, MB));
+    hipLaunchKernelGGL(gemm3_generic_kernel, grid, dim3(256), 0, s, x, Wp, stride, gamma, y, M, N, K);
+    return hipGetLastError();
+}
+
+}  // namespace tl

@@ -1,0 +1,44 @@
+// Internal declarations shared by the .hip translation units of libtl.so.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+#include "tl.h"
+
+namespace tl {
+
+// Clang vector types: what the nontemporal and MFMA builtins take.
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+
+// Launchers return hipGetLastError() of their launch.  All pointers are device pointers.
+hipError_t launch_unpack2(const uint32_t* packed, int64_t N, int64_t K, int8_t* out, hipStream_t s);
+hipError_t launch_unpack3(const uint8_t* packed, int64_t N, int64_t K, int64_t stride, int8_t* out,
+                          hipStream_t s);
+hipError_t launch_probe_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
+
+// Plain VALU kernel: any M, N, K.
+hipError_t launch_gemm_generic(const __half* x, const uint32_t* Wp, float gamma, __half* y,
+                               int64_t M, int64_t N, int64_t K, hipStream_t s);
+hipError_t launch_gemm3_generic(const __half* x, const uint8_t* Wp, int64_t stride, float gamma,
+                                __half* y, int64_t M, int64_t N, int64_t K, hipStream_t s);
+
+// Weight-streaming small-M kernel (2-bit).  Needs K % 64 == 0; handles M in chunks of 16.
+bool gemv_supports(int64_t M, int64_t N, int64_t K);
+hipError_t launch_gemv(const __half* x, const uint32_t* Wp, float gamma, __half* y,
+                       int64_t M, int64_t N, int64_t K, hipStream_t s);
+
+// LDS-tiled MFMA prefill kernel (2-bit).  Needs K % 64 == 0.
+bool mfma_supports(int64_t M, int64_t N, int64_t K);
+hipError_t launch_mfma(const __half* x, const uint32_t* Wp, float gamma, __half* y,
+                       int64_t M, int64_t N, int64_t K, hipStream_t s);
+
+// fp16 bits -> float on the host (exact).
+float half_bits_to_float(uint16_t h);
+
+}  // namespace tl

@@ -1,0 +1,159 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2506_23025_amd as tl
+import synth_inputs as si
+from parity import assert_close, dev_u32, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def run_gemm(x, Wp, g, N, K, path=tl.TL_PATH_AUTO):
+    import torch
+    M = x.shape[0]
+    xd, wd = to_dev(x.view(np.uint16).view(np.int16)), dev_u32(Wp)
+    yd = torch.full((M, N), -21555, dtype=torch.int16, device="cuda")   # poison
+    tl.tl_ternary_gemm_path(xd, wd, si.gamma_bits(g), yd, M, N, K, path=path)
+    torch.cuda.synchronize()
+    return yd.cpu().numpy().view(np.float16)
+
+
+def run_gemm3(x, Wp, g, N, K):
+    import torch
+    M = x.shape[0]
+    xd, wd = to_dev(x.view(np.uint16).view(np.int16)), to_dev(Wp)
+    yd = torch.full((M, N), -21555, dtype=torch.int16, device="cuda")
+    tl.tl_ternary_gemm_1p6(xd, wd, si.gamma_bits(g), yd, M, N, K)
+    torch.cuda.synchronize()
+    return yd.cpu().numpy().view(np.float16)
+
+
+@pytest.mark.parametrize("N,K", [(1, 1), (5, 17), (33, 100), (64, 4096), (7, 11008)])
+def test_unpack_dev_2bit_bit_exact(N, K):
+    import torch
+    W = si.ternary_weights(np.random.default_rng(N + K), N, K)
+    P = oracle.pack2(W)
+    out = torch.full((N, K), 77, dtype=torch.int8, device="cuda")
+    tl.tl_unpack_dev(tl.TL_FMT_2BIT, dev_u32(P), N, K, out)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), W)
+
+
+@pytest.mark.parametrize("N,K", [(1, 1), (5, 17), (33, 101), (64, 4096), (7, 11008)])
+def test_unpack_dev_1p6bit_bit_exact(N, K):
+    import torch
+    W = si.ternary_weights(np.random.default_rng(N + K), N, K)
+    P = oracle.pack3le(W)
+    out = torch.full((N, K), 77, dtype=torch.int8, device="cuda")
+    tl.tl_unpack_dev(tl.TL_FMT_1P6BIT, to_dev(P), N, K, out)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), W)
+
+
+GENERIC_SHAPES = [(1, 1, 1), (1, 3, 16), (2, 5, 17), (3, 70, 100), (5, 129, 4096), (1, 2048, 2048),
+                  (4, 64, 11008), (17, 33, 1000)]
+
+
+@pytest.mark.parametrize("M,N,K", GENERIC_SHAPES)
+def test_gemm_generic_matches_oracle(M, N, K):
+    x, W, g = si.layer(1000 + M + N + K, M, N, K)
+    Wp = tl.tl_pack_2bit(W)
+    assert np.array_equal(Wp, oracle.pack2(W))
+    y = run_gemm(x, Wp, g, N, K, tl.TL_PATH_GENERIC)
+    assert_close(y, oracle.gemm_packed2(x, Wp, g, K), f"generic {M}x{N}x{K}")
+
+
+@pytest.mark.parametrize("M,N,K", GENERIC_SHAPES)
+def test_gemm_1p6_matches_oracle(M, N, K):
+    x, W, g = si.layer(2000 + M + N + K, M, N, K)
+    Wp = tl.tl_pack_1p6bit(W)
+    assert np.array_equal(Wp, oracle.pack3le(W))
+    y = run_gemm3(x, Wp, g, N, K)
+    assert_close(y, oracle.gemm_packed3le(x, Wp, g, K), f"1.6-bit {M}x{N}x{K}")
+
+
+def test_gemm_exact_cases_generic():
+    K = 128
+    rng = np.random.default_rng(4)
+    x = si.activations(rng, 3, K)
+    g = np.float16(0.02)
+    eye = np.eye(K, dtype=np.int8)
+    y = run_gemm(x, tl.tl_pack_2bit(eye), g, K, K, tl.TL_PATH_GENERIC)
+    assert np.array_equal(y, oracle.to_fp16(oracle.gemm(x, eye, g)))      # single product: exact
+    y0 = run_gemm(x, tl.tl_pack_2bit(np.zeros((K, K), dtype=np.int8)), g, K, K, tl.TL_PATH_GENERIC)
+    assert not y0.view(np.uint16).any()
+
+
+# ---------------------------------------------------------------- fast small-M kernel
+
+GEMV_SHAPES = [
+    (1, 16, 64), (1, 1, 64), (3, 17, 128), (16, 100, 512), (5, 33, 576), (2, 48, 1024),
+    (1, 2048, 2048), (7, 272, 4096), (16, 4099, 4096), (4, 40, 11008), (1, 4112, 4160),
+    (17, 64, 1024), (33, 130, 2048), (64, 96, 4096), (9, 2100, 8192),
+]
+
+
+@pytest.mark.parametrize("M,N,K", GEMV_SHAPES)
+def test_gemv_matches_oracle(M, N, K):
+    x, W, g = si.layer(3000 + M + N + K, M, N, K)
+    Wp = tl.tl_pack_2bit(W)
+    y = run_gemm(x, Wp, g, N, K, tl.TL_PATH_GEMV)
+    assert_close(y, oracle.gemm_packed2(x, Wp, g, K), f"gemv {M}x{N}x{K}")
+
+
+def test_gemv_rejects_k_not_multiple_of_64():
+    import torch
+    t = torch.zeros(4096, dtype=torch.int16, device="cuda")
+    with pytest.raises(tl.TlError) as e:
+        tl.tl_ternary_gemm_path(t, t, 0, t, 1, 16, 48, path=tl.TL_PATH_GEMV)
+    assert e.value.status == tl.TL_ERR_UNSUPPORTED
+
+
+def test_gemv_structured_weights():
+    # zero, identity, dense +-1: the kernel's time and correctness do not depend on the values
+    K = N = 512
+    rng = np.random.default_rng(11)
+    x = si.activations(rng, 6, K)
+    g = np.float16(0.03)
+    for W in (np.zeros((N, K), np.int8), np.eye(K, dtype=np.int8), -np.eye(K, dtype=np.int8),
+              np.ones((N, K), np.int8), -np.ones((N, K), np.int8),
+              (rng.integers(0, 2, (N, K)) * 2 - 1).astype(np.int8)):
+        Wp = tl.tl_pack_2bit(W)
+        y = run_gemm(x, Wp, g, N, K, tl.TL_PATH_GEMV)
+        assert_close(y, oracle.gemm(x, W, g), "structured")
+
+
+def test_gemv_large_and_tiny_activations():
+    # |x| up to the fp16 maximum and down to subnormals must not disturb the decode trick
+    K, N = 1024, 64
+    rng = np.random.default_rng(12)
+    W = si.ternary_weights(rng, N, K)
+    g = np.float16(1.0)
+    big = (rng.standard_normal((2, K)) * 40).astype(np.float16)
+    tiny = (rng.standard_normal((2, K)) * 1e-6).astype(np.float16)
+    x = np.concatenate([big, tiny])
+    Wp = tl.tl_pack_2bit(W)
+    y = run_gemm(x, Wp, g, N, K, tl.TL_PATH_GEMV)
+    assert_close(y, oracle.gemm(x, W, g), "range")
+
+
+def test_gemv_is_deterministic_and_odd_symmetric():
+    M, N, K = 8, 4096, 4096
+    x, W, g = si.layer(99, M, N, K)
+    Wp = tl.tl_pack_2bit(W)
+    y0 = run_gemm(x, Wp, g, N, K, tl.TL_PATH_GEMV)
+    for _ in range(5):
+        assert np.array_equal(run_gemm(x, Wp, g, N, K, tl.TL_PATH_GEMV).view(np.uint16), y0.view(np.uint16))
+
+
+def test_auto_path_full_size_sampled_columns():
+    # 4096 -> 14336 at M = 16 through tl_ternary_gemm itself; the oracle checks 512 sampled columns
+    M, N, K = 16, 14336, 4096
+    x, W, g = si.layer(si.SEEDS["c2"], M, N, K)
+    Wp = tl.tl_pack_2bit(W)
+    y = run_gemm(x, Wp, g, N, K)
+    cols = np.sort(np.random.default_rng(0).choice(N, 512, replace=False))
+    ref = oracle.gemm(x, np.ascontiguousarray(W[cols]), g)
+    assert_close(y[:, cols], ref, "full size sampled")

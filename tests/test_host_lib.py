@@ -1,0 +1,115 @@
+"""CPU tests of the library's host side: exports, geometry, packers against the oracle."""
+import ctypes
+import itertools
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2506_23025_amd as tl
+import synth_inputs as si
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "tl.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(tl_[a-z0-9_]+)\s*\(", header))
+    assert declared, "no declarations found"
+    L = ctypes.CDLL(tl.LIB_PATH)
+    for name in sorted(declared):
+        assert hasattr(L, name), f"{name} declared in tl.h but not exported"
+    assert declared == set(tl.EXPORTS)
+
+
+def test_geometry():
+    assert tl.tl_row_stride_bytes(tl.TL_FMT_2BIT, 4096) == 1024
+    assert tl.tl_row_stride_bytes(tl.TL_FMT_2BIT, 17) == 8
+    assert tl.tl_row_stride_bytes(tl.TL_FMT_1P6BIT, 4096) == 832
+    assert tl.tl_row_stride_bytes(tl.TL_FMT_1P6BIT, 11008) == 2208
+    assert tl.tl_row_stride_bytes(tl.TL_FMT_2BIT, 0) == 0
+    assert tl.tl_row_stride_bytes(7, 64) == 0
+    assert tl.tl_packed_bytes(tl.TL_FMT_2BIT, 14336, 4096) == 14336 * 1024
+    assert tl.tl_packed_bytes(tl.TL_FMT_2BIT, 0, 4096) == 0
+    for K in (1, 5, 79, 80, 81, 4096):
+        assert tl.tl_row_stride_bytes(tl.TL_FMT_1P6BIT, K) == oracle.stride3le(K)
+
+
+@pytest.mark.parametrize("N,K", [(1, 1), (3, 15), (4, 16), (5, 17), (2, 100), (7, 4096), (3, 11008)])
+def test_pack_2bit_bit_exact_against_oracle(N, K):
+    W = si.ternary_weights(np.random.default_rng(N * 100003 + K), N, K)
+    P = tl.tl_pack_2bit(W)
+    assert P.dtype == np.uint32 and P.shape == (N, (K + 15) // 16)
+    assert np.array_equal(P, oracle.pack2(W))
+    assert np.array_equal(tl.tl_unpack(tl.TL_FMT_2BIT, P, N, K), W)
+    assert np.array_equal(oracle.unpack2(P, K), W)
+
+
+@pytest.mark.parametrize("N,K", [(1, 1), (3, 4), (4, 5), (5, 6), (2, 81), (7, 4096), (3, 11008)])
+def test_pack_1p6bit_bit_exact_against_oracle(N, K):
+    W = si.ternary_weights(np.random.default_rng(N * 100003 + K), N, K)
+    P = tl.tl_pack_1p6bit(W)
+    assert P.dtype == np.uint8 and P.shape == (N, oracle.stride3le(K))
+    assert np.array_equal(P, oracle.pack3le(W))
+    assert np.array_equal(tl.tl_unpack(tl.TL_FMT_1P6BIT, P, N, K), W)
+
+
+def test_pack_1p6bit_fx_matches_paper_code_and_alg1_decode():
+    all5 = np.array(list(itertools.product((-1, 0, 1), repeat=5)), dtype=np.int8)
+    P = tl.tl_pack_1p6bit_fx(all5)
+    want = [oracle.pack_fx_block(d, 5, 8) for d in all5]
+    assert P[:, 0].tolist() == want
+    assert np.array_equal(tl.tl_unpack_1p6bit_fx(P, 243, 5), all5)
+    # ragged rows
+    W = si.ternary_weights(np.random.default_rng(8), 3, 4096)
+    assert np.array_equal(tl.tl_unpack_1p6bit_fx(tl.tl_pack_1p6bit_fx(W), 3, 4096), W)
+    # each byte decodes like the oracle's Alg. 1
+    Pw = tl.tl_pack_1p6bit_fx(W)
+    for b in range(0, 819, 97):
+        assert oracle.unpack_fx_alg1_block(int(Pw[1, b])).tolist() == W[1, 5 * b:5 * b + 5].tolist()
+
+
+def test_error_codes():
+    L = tl.raw()
+    W = np.zeros((2, 16), dtype=np.int8)
+    out = np.zeros((2, 1), dtype=np.uint32)
+    assert L.tl_pack_2bit(None, 2, 16, out.ctypes.data) == tl.TL_ERR_NULL
+    assert L.tl_pack_2bit(W.ctypes.data, 2, 16, None) == tl.TL_ERR_NULL
+    assert L.tl_pack_2bit(W.ctypes.data, 0, 16, out.ctypes.data) == tl.TL_ERR_SHAPE
+    assert L.tl_pack_2bit(W.ctypes.data, 2, -1, out.ctypes.data) == tl.TL_ERR_SHAPE
+    W[1, 3] = 2
+    assert L.tl_pack_2bit(W.ctypes.data, 2, 16, out.ctypes.data) == tl.TL_ERR_VALUE
+    W[1, 3] = -2
+    out8 = np.zeros((2, 16), dtype=np.uint8)
+    assert L.tl_pack_1p6bit(W.ctypes.data, 2, 16, out8.ctypes.data) == tl.TL_ERR_VALUE
+    assert L.tl_pack_1p6bit_fx(W.ctypes.data, 2, 16, out8.ctypes.data) == tl.TL_ERR_VALUE
+    # invalid codes on unpack
+    bad = np.array([[0x55555557]], dtype=np.uint32)
+    o = np.zeros((1, 16), dtype=np.int8)
+    assert L.tl_unpack(tl.TL_FMT_2BIT, bad.ctypes.data, 1, 16, o.ctypes.data) == tl.TL_ERR_VALUE
+    bad8 = np.zeros((1, 16), dtype=np.uint8)
+    bad8[0, 0] = 243
+    assert L.tl_unpack(tl.TL_FMT_1P6BIT, bad8.ctypes.data, 1, 5, o.ctypes.data) == tl.TL_ERR_VALUE
+    assert L.tl_unpack(9, bad8.ctypes.data, 1, 5, o.ctypes.data) == tl.TL_ERR_UNSUPPORTED
+    # device entry points validate before touching the GPU
+    assert L.tl_ternary_gemm(None, None, 0, None, 1, 1, 16, None) == tl.TL_ERR_NULL
+    assert L.tl_ternary_gemm(16, 16, 0, 16, 0, 1, 16, None) == tl.TL_ERR_SHAPE
+    assert L.tl_ternary_gemm(24, 16, 0, 16, 1, 1, 16, None) == tl.TL_ERR_ALIGN
+    assert L.tl_ternary_gemm_path(16, 16, 0, 16, 1, 1, 16, None, 99) == tl.TL_ERR_UNSUPPORTED
+    assert L.tl_ternary_gemm_1p6(None, 16, 0, 16, 1, 1, 16, None) == tl.TL_ERR_NULL
+    assert L.tl_unpack_dev(tl.TL_FMT_2BIT, None, 1, 16, None, None) == tl.TL_ERR_NULL
+    assert L.tl_probe_copy(16, 16, 24, None) == tl.TL_ERR_SHAPE
+    for s in range(8):
+        assert tl.tl_status_str(s)
+
+
+def test_padding_bits_and_bytes():
+    W = np.ones((1, 19), dtype=np.int8)
+    P = tl.tl_pack_2bit(W)
+    assert P.tolist() == [[0xAAAAAAAA, 0x5555556A]]
+    P3 = tl.tl_pack_1p6bit(W)
+    assert P3[0, :4].tolist() == [242, 242, 242, 2 + 6 + 18 + 54 + 81]
+    assert not P3[0, 4:].any()
