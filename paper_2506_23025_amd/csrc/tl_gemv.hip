@@ -22,8 +22,8 @@
 //    word (<< 4, >> 2, >> 8) therefore bring every code to j in {2, 3, 4}.  Products of
 //    different j carry different power-of-two factors, so they go to three accumulators
 //    that are combined once per tile: sum_j 2^(24-2j) acc_j = sum_k x_k c_k.  With
-//    c = w + 1 the result is sum_k x_k c_k - sum_k x_k; the second sum is formed once per
-//    wave from the activation registers.
+//    c = w + 1 the result is sum_k x_k c_k - sum_k x_k; the second sum comes from one more
+//    group of MFMAs per wave whose 16-row operand is a constant, and seeds the accumulator.
 //  * Split-K partial tiles of the NW waves are added in a fixed order through LDS, scaled
 //    by gamma, rounded to fp16 (RNE) and stored.  No atomics: results are deterministic.
 #include "tl_internal.hpp"
@@ -32,7 +32,7 @@ namespace tl {
 
 namespace {
 
-constexpr int kTMax = 8;          // tiles a workgroup keeps in flight
+constexpr int kTMax = 4;          // tiles a workgroup keeps in flight
 constexpr int kSliceK = 512;      // K elements a wave owns per pass
 constexpr int kWaveLds = 16384;   // bytes of LDS per wave: 16 activation rows x 1 KB
 
@@ -49,9 +49,12 @@ struct GemvParams {
     int passes;     // ceil(slices / NW)
 };
 
-__device__ __forceinline__ u32x4 ldg_nt(const uint32_t* p)
+
+// s_waitcnt immediate for "vmcnt <= n" only (gfx9 layout: vmcnt in bits 3:0 and 15:14,
+// expcnt 6:4 and lgkmcnt 11:8 left at their maxima, i.e. not waited for).
+constexpr int vmcnt_imm(int n)
 {
-    return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+    return (n & 0xF) | ((n >> 4) << 14) | (0x7 << 4) | (0xF << 8);
 }
 
 __device__ __forceinline__ f16x8 as_f16x8(u32x4 v)
@@ -59,20 +62,22 @@ __device__ __forceinline__ f16x8 as_f16x8(u32x4 v)
     return __builtin_bit_cast(f16x8, v);
 }
 
-template <int TMAX>
+// T  tiles per workgroup (tile t of group b is b + t * groups; only the last can be missing)
+// MR activation rows staged per 16-row block (power of two >= Mrem; surplus rows repeat)
+template <int T, int MR>
 __global__ void __launch_bounds__(512)
 gemv_kernel(GemvParams p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int NW = blockDim.x >> 6;
     unsigned char* const my_lds = lds_raw + wave * kWaveLds;
 
     const int m0 = blockIdx.y * 16;
     const int Mrem = (p.M - m0 < 16) ? (p.M - m0) : 16;
     const int K = p.K;
-    const int row_words = K >> 4;
+    const uint32_t row_bytes = uint32_t(K) >> 2;
     const int chunks = K >> 6;                 // 64-weight (16-byte) chunks per row
 
     // ---- coalesced load mapping: 8 lanes per 128-byte line, 8 rows per instruction ----
@@ -81,144 +86,154 @@ gemv_kernel(GemvParams p)
     // ---- MFMA mapping: lane (i, g) = (row / activation column, k group) -----------------
     const int mi = lane & 15;
     const int mg = lane >> 4;
+    const int xrow = mi & (MR - 1);            // staged activation row this lane's column reads
 
-    u32x4 wreg[TMAX][2];
+    // LDS offsets (bytes, relative to my_lds); immediates add the row / tile / half part
+    const uint32_t xr_off = uint32_t(xrow) * 1024u + uint32_t(mg) * 128u;  // + ((c ^ (xrow & 7)) << 4)
+    const uint32_t ww_off = uint32_t(lr) * 128u + (uint32_t(lc ^ lr) << 4);
+    const uint32_t wr_off0 = uint32_t(mi) * 128u + (uint32_t((mg) ^ (mi & 7)) << 4);
+    const uint32_t wr_off1 = uint32_t(mi) * 128u + (uint32_t((4 + mg) ^ (mi & 7)) << 4);
 
-    auto issue_w = [&](int t, int slice, u32x4 (&dst)[2]) {
+    const unsigned char* const Wb = reinterpret_cast<const unsigned char*>(p.W);
+    const unsigned char* const xb = reinterpret_cast<const unsigned char*>(p.x + size_t(m0) * K);
+    const bool last_valid = (blockIdx.x + (T - 1) * p.groups) < p.tiles;
+
+    u32x4 wreg[T][2];
+    auto issue_w = [&](int t, int slice) {
         int tile = blockIdx.x + t * p.groups;
-        if (tile >= p.tiles) tile = p.tiles - 1;          // duplicate work, never stored
+        if (tile >= p.tiles) tile = p.tiles - 1;          // loaded twice, never used
         int chunk = slice * 8 + lc;
         if (chunk >= chunks) chunk = 0;                    // multiplied by zero activations
+        const unsigned char* tb = Wb + size_t(tile) * 16u * row_bytes;
+        const int last = p.N - 1 - tile * 16;              // rows past N read row N-1
+        const uint32_t off0 = uint32_t(lr < last ? lr : last) * row_bytes + uint32_t(chunk) * 16u;
+        const uint32_t off1 = uint32_t(lr + 8 < last ? lr + 8 : last) * row_bytes + uint32_t(chunk) * 16u;
+        wreg[t][0] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tb + off0));
+        wreg[t][1] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tb + off1));
+    };
+
+    // Activation rows go straight from global memory into the LDS staging area (LDS-DMA, no
+    // registers): one instruction per staged row, lane l fetches the 16-byte piece
+    // l ^ (r & 7) of the slice and the hardware drops it at slot l, which is the swizzled
+    // layout the operand set-up reads.  Rows past Mrem repeat row Mrem-1; lanes past K
+    // store zeros instead (their weights are whatever chunk 0 holds).
+    auto issue_x = [&](int slice) {
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            int row = tile * 16 + q * 8 + lr;
-            if (row >= p.N) row = p.N - 1;
-            dst[q] = ldg_nt(p.W + size_t(row) * row_words + chunk * 4);
+        for (int r = 0; r < MR; ++r) {
+            const int rr = r < Mrem ? r : Mrem - 1;
+            const int kx = slice * kSliceK + ((lane ^ (r & 7)) << 3);
+            if (kx < K) {
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void*)(xb + size_t(rr) * K * 2 + uint32_t(kx) * 2u),
+                    (__attribute__((address_space(3))) void*)(my_lds + r * 1024),
+                    16, 0, 0);
+            } else {
+                *reinterpret_cast<u32x4*>(my_lds + r * 1024 + (uint32_t(lane) << 4)) = u32x4{0u, 0u, 0u, 0u};
+            }
         }
     };
 
-    f32x4 part[TMAX];
+    f32x4 part[T];
 #pragma unroll
-    for (int t = 0; t < TMAX; ++t) part[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float sx = 0.f;
+    for (int t = 0; t < T; ++t) part[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+    // Activations go first: they are short L2 hits, and the loads of one wave return in
+    // order, so the weight stream queued behind them overlaps the operand set-up below.
     int slice = wave;
     if (slice < p.slices) {
+        issue_x(slice);
 #pragma unroll
-        for (int t = 0; t < TMAX; ++t)
-            if (t < p.T) issue_w(t, slice, wreg[t]);
+        for (int t = 0; t < T; ++t) issue_w(t, slice);
+        // The compiler does not track LDS-DMA: wait by hand until only the 2T weight loads
+        // issued after the activation rows are outstanding (loads of a wave return in order).
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * T));
     }
 
     for (int pass = 0; pass < p.passes; ++pass, slice += NW) {
         if (slice >= p.slices) break;                      // wave-uniform
+        const bool more = (slice + NW) < p.slices;
         // ---------------- activations of this slice -> MFMA B registers ----------------
-        // coalesced: one instruction per activation row, lane l takes 8 halves (16 bytes)
-        u32x4 xraw[16];
-        const int kx = slice * kSliceK + lane * 8;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            xraw[r] = u32x4{0u, 0u, 0u, 0u};
-            if (r < Mrem && kx < K)
-                xraw[r] = *reinterpret_cast<const u32x4*>(p.x + size_t(m0 + r) * K + kx);
-        }
-        // swizzled staging: row r, 16-byte piece (lane ^ (r & 7))
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-            if (r < Mrem)
-                *reinterpret_cast<u32x4*>(my_lds + r * 1024 + ((lane ^ (r & 7)) << 4)) = xraw[r];
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-
+        // staging layout: row r, 16-byte piece P at slot P ^ (r & 7)
         // breg[h][wd][e]: (x[k], x[k + 8]) with k = slice0 + 64 (4h + g) + 16 wd + e
         uint32_t breg[2][4][8];
-#pragma unroll
-        for (int h = 0; h < 2; ++h)
-#pragma unroll
-            for (int wd = 0; wd < 4; ++wd) {
-                u32x4 lo = u32x4{0u, 0u, 0u, 0u}, hi = u32x4{0u, 0u, 0u, 0u};
-                if (mi < Mrem) {
-                    const int piece = 32 * h + 8 * mg + 2 * wd;     // 16-byte pieces of the row
-                    lo = *reinterpret_cast<const u32x4*>(my_lds + mi * 1024 + (((piece) ^ (mi & 7)) << 4));
-                    hi = *reinterpret_cast<const u32x4*>(my_lds + mi * 1024 + (((piece + 1) ^ (mi & 7)) << 4));
-                }
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    breg[h][wd][2 * r] = __builtin_amdgcn_perm(hi[r], lo[r], 0x05040100u);
-                    breg[h][wd][2 * r + 1] = __builtin_amdgcn_perm(hi[r], lo[r], 0x07060302u);
-                }
-            }
-        // sum of this lane's activations (each k of the slice sits in exactly one register half)
         {
-            const f16x2 ones = {(_Float16)1.0f, (_Float16)1.0f};
+            const uint32_t sw = uint32_t(xrow & 7);
 #pragma unroll
             for (int h = 0; h < 2; ++h)
 #pragma unroll
-                for (int wd = 0; wd < 4; ++wd)
+                for (int wd = 0; wd < 4; ++wd) {
+                    const u32x4 lo = *reinterpret_cast<const u32x4*>(
+                        my_lds + xr_off + h * 512 + ((uint32_t(2 * wd) ^ sw) << 4));
+                    const u32x4 hi = *reinterpret_cast<const u32x4*>(
+                        my_lds + xr_off + h * 512 + ((uint32_t(2 * wd + 1) ^ sw) << 4));
 #pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        sx = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, breg[h][wd][e]), ones, sx, false);
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-
-        // ---------------- stream the tiles of this slice ---------------------------------
-        const bool more = (slice + NW) < p.slices;
-#pragma unroll
-        for (int t = 0; t < TMAX; ++t) {
-            if (t < p.T) {
-                unsigned char* tl_lds = my_lds + t * 2048;
-                // turn the tile slice: [row][chunk ^ (row & 7)]
-#pragma unroll
-                for (int q = 0; q < 2; ++q) {
-                    const int row = q * 8 + lr;
-                    *reinterpret_cast<u32x4*>(tl_lds + row * 128 + ((lc ^ (row & 7)) << 4)) = wreg[t][q];
-                }
-                if (more) issue_w(t, slice + NW, wreg[t]);          // prefetch the next pass
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-
-                f32x4 acc[3];
-#pragma unroll
-                for (int j = 0; j < 3; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const int cc = 4 * h + mg;
-                    const u32x4 wv = *reinterpret_cast<const u32x4*>(tl_lds + mi * 128 + ((cc ^ (mi & 7)) << 4));
-                    // element e of each half-word is moved to mantissa bits 4..9 (position
-                    // class 2, 3 or 4): e = 0..2 by << 4, e = 3..5 by >> 2, e = 6..7 by >> 8
-                    const u32x4 sh[3] = {wv << 4, wv >> 2, wv >> 8};
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const int j = e % 3;                        // accumulator: class j + 2
-                        const uint32_t mask = 0x00300030u << (2 * j);
-                        const u32x4 a = sh[e / 3] & mask;
-                        const u32x4 b = u32x4{breg[h][0][e], breg[h][1][e], breg[h][2][e], breg[h][3][e]};
-                        acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), as_f16x8(b), acc[j], 0, 0, 0);
+                    for (int r = 0; r < 4; ++r) {
+                        breg[h][wd][2 * r] = __builtin_amdgcn_perm(hi[r], lo[r], 0x05040100u);
+                        breg[h][wd][2 * r + 1] = __builtin_amdgcn_perm(hi[r], lo[r], 0x07060302u);
                     }
                 }
-                // fp16 bits c << (2j + 4) are the subnormal c 4^(j+2) 2^-24: undo with 2^(20 - 2j)
-                part[t] += acc[0] * 1048576.f + acc[1] * 262144.f + acc[2] * 65536.f;
-            }
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-    }
+        // nsx[r] = -2^-20 sum_k x[m][k] over the slice, in the layout of an accumulator:
+        // an MFMA whose 16-row operand is the constant -2^-20 in every position.
+        f32x4 nsx = f32x4{0.f, 0.f, 0.f, 0.f};
+        {
+            const uint32_t c = 0x80108010u;               // fp16 pair of -2^-20 (subnormal 0x0010, sign set)
+            const u32x4 a = u32x4{c, c, c, c};
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const u32x4 b = u32x4{breg[h][0][e], breg[h][1][e], breg[h][2][e], breg[h][3][e]};
+                    nsx = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), as_f16x8(b), nsx, 0, 0, 0);
+                }
+        }
 
-    // ---- sum_k x_k over the wave's slices, for this lane's activation column -----------
-    sx += __shfl_xor(sx, 16, 64);
-    sx += __shfl_xor(sx, 32, 64);
+        // ---------------- per tile: turn through LDS, decode, MFMA -----------------------
+        // Tile t lives at my_lds + 16 KB-free area?  No: the staging rows are dead once breg is
+        // built, so region t (2 KB) reuses them; LDS operations of one wave execute in order.
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            if (t == T - 1 && !last_valid) break;          // scalar branch, last tile only
+            unsigned char* const reg_t = my_lds + t * 2048;
+            *reinterpret_cast<u32x4*>(reg_t + ww_off) = wreg[t][0];
+            *reinterpret_cast<u32x4*>(reg_t + 1024 + ww_off) = wreg[t][1];
+            if (more) issue_w(t, slice + NW);              // refill for the next pass
+            // acc[0] starts from -2^-20 sum x: with the 2^20 below it carries the "-1" of c = w + 1
+            f32x4 acc[3] = {nsx, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const u32x4 wv = *reinterpret_cast<const u32x4*>(reg_t + (h ? wr_off1 : wr_off0));
+                // element e of each half-word is moved to mantissa bits 4..9 (position
+                // class 2, 3 or 4): e = 0..2 by << 4, e = 3..5 by >> 2, e = 6..7 by >> 8
+                const u32x4 sh[3] = {wv << 4, wv >> 2, wv >> 8};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int j = e % 3;                        // accumulator: class j + 2
+                    const uint32_t mask = 0x00300030u << (2 * j);
+                    const u32x4 a = sh[e / 3] & mask;
+                    const u32x4 b = u32x4{breg[h][0][e], breg[h][1][e], breg[h][2][e], breg[h][3][e]};
+                    acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), as_f16x8(b), acc[j], 0, 0, 0);
+                }
+            }
+            // fp16 bits c << (2j + 4) are the subnormal c 4^(j+2) 2^-24: undo with 2^(20 - 2j)
+            part[t] += acc[0] * 1048576.f + acc[1] * 262144.f + acc[2] * 65536.f;
+        }
+        // The staging rows share LDS with the tile regions, so the next slice's activations
+        // can only be fetched once the last tile has been read.
+        if (more) {
+            issue_x(slice + NW);
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));       // behind the prefetched weights
+        }
+    }
 
     // ---- split-K reduction across the waves, epilogue -----------------------------------
     // Layout [t][wave][lane] of f32x4 in LDS (reuses the staging space after a barrier).
     __syncthreads();
     f32x4* red = reinterpret_cast<f32x4*>(lds_raw);
 #pragma unroll
-    for (int t = 0; t < TMAX; ++t)
-        if (t < p.T) red[(t * NW + wave) * 64 + lane] = part[t] - sx;
+    for (int t = 0; t < T; ++t) red[(t * NW + wave) * 64 + lane] = part[t];
     __syncthreads();
-    for (int item = threadIdx.x; item < p.T * 64; item += blockDim.x) {
+    for (int item = threadIdx.x; item < T * 64; item += blockDim.x) {
         const int t = item >> 6;
         const int l = item & 63;
         const int tile = blockIdx.x + t * p.groups;
@@ -233,6 +248,38 @@ gemv_kernel(GemvParams p)
             for (int r = 0; r < 4; ++r)
                 if (n + r < p.N) dst[r] = __float2half_rn(p.gamma * s[r]);
         }
+    }
+}
+
+using KernelFn = void (*)(GemvParams);
+
+template <int T>
+KernelFn pick_mr(int mr)
+{
+    switch (mr) {
+        case 1: return gemv_kernel<T, 1>;
+        case 2: return gemv_kernel<T, 2>;
+        case 4: return gemv_kernel<T, 4>;
+        case 8: return gemv_kernel<T, 8>;
+        default: return gemv_kernel<T, 16>;
+    }
+}
+
+// Smallest instantiated T that is >= t (t <= kTMax).
+int round_tiles(int t)
+{
+    static const int have[] = {1, 2, 3, 4};
+    for (int v : have) if (v >= t) return v;
+    return kTMax;
+}
+
+KernelFn pick_kernel(int T, int mr)
+{
+    switch (T) {
+        case 1: return pick_mr<1>(mr);
+        case 2: return pick_mr<2>(mr);
+        case 3: return pick_mr<3>(mr);
+        default: return pick_mr<4>(mr);
     }
 }
 
@@ -254,20 +301,30 @@ hipError_t launch_gemv(const __half* x, const uint32_t* Wp, float gamma, __half*
     p.slices = int((K + kSliceK - 1) / kSliceK);
     const int NW = p.slices < 8 ? p.slices : 8;
     p.passes = (p.slices + NW - 1) / NW;
+    // One workgroup per CU when there is enough work; a group strides over the tiles.
     int groups = p.tiles < 256 ? p.tiles : 256;
     int T = (p.tiles + groups - 1) / groups;
     if (T > kTMax) { T = kTMax; groups = (p.tiles + T - 1) / T; }
+    T = round_tiles(T);
+    // with the rounded T only the last tile of a group may be missing
+    if (int64_t(T - 1) * groups >= p.tiles) groups = (p.tiles + T - 1) / T;
     p.groups = groups; p.T = T;
+    int mr = 1;
+    const int mfirst = M < 16 ? int(M) : 16;
+    while (mr < mfirst) mr *= 2;
     const size_t lds = size_t(NW) * kWaveLds;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemv_kernel<kTMax>),
+    KernelFn fn = pick_kernel(T, mr);
+    // Groups of 5 or more waves need more than the default 64 KB of dynamic LDS; the
+    // attribute is set once per kernel instance (idempotent, so a race only repeats it).
+    static bool lds_raised[kTMax + 1][17];
+    if (!lds_raised[T][mr]) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 8 * kWaveLds);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        lds_raised[T][mr] = true;
     }
     dim3 grid(groups, unsigned((M + 15) / 16));
-    hipLaunchKernelGGL(gemv_kernel<kTMax>, grid, dim3(NW * 64), lds, s, p);
+    hipLaunchKernelGGL(fn, grid, dim3(NW * 64), lds, s, p);
     return hipGetLastError();
 }
 

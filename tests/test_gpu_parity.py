@@ -62,7 +62,7 @@ def test_gemm_generic_matches_oracle(M, N, K):
     Wp = tl.tl_pack_2bit(W)
     assert np.array_equal(Wp, oracle.pack2(W))
     y = run_gemm(x, Wp, g, N, K, tl.TL_PATH_GENERIC)
-    assert_close(y, oracle.gemm_packed2(x, Wp, g, K), f"generic {M}x{N}x{K}")
+    assert_close(y, oracle.gemm_packed2(x, Wp, g, K), x, g, f"generic {M}x{N}x{K}")
 
 
 @pytest.mark.parametrize("M,N,K", GENERIC_SHAPES)
@@ -71,7 +71,7 @@ def test_gemm_1p6_matches_oracle(M, N, K):
     Wp = tl.tl_pack_1p6bit(W)
     assert np.array_equal(Wp, oracle.pack3le(W))
     y = run_gemm3(x, Wp, g, N, K)
-    assert_close(y, oracle.gemm_packed3le(x, Wp, g, K), f"1.6-bit {M}x{N}x{K}")
+    assert_close(y, oracle.gemm_packed3le(x, Wp, g, K), x, g, f"1.6-bit {M}x{N}x{K}")
 
 
 def test_gemm_exact_cases_generic():
@@ -100,7 +100,7 @@ def test_gemv_matches_oracle(M, N, K):
     x, W, g = si.layer(3000 + M + N + K, M, N, K)
     Wp = tl.tl_pack_2bit(W)
     y = run_gemm(x, Wp, g, N, K, tl.TL_PATH_GEMV)
-    assert_close(y, oracle.gemm_packed2(x, Wp, g, K), f"gemv {M}x{N}x{K}")
+    assert_close(y, oracle.gemm_packed2(x, Wp, g, K), x, g, f"gemv {M}x{N}x{K}")
 
 
 def test_gemv_rejects_k_not_multiple_of_64():
@@ -122,7 +122,7 @@ def test_gemv_structured_weights():
               (rng.integers(0, 2, (N, K)) * 2 - 1).astype(np.int8)):
         Wp = tl.tl_pack_2bit(W)
         y = run_gemm(x, Wp, g, N, K, tl.TL_PATH_GEMV)
-        assert_close(y, oracle.gemm(x, W, g), "structured")
+        assert_close(y, oracle.gemm(x, W, g), x, g, "structured")
 
 
 def test_gemv_large_and_tiny_activations():
@@ -136,7 +136,7 @@ def test_gemv_large_and_tiny_activations():
     x = np.concatenate([big, tiny])
     Wp = tl.tl_pack_2bit(W)
     y = run_gemm(x, Wp, g, N, K, tl.TL_PATH_GEMV)
-    assert_close(y, oracle.gemm(x, W, g), "range")
+    assert_close(y, oracle.gemm(x, W, g), x, g, "range")
 
 
 def test_gemv_is_deterministic_and_odd_symmetric():
@@ -156,4 +156,4 @@ def test_auto_path_full_size_sampled_columns():
     y = run_gemm(x, Wp, g, N, K)
     cols = np.sort(np.random.default_rng(0).choice(N, 512, replace=False))
     ref = oracle.gemm(x, np.ascontiguousarray(W[cols]), g)
-    assert_close(y[:, cols], ref, "full size sampled")
+    assert_close(y[:, cols], ref, x, g, "full size sampled")
