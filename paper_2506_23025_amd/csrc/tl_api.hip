@@ -31,7 +31,7 @@ inline bool dims_ok(int64_t M, int64_t N, int64_t K)
 inline tl_status from_hip(hipError_t e) { return e == hipSuccess ? TL_OK : TL_ERR_HIP; }
 
 // M at and below which the weight-streaming kernel is used when both fast kernels fit.
-constexpr int64_t kGemvMaxM = 64;
+constexpr int64_t kGemvMaxM = 128;
 
 }  // namespace
 }  // namespace tl

@@ -157,3 +157,55 @@ def test_auto_path_full_size_sampled_columns():
     cols = np.sort(np.random.default_rng(0).choice(N, 512, replace=False))
     ref = oracle.gemm(x, np.ascontiguousarray(W[cols]), g)
     assert_close(y[:, cols], ref, x, g, "full size sampled")
+
+
+# ---------------------------------------------------------------- MFMA prefill kernel
+
+MFMA_SHAPES = [
+    (256, 256, 64), (1, 16, 64), (300, 200, 128), (128, 128, 4096), (512, 384, 1024),
+    (257, 130, 192), (64, 1000, 2048), (1024, 512, 512), (31, 257, 11008),
+]
+
+
+@pytest.mark.parametrize("M,N,K", MFMA_SHAPES)
+def test_mfma_matches_oracle(M, N, K):
+    x, W, g = si.layer(5000 + M + N + K, M, N, K)
+    Wp = tl.tl_pack_2bit(W)
+    y = run_gemm(x, Wp, g, N, K, tl.TL_PATH_MFMA)
+    assert_close(y, oracle.gemm_packed2(x, Wp, g, K), x, g, f"mfma {M}x{N}x{K}")
+
+
+def test_mfma_exact_cases():
+    # identity / zero weights: every output is a single product (or nothing), so fp16(gamma x) exactly
+    K = N = 256
+    rng = np.random.default_rng(21)
+    x = si.activations(rng, 40, K)
+    g = np.float16(0.02)
+    eye = np.eye(K, dtype=np.int8)
+    y = run_gemm(x, tl.tl_pack_2bit(eye), g, N, K, tl.TL_PATH_MFMA)
+    assert np.array_equal(y, oracle.to_fp16(oracle.gemm(x, eye, g)))
+    y = run_gemm(x, tl.tl_pack_2bit(-eye), g, N, K, tl.TL_PATH_MFMA)
+    assert np.array_equal(y, oracle.to_fp16(oracle.gemm(x, -eye, g)))
+    y0 = run_gemm(x, tl.tl_pack_2bit(np.zeros((N, K), np.int8)), g, N, K, tl.TL_PATH_MFMA)
+    assert not (y0.view(np.uint16) & 0x7FFF).any()
+
+
+@pytest.mark.parametrize("M", [256, 2048])
+def test_prefill_full_size_sampled(M):
+    # 4096 -> 14336 through tl_ternary_gemm (picks the MFMA kernel); 256 sampled columns
+    N, K = 14336, 4096
+    x, W, g = si.layer(si.SEEDS["c4"] + M, M, N, K)
+    Wp = tl.tl_pack_2bit(W)
+    y = run_gemm(x, Wp, g, N, K)
+    cols = np.sort(np.random.default_rng(1).choice(N, 256, replace=False))
+    ref = oracle.gemm(x, np.ascontiguousarray(W[cols]), g)
+    assert_close(y[:, cols], ref, x, g, f"prefill full size M={M}")
+    # y(-W) = -y: the matrix core's internal alignment is not exactly sign-symmetric, so a
+    # few outputs may land on the neighbouring fp16 value; nothing may be further off
+    y2 = run_gemm(x, tl.tl_pack_2bit(-W), g, N, K)
+    assert_close(-y2[:, cols], ref, x, g, f"prefill full size, negated W, M={M}")
+    a = y.view(np.int16).astype(np.int32)
+    b = (y2.view(np.uint16) ^ 0x8000).view(np.int16).astype(np.int32)
+    differs = a != b
+    assert np.abs(a - b)[differs & (y != 0)].max(initial=0) <= 1
+    assert differs.mean() < 1e-3
