@@ -37,6 +37,9 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--mode", choices=("sweep", "dominant", "copy"), default="sweep",
+                    help="sweep: the benchmark; dominant / copy: run only the dominant kernel, or only "
+                         "the plain copy probe, `steps` times (for rocprofv3 counter collection)")
     ap.add_argument("--eager", action="store_true",
                     help="launch every call from the host instead of replaying a captured HIP graph")
     args = ap.parse_args()
@@ -55,6 +58,21 @@ def main():
     dev = torch.device("cuda:0")
     L = tl.raw()
     stream = torch.cuda.current_stream().cuda_stream
+
+    if args.mode == "copy":
+        # calibration for the HBM counters: a plain copy of known size (256 MiB read + written)
+        nbytes = 256 << 20
+        src = torch.full((nbytes,), 3, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(args.steps):
+            st = L.tl_probe_copy(dst.data_ptr(), src.data_ptr(), nbytes, stream)
+            if st != tl.TL_OK:
+                raise tl.TlError(st, "tl_probe_copy")
+        torch.cuda.synchronize()
+        print(json.dumps({"mode": "copy", "launches": args.steps, "bytes_read_per_launch": nbytes,
+                          "bytes_written_per_launch": nbytes}))
+        return
 
     # ---------------- synthetic workload (seeded), resident in HBM -------------------------
     rng = np.random.default_rng(si.SEEDS["c2"])
@@ -93,6 +111,14 @@ def main():
     def step():
         for name, M in calls:
             launch(name, M)
+
+    if args.mode == "dominant":
+        for _ in range(args.steps):
+            launch("mlp_up_8b", 16)
+        torch.cuda.synchronize()
+        print(json.dumps({"mode": "dominant", "launches": args.steps, "layer": "mlp_up_8b", "M": 16,
+                          "algorithmic_bytes_per_launch": algorithmic_bytes(16, layers["mlp_up_8b"]["N"], K)}))
+        return
 
     # ---------------- timed region: exactly `steps` steps ---------------------------------
     # The launches are captured once into a HIP graph (as a serving loop would do for a decode
@@ -149,10 +175,11 @@ def main():
     dom = next(c for c in per_call if c["layer"] == "mlp_up_8b" and c["M"] == 16)
     dom_bytes = algorithmic_bytes(16, dom["N"], K)
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.txt")     # figure from the rocprofv3 --pmc runs
     if os.path.exists(tpath):
-        with open(tpath) as f:
-            traffic = json.load(f).get("gemv_4096x14336_M16_bytes_per_launch")
+        for line in open(tpath):
+            if line.startswith("gemv_4096x14336_M16_bytes_per_launch"):
+                traffic = float(line.split("=")[1])
     roofline = dict(bound="hbm", kernel="gemv_kernel (small-M, 4096->14336, M=16)",
                     achieved=round(dom_bytes / dom["us"] / 1e3, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(dom_bytes / dom["us"] / 1e3 / HBM_PEAK_GBS, 4),
