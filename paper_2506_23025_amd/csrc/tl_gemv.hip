@@ -64,6 +64,17 @@ __device__ __forceinline__ f16x8 as_f16x8(u32x4 v)
 
 // T  tiles per workgroup (tile t of group b is b + t * groups; only the last can be missing)
 // MR activation rows staged per 16-row block (power of two >= Mrem; surplus rows repeat)
+#ifdef TL_GEMV_TRACE
+__device__ unsigned long long* g_trace;   // [group][wave][16] time stamps, development builds only
+#define TL_STAMP(i) do { tl_stamp[i] = __builtin_amdgcn_s_memtime(); } while (0)
+#define TL_STAMP_DECL unsigned long long tl_stamp[16] = {}
+#define TL_STAMP_FLUSH do { if (lane == 0) for (int i_ = 0; i_ < 16; ++i_) g_trace[(size_t(blockIdx.x) * 8 + wave) * 16 + i_] = tl_stamp[i_]; } while (0)
+#else
+#define TL_STAMP(i) do { } while (0)
+#define TL_STAMP_DECL do { } while (0)
+#define TL_STAMP_FLUSH do { } while (0)
+#endif
+
 template <int T, int MR>
 __global__ void __launch_bounds__(512)
 gemv_kernel(GemvParams p)
@@ -74,6 +85,8 @@ gemv_kernel(GemvParams p)
     const int NW = blockDim.x >> 6;
     unsigned char* const my_lds = lds_raw + wave * kWaveLds;
 
+    TL_STAMP_DECL;
+    TL_STAMP(0);
     const int m0 = blockIdx.y * 16;
     const int Mrem = (p.M - m0 < 16) ? (p.M - m0) : 16;
     const int K = p.K;
@@ -99,15 +112,20 @@ gemv_kernel(GemvParams p)
     const bool last_valid = (blockIdx.x + (T - 1) * p.groups) < p.tiles;
 
     u32x4 wreg[T][2];
+    const bool ragged_n = (p.N & 15) != 0;
     auto issue_w = [&](int t, int slice) {
         int tile = blockIdx.x + t * p.groups;
         if (tile >= p.tiles) tile = p.tiles - 1;          // loaded twice, never used
         int chunk = slice * 8 + lc;
         if (chunk >= chunks) chunk = 0;                    // multiplied by zero activations
         const unsigned char* tb = Wb + size_t(tile) * 16u * row_bytes;
-        const int last = p.N - 1 - tile * 16;              // rows past N read row N-1
-        const uint32_t off0 = uint32_t(lr < last ? lr : last) * row_bytes + uint32_t(chunk) * 16u;
-        const uint32_t off1 = uint32_t(lr + 8 < last ? lr + 8 : last) * row_bytes + uint32_t(chunk) * 16u;
+        uint32_t off0 = uint32_t(lr) * row_bytes + uint32_t(chunk) * 16u;
+        uint32_t off1 = off0 + 8u * row_bytes;
+        if (ragged_n && tile == p.tiles - 1) {             // scalar branch: rows past N read row N-1
+            const int last = p.N - 1 - tile * 16;
+            off0 = uint32_t(lr < last ? lr : last) * row_bytes + uint32_t(chunk) * 16u;
+            off1 = uint32_t(lr + 8 < last ? lr + 8 : last) * row_bytes + uint32_t(chunk) * 16u;
+        }
         wreg[t][0] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tb + off0));
         wreg[t][1] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tb + off1));
     };
@@ -144,9 +162,11 @@ gemv_kernel(GemvParams p)
         issue_x(slice);
 #pragma unroll
         for (int t = 0; t < T; ++t) issue_w(t, slice);
+        TL_STAMP(1);
         // The compiler does not track LDS-DMA: wait by hand until only the 2T weight loads
         // issued after the activation rows are outstanding (loads of a wave return in order).
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * T));
+        TL_STAMP(2);
     }
 
     for (int pass = 0; pass < p.passes; ++pass, slice += NW) {
@@ -188,6 +208,7 @@ gemv_kernel(GemvParams p)
                 }
         }
 
+        TL_STAMP(3);
         // ---------------- per tile: turn through LDS, decode, MFMA -----------------------
         // Tile t lives at my_lds + 16 KB-free area?  No: the staging rows are dead once breg is
         // built, so region t (2 KB) reuses them; LDS operations of one wave execute in order.
@@ -217,6 +238,7 @@ gemv_kernel(GemvParams p)
             }
             // fp16 bits c << (2j + 4) are the subnormal c 4^(j+2) 2^-24: undo with 2^(20 - 2j)
             part[t] += acc[0] * 1048576.f + acc[1] * 262144.f + acc[2] * 65536.f;
+            TL_STAMP(4 + t);
         }
         // The staging rows share LDS with the tile regions, so the next slice's activations
         // can only be fetched once the last tile has been read.
@@ -228,7 +250,9 @@ gemv_kernel(GemvParams p)
 
     // ---- split-K reduction across the waves, epilogue -----------------------------------
     // Layout [t][wave][lane] of f32x4 in LDS (reuses the staging space after a barrier).
+    TL_STAMP(12);
     __syncthreads();
+    TL_STAMP(13);
     f32x4* red = reinterpret_cast<f32x4*>(lds_raw);
 #pragma unroll
     for (int t = 0; t < T; ++t) red[(t * NW + wave) * 64 + lane] = part[t];
@@ -238,17 +262,28 @@ gemv_kernel(GemvParams p)
         const int l = item & 63;
         const int tile = blockIdx.x + t * p.groups;
         if (tile >= p.tiles) continue;
-        f32x4 s = red[(t * NW) * 64 + l];
-        for (int w = 1; w < NW; ++w) s += red[(t * NW + w) * 64 + l];
+        f32x4 v[8];
+#pragma unroll
+        for (int w = 0; w < 8; ++w)                         // all reads in flight, then a fixed-order sum
+            v[w] = (w < NW) ? red[(t * NW + w) * 64 + l] : f32x4{0.f, 0.f, 0.f, 0.f};
+        const f32x4 s = ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
         const int m = m0 + (l & 15);
         const int n = tile * 16 + 4 * (l >> 4);
         if ((l & 15) < Mrem) {
             __half* dst = p.y + size_t(m) * p.N + n;
+            if (n + 3 < p.N && (p.N & 3) == 0) {            // four consecutive n: one 8-byte store
+                const f16x2 lo = {(_Float16)(p.gamma * s[0]), (_Float16)(p.gamma * s[1])};
+                const f16x2 hi = {(_Float16)(p.gamma * s[2]), (_Float16)(p.gamma * s[3])};
+                *reinterpret_cast<u32x2*>(dst) = u32x2{__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
+            } else {
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-                if (n + r < p.N) dst[r] = __float2half_rn(p.gamma * s[r]);
+                for (int r = 0; r < 4; ++r)
+                    if (n + r < p.N) dst[r] = __float2half_rn(p.gamma * s[r]);
+            }
         }
     }
+    TL_STAMP(14);
+    TL_STAMP_FLUSH;
 }
 
 using KernelFn = void (*)(GemvParams);
