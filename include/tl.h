@@ -138,6 +138,24 @@ tl_status tl_ternary_gemm_path(const void* x, const void* Wpacked, uint16_t gamm
                                void* y, int64_t M, int64_t N, int64_t K, void* stream,
                                tl_path path);
 
+/*
+ * Several independent products in one call: the linears of a transformer block (the unit
+ * the paper's kernel benchmark is quoted on, App. G "performance benchmark"), or any list
+ * of (x, W, gamma, y).  Each job has the contract of tl_ternary_gemm.  Jobs must not alias
+ * each other's outputs; they are enqueued in as few kernel launches as possible (jobs with
+ * M <= 128 and K % 64 == 0 share launches, 16 blocks of 16 activation rows per launch) and
+ * may run concurrently.  `jobs` is host memory, read before the call returns.
+ */
+typedef struct tl_gemm_job {
+    const void* x;            /* device, fp16 [M][K]                */
+    const void* Wpacked;      /* device, TL_FMT_2BIT                */
+    void* y;                  /* device, fp16 [M][N]                */
+    int64_t M, N, K;
+    uint16_t gamma_fp16_bits;
+} tl_gemm_job;
+
+tl_status tl_ternary_gemm_grouped(const tl_gemm_job* jobs, int64_t count, void* stream);
+
 /* Same contract for weights in the TL_FMT_1P6BIT layout of tl_pack_1p6bit. */
 tl_status tl_ternary_gemm_1p6(const void* x, const void* Wpacked, uint16_t gamma_fp16_bits,
                               void* y, int64_t M, int64_t N, int64_t K, void* stream);

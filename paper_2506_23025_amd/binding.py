@@ -21,8 +21,15 @@ TL_PATH_AUTO, TL_PATH_GENERIC, TL_PATH_GEMV, TL_PATH_MFMA = 0, 1, 2, 3
 EXPORTS = (
     "tl_status_str", "tl_row_stride_bytes", "tl_packed_bytes", "tl_pack_2bit", "tl_pack_1p6bit",
     "tl_pack_1p6bit_fx", "tl_unpack_1p6bit_fx", "tl_unpack", "tl_unpack_dev", "tl_ternary_gemm",
-    "tl_ternary_gemm_path", "tl_ternary_gemm_1p6", "tl_probe_copy",
+    "tl_ternary_gemm_path", "tl_ternary_gemm_grouped", "tl_ternary_gemm_1p6", "tl_probe_copy",
 )
+
+
+class tl_gemm_job(ctypes.Structure):
+    """Mirror of struct tl_gemm_job in include/tl.h."""
+    _fields_ = [("x", ctypes.c_void_p), ("Wpacked", ctypes.c_void_p), ("y", ctypes.c_void_p),
+                ("M", ctypes.c_int64), ("N", ctypes.c_int64), ("K", ctypes.c_int64),
+                ("gamma_fp16_bits", ctypes.c_uint16)]
 
 
 class TlError(RuntimeError):
@@ -63,6 +70,8 @@ def _load():
     L.tl_ternary_gemm.restype = ci
     L.tl_ternary_gemm_path.argtypes = [vp, vp, u16, vp, i64, i64, i64, vp, ci]
     L.tl_ternary_gemm_path.restype = ci
+    L.tl_ternary_gemm_grouped.argtypes = [ctypes.POINTER(tl_gemm_job), i64, vp]
+    L.tl_ternary_gemm_grouped.restype = ci
     L.tl_ternary_gemm_1p6.argtypes = [vp, vp, u16, vp, i64, i64, i64, vp]
     L.tl_ternary_gemm_1p6.restype = ci
     L.tl_probe_copy.argtypes = [vp, vp, sz, vp]
@@ -178,6 +187,21 @@ def tl_ternary_gemm(x, Wpacked, gamma_fp16_bits, y, M, N, K, stream=None):
 def tl_ternary_gemm_path(x, Wpacked, gamma_fp16_bits, y, M, N, K, stream=None, path=TL_PATH_AUTO):
     _check(_lib.tl_ternary_gemm_path(_ptr(x), _ptr(Wpacked), gamma_fp16_bits, _ptr(y), M, N, K,
                                      _stream(stream), path), "tl_ternary_gemm_path")
+
+
+def make_jobs(jobs):
+    """[(x, Wpacked, gamma_fp16_bits, y, M, N, K), ...] -> ctypes array of tl_gemm_job."""
+    arr = (tl_gemm_job * len(jobs))()
+    for a, (x, Wp, gbits, y, M, N, K) in zip(arr, jobs):
+        a.x, a.Wpacked, a.y = _ptr(x), _ptr(Wp), _ptr(y)
+        a.M, a.N, a.K, a.gamma_fp16_bits = M, N, K, gbits
+    return arr
+
+
+def tl_ternary_gemm_grouped(jobs, stream=None):
+    """jobs: list of (x, Wpacked, gamma_fp16_bits, y, M, N, K), or an array made by make_jobs."""
+    arr = jobs if isinstance(jobs, ctypes.Array) else make_jobs(jobs)
+    _check(_lib.tl_ternary_gemm_grouped(arr, len(arr), _stream(stream)), "tl_ternary_gemm_grouped")
 
 
 def tl_ternary_gemm_1p6(x, Wpacked, gamma_fp16_bits, y, M, N, K, stream=None):

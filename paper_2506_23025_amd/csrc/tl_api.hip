@@ -91,6 +91,44 @@ tl_status tl_ternary_gemm(const void* x, const void* Wpacked, uint16_t gamma_fp1
     return tl_ternary_gemm_path(x, Wpacked, gamma_fp16_bits, y, M, N, K, stream, TL_PATH_AUTO);
 }
 
+tl_status tl_ternary_gemm_grouped(const tl_gemm_job* jobs, int64_t count, void* stream)
+{
+    if (count == 0) return TL_OK;
+    if (!jobs) return TL_ERR_NULL;
+    if (count < 0 || count > 4096) return TL_ERR_SHAPE;
+    for (int64_t i = 0; i < count; ++i) {
+        const tl_gemm_job& j = jobs[i];
+        if (!j.x || !j.Wpacked || !j.y) return TL_ERR_NULL;
+        if (!tl::dims_ok(j.M, j.N, j.K)) return TL_ERR_SHAPE;
+        if (!tl::aligned16(j.x) || !tl::aligned16(j.Wpacked) || !tl::aligned16(j.y)) return TL_ERR_ALIGN;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // Jobs the small-M kernel takes are fused; the others go through tl_ternary_gemm one by one.
+    tl::GemmDesc fused[64];
+    int nf = 0;
+    auto flush = [&]() -> tl_status {
+        if (nf == 0) return TL_OK;
+        const hipError_t e = tl::launch_gemv_jobs(fused, nf, s);
+        nf = 0;
+        return tl::from_hip(e);
+    };
+    for (int64_t i = 0; i < count; ++i) {
+        const tl_gemm_job& j = jobs[i];
+        if (j.M <= tl::kGemvMaxM && tl::gemv_supports(j.M, j.N, j.K)) {
+            fused[nf++] = tl::GemmDesc{static_cast<const __half*>(j.x), static_cast<const uint32_t*>(j.Wpacked),
+                                       static_cast<__half*>(j.y), tl::half_bits_to_float(j.gamma_fp16_bits),
+                                       j.M, j.N, j.K};
+            if (nf == 64) { const tl_status st = flush(); if (st != TL_OK) return st; }
+        } else {
+            tl_status st = flush();
+            if (st != TL_OK) return st;
+            st = tl_ternary_gemm(j.x, j.Wpacked, j.gamma_fp16_bits, j.y, j.M, j.N, j.K, stream);
+            if (st != TL_OK) return st;
+        }
+    }
+    return flush();
+}
+
 tl_status tl_ternary_gemm_1p6(const void* x, const void* Wpacked, uint16_t gamma_fp16_bits, void* y,
                               int64_t M, int64_t N, int64_t K, void* stream)
 {

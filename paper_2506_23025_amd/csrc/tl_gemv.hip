@@ -26,6 +26,9 @@
 //    group of MFMAs per wave whose 16-row operand is a constant, and seeds the accumulator.
 //  * Split-K partial tiles of the NW waves are added in a fixed order through LDS, scaled
 //    by gamma, rounded to fp16 (RNE) and stored.  No atomics: results are deterministic.
+//  * One launch can carry up to 16 independent jobs (a job = one matrix and at most 16
+//    activation rows); a workgroup finds its job from its index.  Grouped launches use
+//    4-wave groups, two per CU, so that one group's wait for HBM overlaps the other's MFMAs.
 #include "tl_internal.hpp"
 
 namespace tl {
@@ -35,20 +38,28 @@ namespace {
 constexpr int kTMax = 4;          // tiles a workgroup keeps in flight
 constexpr int kSliceK = 512;      // K elements a wave owns per pass
 constexpr int kWaveLds = 16384;   // bytes of LDS per wave: 16 activation rows x 1 KB
+constexpr int kMaxJobs = 16;      // jobs per launch
 
-struct GemvParams {
-    const __half* x;
+struct GemvJob {                  // 64 bytes, lives in the kernel argument segment
+    const __half* x;              // first activation row of this 16-row block
     const uint32_t* W;
-    __half* y;
+    __half* y;                    // first output row of this block
     float gamma;
-    int M, N, K;
-    int tiles;      // ceil(N / 16)
-    int groups;     // gridDim.x
-    int T;          // tiles per workgroup (<= kTMax)
-    int slices;     // ceil(K / 512)
-    int passes;     // ceil(slices / NW)
+    int Mrem;                     // 1..16 activation rows
+    int N, K;
+    int tiles;                    // ceil(N / 16)
+    int groups;                   // workgroups that share this job
+    int group0;                   // index of the job's first workgroup in the launch
+    int slices;                   // ceil(K / 512)
+    int mr;                       // staged rows: power of two >= Mrem (surplus rows repeat)
+    int pad;
 };
 
+struct GemvBatch {
+    int count;
+    int pad[3];
+    GemvJob job[kMaxJobs];
+};
 
 // s_waitcnt immediate for "vmcnt <= n" only (gfx9 layout: vmcnt in bits 3:0 and 15:14,
 // expcnt 6:4 and lgkmcnt 11:8 left at their maxima, i.e. not waited for).
@@ -62,8 +73,6 @@ __device__ __forceinline__ f16x8 as_f16x8(u32x4 v)
     return __builtin_bit_cast(f16x8, v);
 }
 
-// T  tiles per workgroup (tile t of group b is b + t * groups; only the last can be missing)
-// MR activation rows staged per 16-row block (power of two >= Mrem; surplus rows repeat)
 #ifdef TL_GEMV_TRACE
 __device__ unsigned long long* g_trace;   // [group][wave][16] time stamps, development builds only
 #define TL_STAMP(i) do { tl_stamp[i] = __builtin_amdgcn_s_memtime(); } while (0)
@@ -75,21 +84,26 @@ __device__ unsigned long long* g_trace;   // [group][wave][16] time stamps, deve
 #define TL_STAMP_FLUSH do { } while (0)
 #endif
 
-template <int T, int MR>
+// T: tiles per workgroup; tile t of group g (within its job) is g + t * groups.
+template <int T>
 __global__ void __launch_bounds__(512)
-gemv_kernel(GemvParams p)
+gemv_kernel(GemvBatch b)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int NW = blockDim.x >> 6;
     unsigned char* const my_lds = lds_raw + wave * kWaveLds;
-
     TL_STAMP_DECL;
     TL_STAMP(0);
-    const int m0 = blockIdx.y * 16;
-    const int Mrem = (p.M - m0 < 16) ? (p.M - m0) : 16;
-    const int K = p.K;
+
+    int ji = 0;
+    while (ji + 1 < b.count && int(blockIdx.x) >= b.job[ji + 1].group0) ++ji;
+    const GemvJob& J = b.job[ji];
+    const int grp = int(blockIdx.x) - J.group0;
+    const int groups = J.groups, tiles = J.tiles, slices = J.slices;
+    const int Mrem = J.Mrem, MR = J.mr;
+    const int K = J.K, N = J.N;
     const uint32_t row_bytes = uint32_t(K) >> 2;
     const int chunks = K >> 6;                 // 64-weight (16-byte) chunks per row
 
@@ -107,22 +121,21 @@ gemv_kernel(GemvParams p)
     const uint32_t wr_off0 = uint32_t(mi) * 128u + (uint32_t((mg) ^ (mi & 7)) << 4);
     const uint32_t wr_off1 = uint32_t(mi) * 128u + (uint32_t((4 + mg) ^ (mi & 7)) << 4);
 
-    const unsigned char* const Wb = reinterpret_cast<const unsigned char*>(p.W);
-    const unsigned char* const xb = reinterpret_cast<const unsigned char*>(p.x + size_t(m0) * K);
-    const bool last_valid = (blockIdx.x + (T - 1) * p.groups) < p.tiles;
+    const unsigned char* const Wb = reinterpret_cast<const unsigned char*>(J.W);
+    const unsigned char* const xb = reinterpret_cast<const unsigned char*>(J.x);
 
     u32x4 wreg[T][2];
-    const bool ragged_n = (p.N & 15) != 0;
+    const bool ragged_n = (N & 15) != 0;
     auto issue_w = [&](int t, int slice) {
-        int tile = blockIdx.x + t * p.groups;
-        if (tile >= p.tiles) tile = p.tiles - 1;          // loaded twice, never used
+        int tile = grp + t * groups;
+        if (tile >= tiles) tile = tiles - 1;               // loaded again, never used
         int chunk = slice * 8 + lc;
         if (chunk >= chunks) chunk = 0;                    // multiplied by zero activations
         const unsigned char* tb = Wb + size_t(tile) * 16u * row_bytes;
         uint32_t off0 = uint32_t(lr) * row_bytes + uint32_t(chunk) * 16u;
         uint32_t off1 = off0 + 8u * row_bytes;
-        if (ragged_n && tile == p.tiles - 1) {             // scalar branch: rows past N read row N-1
-            const int last = p.N - 1 - tile * 16;
+        if (ragged_n && tile == tiles - 1) {               // scalar branch: rows past N read row N-1
+            const int last = N - 1 - tile * 16;
             off0 = uint32_t(lr < last ? lr : last) * row_bytes + uint32_t(chunk) * 16u;
             off1 = uint32_t(lr + 8 < last ? lr + 8 : last) * row_bytes + uint32_t(chunk) * 16u;
         }
@@ -136,7 +149,6 @@ gemv_kernel(GemvParams p)
     // layout the operand set-up reads.  Rows past Mrem repeat row Mrem-1; lanes past K
     // store zeros instead (their weights are whatever chunk 0 holds).
     auto issue_x = [&](int slice) {
-#pragma unroll
         for (int r = 0; r < MR; ++r) {
             const int rr = r < Mrem ? r : Mrem - 1;
             const int kx = slice * kSliceK + ((lane ^ (r & 7)) << 3);
@@ -158,7 +170,7 @@ gemv_kernel(GemvParams p)
     // Activations go first: they are short L2 hits, and the loads of one wave return in
     // order, so the weight stream queued behind them overlaps the operand set-up below.
     int slice = wave;
-    if (slice < p.slices) {
+    if (slice < slices) {
         issue_x(slice);
 #pragma unroll
         for (int t = 0; t < T; ++t) issue_w(t, slice);
@@ -169,9 +181,8 @@ gemv_kernel(GemvParams p)
         TL_STAMP(2);
     }
 
-    for (int pass = 0; pass < p.passes; ++pass, slice += NW) {
-        if (slice >= p.slices) break;                      // wave-uniform
-        const bool more = (slice + NW) < p.slices;
+    for (; slice < slices; slice += NW) {                  // wave-uniform trip count
+        const bool more = (slice + NW) < slices;
         // ---------------- activations of this slice -> MFMA B registers ----------------
         // staging layout: row r, 16-byte piece P at slot P ^ (r & 7)
         // breg[h][wd][e]: (x[k], x[k + 8]) with k = slice0 + 64 (4h + g) + 16 wd + e
@@ -203,41 +214,41 @@ gemv_kernel(GemvParams p)
             for (int h = 0; h < 2; ++h)
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    const u32x4 b = u32x4{breg[h][0][e], breg[h][1][e], breg[h][2][e], breg[h][3][e]};
-                    nsx = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), as_f16x8(b), nsx, 0, 0, 0);
+                    const u32x4 bb = u32x4{breg[h][0][e], breg[h][1][e], breg[h][2][e], breg[h][3][e]};
+                    nsx = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), as_f16x8(bb), nsx, 0, 0, 0);
                 }
         }
-
         TL_STAMP(3);
         // ---------------- per tile: turn through LDS, decode, MFMA -----------------------
-        // Tile t lives at my_lds + 16 KB-free area?  No: the staging rows are dead once breg is
-        // built, so region t (2 KB) reuses them; LDS operations of one wave execute in order.
+        // The staging rows are dead once breg is built, so region t (2 KB) reuses them; LDS
+        // operations of one wave execute in order.
 #pragma unroll
         for (int t = 0; t < T; ++t) {
-            if (t == T - 1 && !last_valid) break;          // scalar branch, last tile only
             unsigned char* const reg_t = my_lds + t * 2048;
             *reinterpret_cast<u32x4*>(reg_t + ww_off) = wreg[t][0];
             *reinterpret_cast<u32x4*>(reg_t + 1024 + ww_off) = wreg[t][1];
             if (more) issue_w(t, slice + NW);              // refill for the next pass
-            // acc[0] starts from -2^-20 sum x: with the 2^20 below it carries the "-1" of c = w + 1
-            f32x4 acc[3] = {nsx, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+            if (grp + t * groups < tiles) {                // scalar: tiles past the end are skipped
+                // acc[0] starts from -2^-20 sum x: with the 2^20 below it carries the "-1" of c = w + 1
+                f32x4 acc[3] = {nsx, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const u32x4 wv = *reinterpret_cast<const u32x4*>(reg_t + (h ? wr_off1 : wr_off0));
-                // element e of each half-word is moved to mantissa bits 4..9 (position
-                // class 2, 3 or 4): e = 0..2 by << 4, e = 3..5 by >> 2, e = 6..7 by >> 8
-                const u32x4 sh[3] = {wv << 4, wv >> 2, wv >> 8};
+                for (int h = 0; h < 2; ++h) {
+                    const u32x4 wv = *reinterpret_cast<const u32x4*>(reg_t + (h ? wr_off1 : wr_off0));
+                    // element e of each half-word is moved to mantissa bits 4..9 (position
+                    // class 2, 3 or 4): e = 0..2 by << 4, e = 3..5 by >> 2, e = 6..7 by >> 8
+                    const u32x4 sh[3] = {wv << 4, wv >> 2, wv >> 8};
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int j = e % 3;                        // accumulator: class j + 2
-                    const uint32_t mask = 0x00300030u << (2 * j);
-                    const u32x4 a = sh[e / 3] & mask;
-                    const u32x4 b = u32x4{breg[h][0][e], breg[h][1][e], breg[h][2][e], breg[h][3][e]};
-                    acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), as_f16x8(b), acc[j], 0, 0, 0);
+                    for (int e = 0; e < 8; ++e) {
+                        const int j = e % 3;                        // accumulator: class j + 2
+                        const uint32_t mask = 0x00300030u << (2 * j);
+                        const u32x4 a = sh[e / 3] & mask;
+                        const u32x4 bb = u32x4{breg[h][0][e], breg[h][1][e], breg[h][2][e], breg[h][3][e]};
+                        acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), as_f16x8(bb), acc[j], 0, 0, 0);
+                    }
                 }
+                // fp16 bits c << (2j + 4) are the subnormal c 4^(j+2) 2^-24: undo with 2^(20 - 2j)
+                part[t] += acc[0] * 1048576.f + acc[1] * 262144.f + acc[2] * 65536.f;
             }
-            // fp16 bits c << (2j + 4) are the subnormal c 4^(j+2) 2^-24: undo with 2^(20 - 2j)
-            part[t] += acc[0] * 1048576.f + acc[1] * 262144.f + acc[2] * 65536.f;
             TL_STAMP(4 + t);
         }
         // The staging rows share LDS with the tile regions, so the next slice's activations
@@ -257,28 +268,28 @@ gemv_kernel(GemvParams p)
 #pragma unroll
     for (int t = 0; t < T; ++t) red[(t * NW + wave) * 64 + lane] = part[t];
     __syncthreads();
+    const float gamma = J.gamma;
     for (int item = threadIdx.x; item < T * 64; item += blockDim.x) {
         const int t = item >> 6;
         const int l = item & 63;
-        const int tile = blockIdx.x + t * p.groups;
-        if (tile >= p.tiles) continue;
+        const int tile = grp + t * groups;
+        if (tile >= tiles) continue;
         f32x4 v[8];
 #pragma unroll
         for (int w = 0; w < 8; ++w)                         // all reads in flight, then a fixed-order sum
             v[w] = (w < NW) ? red[(t * NW + w) * 64 + l] : f32x4{0.f, 0.f, 0.f, 0.f};
         const f32x4 s = ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
-        const int m = m0 + (l & 15);
         const int n = tile * 16 + 4 * (l >> 4);
         if ((l & 15) < Mrem) {
-            __half* dst = p.y + size_t(m) * p.N + n;
-            if (n + 3 < p.N && (p.N & 3) == 0) {            // four consecutive n: one 8-byte store
-                const f16x2 lo = {(_Float16)(p.gamma * s[0]), (_Float16)(p.gamma * s[1])};
-                const f16x2 hi = {(_Float16)(p.gamma * s[2]), (_Float16)(p.gamma * s[3])};
+            __half* dst = J.y + size_t(l & 15) * N + n;
+            if (n + 3 < N && (N & 3) == 0) {                // four consecutive n: one 8-byte store
+                const f16x2 lo = {(_Float16)(gamma * s[0]), (_Float16)(gamma * s[1])};
+                const f16x2 hi = {(_Float16)(gamma * s[2]), (_Float16)(gamma * s[3])};
                 *reinterpret_cast<u32x2*>(dst) = u32x2{__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
             } else {
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
-                    if (n + r < p.N) dst[r] = __float2half_rn(p.gamma * s[r]);
+                    if (n + r < N) dst[r] = __float2half_rn(gamma * s[r]);
             }
         }
     }
@@ -286,36 +297,40 @@ gemv_kernel(GemvParams p)
     TL_STAMP_FLUSH;
 }
 
-using KernelFn = void (*)(GemvParams);
+using KernelFn = void (*)(GemvBatch);
 
-template <int T>
-KernelFn pick_mr(int mr)
-{
-    switch (mr) {
-        case 1: return gemv_kernel<T, 1>;
-        case 2: return gemv_kernel<T, 2>;
-        case 4: return gemv_kernel<T, 4>;
-        case 8: return gemv_kernel<T, 8>;
-        default: return gemv_kernel<T, 16>;
-    }
-}
-
-// Smallest instantiated T that is >= t (t <= kTMax).
-int round_tiles(int t)
-{
-    static const int have[] = {1, 2, 3, 4};
-    for (int v : have) if (v >= t) return v;
-    return kTMax;
-}
-
-KernelFn pick_kernel(int T, int mr)
+KernelFn pick_kernel(int T)
 {
     switch (T) {
-        case 1: return pick_mr<1>(mr);
-        case 2: return pick_mr<2>(mr);
-        case 3: return pick_mr<3>(mr);
-        default: return pick_mr<4>(mr);
+        case 1: return gemv_kernel<1>;
+        case 2: return gemv_kernel<2>;
+        case 3: return gemv_kernel<3>;
+        default: return gemv_kernel<4>;
     }
+}
+
+int pow2_at_least(int v)
+{
+    int r = 1;
+    while (r < v) r *= 2;
+    return r;
+}
+
+// Launch one batch (<= kMaxJobs jobs with group0 / groups filled in).
+hipError_t launch_batch(GemvBatch& b, int T, int NW, int total_groups, hipStream_t s)
+{
+    KernelFn fn = pick_kernel(T);
+    // Groups of 5 or more waves need more than the default 64 KB of dynamic LDS; the
+    // attribute is set once per kernel instance (idempotent, so a race only repeats it).
+    static bool lds_raised[kTMax + 1];
+    if (!lds_raised[T]) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 8 * kWaveLds);
+        if (e != hipSuccess) return e;
+        lds_raised[T] = true;
+    }
+    hipLaunchKernelGGL(fn, dim3(total_groups), dim3(NW * 64), size_t(NW) * kWaveLds, s, b);
+    return hipGetLastError();
 }
 
 }  // namespace
@@ -323,44 +338,68 @@ KernelFn pick_kernel(int T, int mr)
 bool gemv_supports(int64_t M, int64_t N, int64_t K)
 {
     return M >= 1 && N >= 1 && K >= 64 && (K % 64) == 0 && K <= (int64_t(1) << 24) &&
-           N <= (int64_t(1) << 24) && (M + 15) / 16 <= 65535;
+           N <= (int64_t(1) << 24) && M <= (int64_t(1) << 20);
+}
+
+hipError_t launch_gemv_jobs(const GemmDesc* jobs, int count, hipStream_t s)
+{
+    // A user job with M > 16 becomes ceil(M / 16) kernel jobs (blocks of 16 activation rows).
+    // One job alone gets 8-wave groups, one per CU, each holding up to 4 tiles; several jobs
+    // in one launch get 4-wave groups with 2 tiles, two groups per CU.
+    int64_t blocks_total = 0;
+    for (int i = 0; i < count; ++i) blocks_total += (jobs[i].M + 15) / 16;
+    const bool grouped = blocks_total > 1;
+    const int nw_cap = grouped ? 4 : 8;
+    const int t_cap = grouped ? 2 : kTMax;
+    const int group_cap = grouped ? 512 : 256;
+
+    GemvBatch b;
+    b.count = 0;
+    int total_groups = 0, Tmax = 1, NW = 1;
+    auto flush = [&]() -> hipError_t {
+        if (b.count == 0) return hipSuccess;
+        hipError_t e = launch_batch(b, Tmax, NW, total_groups, s);
+        b.count = 0; total_groups = 0; Tmax = 1; NW = 1;
+        return e;
+    };
+    for (int i = 0; i < count; ++i) {
+        const GemmDesc& d = jobs[i];
+        for (int64_t m0 = 0; m0 < d.M; m0 += 16) {
+            GemvJob j;
+            j.x = d.x + m0 * d.K;
+            j.W = d.W;
+            j.y = d.y + m0 * d.N;
+            j.gamma = d.gamma;
+            j.Mrem = int(d.M - m0 < 16 ? d.M - m0 : 16);
+            j.N = int(d.N); j.K = int(d.K);
+            j.tiles = int((d.N + 15) / 16);
+            j.slices = int((d.K + kSliceK - 1) / kSliceK);
+            j.mr = pow2_at_least(j.Mrem);
+            j.pad = 0;
+            int groups = j.tiles < group_cap ? j.tiles : group_cap;
+            int T = (j.tiles + groups - 1) / groups;
+            if (T > t_cap) { T = t_cap; groups = (j.tiles + T - 1) / T; }
+            j.groups = groups;
+            j.group0 = total_groups;
+            total_groups += groups;
+            if (T > Tmax) Tmax = T;
+            const int nw = j.slices < nw_cap ? j.slices : nw_cap;
+            if (nw > NW) NW = nw;
+            b.job[b.count++] = j;
+            if (b.count == kMaxJobs) {
+                hipError_t e = flush();
+                if (e != hipSuccess) return e;
+            }
+        }
+    }
+    return flush();
 }
 
 hipError_t launch_gemv(const __half* x, const uint32_t* Wp, float gamma, __half* y,
                        int64_t M, int64_t N, int64_t K, hipStream_t s)
 {
-    GemvParams p;
-    p.x = x; p.W = Wp; p.y = y; p.gamma = gamma;
-    p.M = int(M); p.N = int(N); p.K = int(K);
-    p.tiles = int((N + 15) / 16);
-    p.slices = int((K + kSliceK - 1) / kSliceK);
-    const int NW = p.slices < 8 ? p.slices : 8;
-    p.passes = (p.slices + NW - 1) / NW;
-    // One workgroup per CU when there is enough work; a group strides over the tiles.
-    int groups = p.tiles < 256 ? p.tiles : 256;
-    int T = (p.tiles + groups - 1) / groups;
-    if (T > kTMax) { T = kTMax; groups = (p.tiles + T - 1) / T; }
-    T = round_tiles(T);
-    // with the rounded T only the last tile of a group may be missing
-    if (int64_t(T - 1) * groups >= p.tiles) groups = (p.tiles + T - 1) / T;
-    p.groups = groups; p.T = T;
-    int mr = 1;
-    const int mfirst = M < 16 ? int(M) : 16;
-    while (mr < mfirst) mr *= 2;
-    const size_t lds = size_t(NW) * kWaveLds;
-    KernelFn fn = pick_kernel(T, mr);
-    // Groups of 5 or more waves need more than the default 64 KB of dynamic LDS; the
-    // attribute is set once per kernel instance (idempotent, so a race only repeats it).
-    static bool lds_raised[kTMax + 1][17];
-    if (!lds_raised[T][mr]) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 8 * kWaveLds);
-        if (e != hipSuccess) return e;
-        lds_raised[T][mr] = true;
-    }
-    dim3 grid(groups, unsigned((M + 15) / 16));
-    hipLaunchKernelGGL(fn, grid, dim3(NW * 64), lds, s, p);
-    return hipGetLastError();
+    GemmDesc d{x, Wp, y, gamma, M, N, K};
+    return launch_gemv_jobs(&d, 1, s);
 }
 
 }  // namespace tl

@@ -28,10 +28,21 @@ hipError_t launch_gemm_generic(const __half* x, const uint32_t* Wp, float gamma,
 hipError_t launch_gemm3_generic(const __half* x, const uint8_t* Wp, int64_t stride, float gamma,
                                 __half* y, int64_t M, int64_t N, int64_t K, hipStream_t s);
 
+// One GEMM of a grouped call, device pointers, gamma already widened.
+struct GemmDesc {
+    const __half* x;
+    const uint32_t* W;
+    __half* y;
+    float gamma;
+    int64_t M, N, K;
+};
+
 // Weight-streaming small-M kernel (2-bit).  Needs K % 64 == 0; handles M in chunks of 16.
 bool gemv_supports(int64_t M, int64_t N, int64_t K);
 hipError_t launch_gemv(const __half* x, const uint32_t* Wp, float gamma, __half* y,
                        int64_t M, int64_t N, int64_t K, hipStream_t s);
+// Several independent GEMMs (each passing gemv_supports) in as few launches as possible.
+hipError_t launch_gemv_jobs(const GemmDesc* jobs, int count, hipStream_t s);
 
 // LDS-tiled MFMA prefill kernel (2-bit).  Needs K % 64 == 0.
 bool mfma_supports(int64_t M, int64_t N, int64_t K);
