@@ -1,14 +1,16 @@
 """Benchmark of the ternary-linear hot path on one MI355X.
 
 One step = one pass of the decode-shape sweep (K = 4096; N = 4096 and N = 14336; M in
-{1, 2, 4, 8, 16}): ten calls of tl_ternary_gemm on packed weights that are already in HBM.
-Every call reads a different copy of its weight matrix, taken from a ring of copies that is
-several times larger than the 256 MB last-level cache, so the weights really stream from
-HBM as they do when a model walks through its layers.
+{1, 2, 4, 8, 16}): ten GEMMs on packed weights that are already in HBM, handed to the library
+as one tl_ternary_gemm_grouped call (one kernel launch).  Every GEMM reads a different copy of
+its weight matrix, taken from a ring of copies that is several times larger than the 256 MB
+last-level cache, so the weights really stream from HBM as they do when a model walks through
+its layers.  The same step issued as ten separate tl_ternary_gemm calls is timed as well
+(`single_calls`, `per_call`).
 
 Prints one JSON line: `value` is the sweep's algorithmic bytes per second (packed W + x + y
-of all ten calls / time of a step).  `roofline` is measured live for the dominant kernel,
-`cpu_baseline` is the CPU oracle timed on the same workload.
+of all ten GEMMs / time of a step).  `roofline` is measured live for the dominant kernel (the
+grouped launch), `cpu_baseline` is the CPU oracle timed on the same workload.
 """
 import argparse
 import json
@@ -40,6 +42,7 @@ def main():
     ap.add_argument("--mode", choices=("sweep", "dominant", "copy"), default="sweep",
                     help="sweep: the benchmark; dominant / copy: run only the dominant kernel, or only "
                          "the plain copy probe, `steps` times (for rocprofv3 counter collection)")
+    ap.add_argument("--no-per-call", action="store_true", help="skip the ten-separate-calls measurements")
     ap.add_argument("--eager", action="store_true",
                     help="launch every call from the host instead of replaying a captured HIP graph")
     args = ap.parse_args()
@@ -112,12 +115,25 @@ def main():
         for name, M in calls:
             launch(name, M)
 
+    def step_grouped():
+        jobs = []
+        for name, M in calls:
+            lay = layers[name]
+            i = cursor[name]
+            cursor[name] = (i + 1) % lay["copies"]
+            jobs.append((xd[M], lay["ring"][i], lay["gbits"], yd[(name, M)], M, lay["N"], K))
+        arr = tl.make_jobs(jobs)
+        st = L.tl_ternary_gemm_grouped(arr, len(arr), stream)
+        if st != tl.TL_OK:
+            raise tl.TlError(st, "tl_ternary_gemm_grouped")
+
+    step_bytes = sum(algorithmic_bytes(M, layers[name]["N"], K) for name, M in calls)
     if args.mode == "dominant":
         for _ in range(args.steps):
-            launch("mlp_up_8b", 16)
+            step_grouped()
         torch.cuda.synchronize()
-        print(json.dumps({"mode": "dominant", "launches": args.steps, "layer": "mlp_up_8b", "M": 16,
-                          "algorithmic_bytes_per_launch": algorithmic_bytes(16, layers["mlp_up_8b"]["N"], K)}))
+        print(json.dumps({"mode": "dominant", "launches": args.steps, "kernel": "grouped sweep launch",
+                          "algorithmic_bytes_per_launch": step_bytes}))
         return
 
     # ---------------- timed region: exactly `steps` steps ---------------------------------
@@ -153,17 +169,21 @@ def main():
         return a.elapsed_time(b)
 
     for _ in range(args.warmup):
-        step()
+        step_grouped()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    ms_per_step = timed(step, args.steps) / args.steps
+    ms_per_step = timed(step_grouped, args.steps) / args.steps
     wall_ms = (time.perf_counter() - t0) * 1e3
-    step_bytes = sum(algorithmic_bytes(M, layers[name]["N"], K) for name, M in calls)
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
 
-    # ---------------- per-call figures, HIP events on the launch stream --------------------
+    # ---------------- the same step as ten separate calls; per-call figures ----------------
     per_call = []
-    for name, M in calls:
+    single = None
+    if not args.no_per_call:
+        ms_single = timed(step, args.steps) / args.steps
+        single = dict(ms_per_step=round(ms_single, 5), GBps=round(step_bytes / ms_single / 1e6, 1),
+                      hbm_frac=round(step_bytes / ms_single / 1e6 / HBM_PEAK_GBS, 4))
+    for name, M in ([] if args.no_per_call else calls):
         us = timed(lambda: launch(name, M), args.steps) * 1e3 / args.steps
         N = layers[name]["N"]
         b = algorithmic_bytes(M, N, K)
@@ -171,19 +191,18 @@ def main():
                              hbm_frac=round(b / us / 1e3 / HBM_PEAK_GBS, 4),
                              TFLOPs=round(2.0 * M * N * K / us / 1e6, 3)))
 
-    # dominant kernel: the small-M kernel on 4096 -> 14336 at M = 16 (largest launch of the step)
-    dom = next(c for c in per_call if c["layer"] == "mlp_up_8b" and c["M"] == 16)
-    dom_bytes = algorithmic_bytes(16, dom["N"], K)
+    # dominant kernel: the small-M kernel in its grouped launch; one launch = one step
+    us_launch = ms_per_step * 1e3
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.txt")     # figure from the rocprofv3 --pmc runs
     if os.path.exists(tpath):
         for line in open(tpath):
-            if line.startswith("gemv_4096x14336_M16_bytes_per_launch"):
+            if line.startswith("grouped_sweep_bytes_per_launch"):
                 traffic = float(line.split("=")[1])
-    roofline = dict(bound="hbm", kernel="gemv_kernel (small-M, 4096->14336, M=16)",
-                    achieved=round(dom_bytes / dom["us"] / 1e3, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(dom_bytes / dom["us"] / 1e3 / HBM_PEAK_GBS, 4),
-                    bytes_per_launch=dom_bytes, us_per_launch=dom["us"], traffic=traffic)
+    roofline = dict(bound="hbm", kernel="gemv_kernel<4>, grouped launch of the ten GEMMs of a step",
+                    achieved=round(step_bytes / us_launch / 1e3, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=round(step_bytes / us_launch / 1e3 / HBM_PEAK_GBS, 4),
+                    bytes_per_launch=step_bytes, us_per_launch=round(us_launch, 3), traffic=traffic)
 
     # ---------------- CPU oracle on the same sweep (reported baseline, not a target) -------
     cpu = None
@@ -215,10 +234,10 @@ def main():
         "vs_baseline": None, "dtype": "f16 x int2 -> f32 accumulate -> f16", "data": "synthetic",
         "config": {"workload": "decode-shape sweep: K=4096, N in {4096, 14336}, M in {1,2,4,8,16}, "
                                "2-bit packed ternary W (P(-1)=P(+1)=0.3), x fp16 ~ N(0,1), one fp16 gamma per matrix",
-                   "calls_per_step": len(calls), "weight_ring_copies": {n: layers[n]["copies"] for n in layers},
+                   "gemms_per_step": len(calls), "launches_per_step": 1, "weight_ring_copies": {n: layers[n]["copies"] for n in layers},
                    "algorithmic_bytes_per_step": step_bytes},
         "hbm_frac_of_peak": round(value / HBM_PEAK_GBS, 4),
-        "roofline": roofline, "cpu_baseline": cpu, "per_call": per_call,
+        "roofline": roofline, "cpu_baseline": cpu, "single_calls": single, "per_call": per_call,
         "launch_mode": "eager" if args.eager else "hip_graph_replay",
         "host_wall_ms_timed_region_incl_capture": round(wall_ms, 2), "context": PAPER_CONTEXT,
     }

@@ -345,13 +345,15 @@ hipError_t launch_gemv_jobs(const GemmDesc* jobs, int count, hipStream_t s)
 {
     // A user job with M > 16 becomes ceil(M / 16) kernel jobs (blocks of 16 activation rows).
     // One job alone gets 8-wave groups, one per CU, each holding up to 4 tiles; several jobs
-    // in one launch get 4-wave groups with 2 tiles, two groups per CU.
+    // in one launch get 4-wave groups (two passes over K = 4096), two groups per CU, so that
+    // one group's wait for HBM overlaps the other's arithmetic (measured best of the
+    // (waves, tiles, groups) settings tried on the decode sweep).
     int64_t blocks_total = 0;
     for (int i = 0; i < count; ++i) blocks_total += (jobs[i].M + 15) / 16;
     const bool grouped = blocks_total > 1;
     const int nw_cap = grouped ? 4 : 8;
-    const int t_cap = grouped ? 2 : kTMax;
-    const int group_cap = grouped ? 512 : 256;
+    const int t_cap = kTMax;
+    const int group_cap = 256;
 
     GemvBatch b;
     b.count = 0;
