@@ -9,7 +9,7 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libtl.so")
 OBJDIR = os.path.join(HERE, "_build")
 
-SOURCES = ["tl_host.cpp", "tl_basic.hip", "tl_gemv.hip", "tl_mfma.hip", "tl_api.hip"]
+SOURCES = ["tl_host.cpp", "tl_basic.hip", "tl_gemv.hip", "tl_gemv3.hip", "tl_mfma.hip", "tl_api.hip"]
 
 # packed-fp32 VALU forms are switched off for every device translation unit.
 HIPCC_FLAGS = [

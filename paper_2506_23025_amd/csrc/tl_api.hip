@@ -136,10 +136,14 @@ tl_status tl_ternary_gemm_1p6(const void* x, const void* Wpacked, uint16_t gamma
     if (!tl::dims_ok(M, N, K)) return TL_ERR_SHAPE;
     if (!tl::aligned16(x) || !tl::aligned16(Wpacked) || !tl::aligned16(y)) return TL_ERR_ALIGN;
     const float gamma = tl::half_bits_to_float(gamma_fp16_bits);
-    return tl::from_hip(tl::launch_gemm3_generic(
-        static_cast<const __half*>(x), static_cast<const uint8_t*>(Wpacked),
-        static_cast<int64_t>(tl_row_stride_bytes(TL_FMT_1P6BIT, K)), gamma, static_cast<__half*>(y),
-        M, N, K, static_cast<hipStream_t>(stream)));
+    const int64_t stride = static_cast<int64_t>(tl_row_stride_bytes(TL_FMT_1P6BIT, K));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (M <= tl::kGemvMaxM && tl::gemv3_supports(M, N, K))
+        return tl::from_hip(tl::launch_gemv3(static_cast<const __half*>(x), static_cast<const uint8_t*>(Wpacked),
+                                             stride, gamma, static_cast<__half*>(y), M, N, K, s));
+    return tl::from_hip(tl::launch_gemm3_generic(static_cast<const __half*>(x),
+                                                 static_cast<const uint8_t*>(Wpacked), stride, gamma,
+                                                 static_cast<__half*>(y), M, N, K, s));
 }
 
 tl_status tl_probe_copy(void* dst, const void* src, size_t bytes, void* stream)

@@ -1,0 +1,296 @@
+// Weight-streaming small-M kernel for the 1.6-bit format (5 trits per byte, plain base 3:
+// byte = sum_i (w_i + 1) 3^i, the block code of Sec. 3.2 without its fixed-point scaling).
+//
+// Same organisation as the 2-bit kernel (tl_gemv.hip): a workgroup owns 16-row tiles, wave w
+// owns a K slice and keeps its activations in registers as MFMA B operands, packed rows
+// stream once in full 128-byte lines, the tile slice is turned into MFMA order through
+// wave-private LDS, split-K partial tiles are summed through LDS in a fixed order.
+// What differs is the slice geometry and the decode:
+//
+//  * A slice is 128 packed bytes = 640 weights per row; a lane's 16 bytes hold 80 weights.
+//  * Decode is a table look-up: a 256-entry table in LDS maps a byte to its five digits
+//    c = w + 1, already placed where the 2-bit kernel's masks put them: low half-word
+//    c0 << 4 | c1 << 6 | c2 << 8, high half-word c3 << 4 | c4 << 6.  Three ANDs per byte give
+//    the fp16 (subnormal) pairs (c0, c3) 2^-20, (c1, c4) 2^-18 and (c2, 0) 2^-16, which feed
+//    v_mfma_f32_16x16x32_f16 against the activation pairs (x[5b], x[5b+3]), (x[5b+1], x[5b+4])
+//    and (x[5b+2], 0).  Per 5 weights: 2 address operations, 1 LDS read, 3 ANDs.
+//  * The paper expects the 1.6-bit form to cost more arithmetic per weight than the 2-bit
+//    form (Sec. 3.3 results, "Limitations"); here it is 1.0 against 0.7 VALU operations per
+//    weight, for 0.81 of the bytes.
+#include "tl_internal.hpp"
+
+namespace tl {
+
+namespace {
+
+constexpr int kT3Max = 4;            // tiles per workgroup
+constexpr int kSlice3 = 640;         // weights per slice (128 packed bytes)
+constexpr int kXRow = 1296;          // bytes per staged activation row (1280 + 16: spreads LDS banks)
+constexpr int kWave3Lds = 16 * kXRow;   // 20736 bytes per wave
+constexpr int kLutBytes = 1024;
+constexpr int kNW3Max = 7;           // 7 * 20736 + 1024 bytes of LDS
+
+struct Gemv3Params {
+    const __half* x;
+    const uint8_t* W;
+    __half* y;
+    float gamma;
+    int M, N, K;
+    int stride;      // bytes per packed row (multiple of 16)
+    int tiles;       // ceil(N / 16)
+    int groups;      // gridDim.x
+    int slices;      // ceil(stride / 128)
+};
+
+constexpr int vmcnt_imm3(int n)
+{
+    return (n & 0xF) | ((n >> 4) << 14) | (0x7 << 4) | (0xF << 8);
+}
+
+__device__ __forceinline__ f16x8 as_h8(u32x4 v) { return __builtin_bit_cast(f16x8, v); }
+
+template <int T>
+__global__ void __launch_bounds__(512)
+gemv3_kernel(Gemv3Params p)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int NW = blockDim.x >> 6;
+    uint32_t* const lut = reinterpret_cast<uint32_t*>(lds_raw);
+    unsigned char* const my_lds = lds_raw + kLutBytes + wave * kWave3Lds;
+
+    const int m0 = blockIdx.y * 16;
+    const int Mrem = (p.M - m0 < 16) ? (p.M - m0) : 16;
+    int MR = 1;
+    while (MR < Mrem) MR *= 2;
+    const int K = p.K, N = p.N;
+    const uint32_t stride = uint32_t(p.stride);
+    const int chunks = p.stride >> 4;          // 16-byte chunks per packed row
+    const int grp = blockIdx.x, groups = p.groups, tiles = p.tiles, slices = p.slices;
+
+    const int lr = lane >> 3, lc = lane & 7;   // load mapping: row of the half tile, chunk of the slice
+    const int mi = lane & 15, mg = lane >> 4;  // MFMA mapping: row / activation column, k group
+    const int xrow = mi & (MR - 1);
+
+    const uint32_t ww_off = uint32_t(lr) * 128u + (uint32_t(lc ^ lr) << 4);
+    const uint32_t wr_off0 = uint32_t(mi) * 128u + (uint32_t((mg) ^ (mi & 7)) << 4);
+    const uint32_t wr_off1 = uint32_t(mi) * 128u + (uint32_t((4 + mg) ^ (mi & 7)) << 4);
+
+    const unsigned char* const Wb = p.W;
+    const unsigned char* const xb = reinterpret_cast<const unsigned char*>(p.x + size_t(m0) * K);
+
+    u32x4 wreg[T][2];
+    const bool ragged_n = (N & 15) != 0;
+    auto issue_w = [&](int t, int slice) {
+        int tile = grp + t * groups;
+        if (tile >= tiles) tile = tiles - 1;
+        int chunk = slice * 8 + lc;
+        if (chunk >= chunks) chunk = 0;                    // past the row: meets zero activations
+        const unsigned char* tb = Wb + size_t(tile) * 16u * stride;
+        uint32_t off0 = uint32_t(lr) * stride + uint32_t(chunk) * 16u;
+        uint32_t off1 = off0 + 8u * stride;
+        if (ragged_n && tile == tiles - 1) {
+            const int last = N - 1 - tile * 16;
+            off0 = uint32_t(lr < last ? lr : last) * stride + uint32_t(chunk) * 16u;
+            off1 = uint32_t(lr + 8 < last ? lr + 8 : last) * stride + uint32_t(chunk) * 16u;
+        }
+        wreg[t][0] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tb + off0));
+        wreg[t][1] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tb + off1));
+    };
+
+    // Staged activation row r of the slice: 640 halves = 80 pieces of 16 bytes, by LDS-DMA
+    // (two instructions: pieces 0..63, then 64..79).  Pieces past K are stored as zeros.
+    auto issue_x = [&](int slice) {
+        for (int r = 0; r < MR; ++r) {
+            const int rr = r < Mrem ? r : Mrem - 1;
+            const unsigned char* src = xb + size_t(rr) * K * 2;
+            unsigned char* dst = my_lds + r * kXRow;
+#pragma unroll
+            for (int part = 0; part < 2; ++part) {
+                const int piece = part * 64 + lane;
+                const int kx = slice * kSlice3 + piece * 8;
+                if (piece < 80) {
+                    if (kx < K) {
+                        __builtin_amdgcn_global_load_lds(
+                            (const __attribute__((address_space(1))) void*)(src + uint32_t(kx) * 2u),
+                            (__attribute__((address_space(3))) void*)(dst + part * 1024),
+                            16, 0, 0);
+                    } else {
+                        *reinterpret_cast<u32x4*>(dst + piece * 16) = u32x4{0u, 0u, 0u, 0u};
+                    }
+                }
+            }
+        }
+    };
+
+    f32x4 part_acc[T];
+#pragma unroll
+    for (int t = 0; t < T; ++t) part_acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    int slice = wave;
+    if (slice < slices) {
+        issue_x(slice);
+#pragma unroll
+        for (int t = 0; t < T; ++t) issue_w(t, slice);
+    }
+
+    // byte -> digits table (bytes 243..255 never occur; they decode like byte - 243)
+    for (unsigned b = threadIdx.x; b < 256; b += blockDim.x) {
+        unsigned v = b >= 243 ? b - 243 : b;
+        unsigned c[5];
+#pragma unroll
+        for (int i = 0; i < 5; ++i) { c[i] = v % 3u; v /= 3u; }
+        lut[b] = (c[0] << 4) | (c[1] << 6) | (c[2] << 8) | (c[3] << 20) | (c[4] << 22);
+    }
+    __syncthreads();
+    if (wave < slices) __builtin_amdgcn_s_waitcnt(vmcnt_imm3(2 * T));   // LDS-DMA is not tracked by the compiler
+
+    for (; slice < slices; slice += NW) {
+        const bool more = (slice + NW) < slices;
+        // breg[h][d][cls][j]: activation pair for byte 4d + j of the lane's 16 bytes (half h):
+        // cls 0 -> (x[k], x[k+3]), 1 -> (x[k+1], x[k+4]), 2 -> (x[k+2], 0), k = 5 * byte index
+        uint32_t breg[2][4][3][4];
+        {
+            const unsigned char* row = my_lds + xrow * kXRow;
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int d = 0; d < 4; ++d)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int kl = ((4 * h + mg) * 16 + 4 * d + j) * 5;      // first weight of the byte
+                        const uint16_t* px = reinterpret_cast<const uint16_t*>(row + kl * 2);
+                        const uint32_t x0 = px[0], x1 = px[1], x2 = px[2], x3 = px[3], x4 = px[4];
+                        breg[h][d][0][j] = x0 | (x3 << 16);
+                        breg[h][d][1][j] = x1 | (x4 << 16);
+                        breg[h][d][2][j] = x2;
+                    }
+        }
+        // nsx = -2^-20 sum_k x over the slice, in accumulator layout (constant 16-row operand)
+        f32x4 nsx = f32x4{0.f, 0.f, 0.f, 0.f};
+        {
+            const uint32_t c = 0x80108010u;
+            const u32x4 a = u32x4{c, c, c, c};
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int d = 0; d < 4; ++d)
+#pragma unroll
+                    for (int cls = 0; cls < 3; ++cls) {
+                        const u32x4 bb = u32x4{breg[h][d][cls][0], breg[h][d][cls][1], breg[h][d][cls][2], breg[h][d][cls][3]};
+                        nsx = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(a), as_h8(bb), nsx, 0, 0, 0);
+                    }
+        }
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            unsigned char* const reg_t = my_lds + t * 2048;
+            *reinterpret_cast<u32x4*>(reg_t + ww_off) = wreg[t][0];
+            *reinterpret_cast<u32x4*>(reg_t + 1024 + ww_off) = wreg[t][1];
+            if (more) issue_w(t, slice + NW);
+            if (grp + t * groups < tiles) {
+                f32x4 acc[3] = {nsx, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const u32x4 wv = *reinterpret_cast<const u32x4*>(reg_t + (h ? wr_off1 : wr_off0));
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) {
+                        const uint32_t w = wv[d];
+                        uint32_t e[4];
+                        e[0] = lut[w & 0xFFu];
+                        e[1] = lut[(w >> 8) & 0xFFu];
+                        e[2] = lut[(w >> 16) & 0xFFu];
+                        e[3] = lut[w >> 24];
+#pragma unroll
+                        for (int cls = 0; cls < 3; ++cls) {
+                            const uint32_t mask = (cls == 0) ? 0x00300030u : (cls == 1) ? 0x00C000C0u : 0x00000300u;
+                            const u32x4 a = u32x4{e[0] & mask, e[1] & mask, e[2] & mask, e[3] & mask};
+                            const u32x4 bb = u32x4{breg[h][d][cls][0], breg[h][d][cls][1], breg[h][d][cls][2], breg[h][d][cls][3]};
+                            acc[cls] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(a), as_h8(bb), acc[cls], 0, 0, 0);
+                        }
+                    }
+                }
+                part_acc[t] += acc[0] * 1048576.f + acc[1] * 262144.f + acc[2] * 65536.f;
+            }
+        }
+        if (more) {
+            issue_x(slice + NW);
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm3(0));
+        }
+    }
+
+    // ---- split-K reduction across the waves, epilogue ----
+    __syncthreads();
+    f32x4* red = reinterpret_cast<f32x4*>(lds_raw + kLutBytes);
+#pragma unroll
+    for (int t = 0; t < T; ++t) red[(t * NW + wave) * 64 + lane] = part_acc[t];
+    __syncthreads();
+    for (int item = threadIdx.x; item < T * 64; item += blockDim.x) {
+        const int t = item >> 6;
+        const int l = item & 63;
+        const int tile = grp + t * groups;
+        if (tile >= tiles) continue;
+        f32x4 v[8];
+#pragma unroll
+        for (int w = 0; w < 8; ++w)
+            v[w] = (w < NW) ? red[(t * NW + w) * 64 + l] : f32x4{0.f, 0.f, 0.f, 0.f};
+        const f32x4 s = ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
+        const int n = tile * 16 + 4 * (l >> 4);
+        if ((l & 15) < Mrem) {
+            __half* dst = p.y + size_t(m0 + (l & 15)) * N + n;
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                if (n + r < N) dst[r] = __float2half_rn(p.gamma * s[r]);
+        }
+    }
+}
+
+using Kernel3Fn = void (*)(Gemv3Params);
+
+Kernel3Fn pick3(int T)
+{
+    switch (T) {
+        case 1: return gemv3_kernel<1>;
+        case 2: return gemv3_kernel<2>;
+        case 3: return gemv3_kernel<3>;
+        default: return gemv3_kernel<4>;
+    }
+}
+
+}  // namespace
+
+bool gemv3_supports(int64_t M, int64_t N, int64_t K)
+{
+    return M >= 1 && N >= 1 && K >= 8 && (K % 8) == 0 && K <= (int64_t(1) << 24) &&
+           N <= (int64_t(1) << 24) && (M + 15) / 16 <= 65535;
+}
+
+hipError_t launch_gemv3(const __half* x, const uint8_t* Wp, int64_t stride, float gamma, __half* y,
+                        int64_t M, int64_t N, int64_t K, hipStream_t s)
+{
+    Gemv3Params p;
+    p.x = x; p.W = Wp; p.y = y; p.gamma = gamma;
+    p.M = int(M); p.N = int(N); p.K = int(K);
+    p.stride = int(stride);
+    p.tiles = int((N + 15) / 16);
+    p.slices = int((stride + 127) / 128);
+    const int NW = p.slices < kNW3Max ? p.slices : kNW3Max;
+    int groups = p.tiles < 256 ? p.tiles : 256;
+    int T = (p.tiles + groups - 1) / groups;
+    if (T > kT3Max) { T = kT3Max; groups = (p.tiles + T - 1) / T; }
+    p.groups = groups;
+    Kernel3Fn fn = pick3(T);
+    static bool lds_raised[kT3Max + 1];
+    if (!lds_raised[T]) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           kNW3Max * kWave3Lds + kLutBytes);
+        if (e != hipSuccess) return e;
+        lds_raised[T] = true;
+    }
+    dim3 grid(groups, unsigned((M + 15) / 16));
+    hipLaunchKernelGGL(fn, grid, dim3(NW * 64), size_t(NW) * kWave3Lds + kLutBytes, s, p);
+    return hipGetLastError();
+}
+
+}  // namespace tl

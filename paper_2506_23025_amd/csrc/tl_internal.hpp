@@ -44,6 +44,11 @@ hipError_t launch_gemv(const __half* x, const uint32_t* Wp, float gamma, __half*
 // Several independent GEMMs (each passing gemv_supports) in as few launches as possible.
 hipError_t launch_gemv_jobs(const GemmDesc* jobs, int count, hipStream_t s);
 
+// Weight-streaming small-M kernel for the 1.6-bit format.  Needs K % 8 == 0.
+bool gemv3_supports(int64_t M, int64_t N, int64_t K);
+hipError_t launch_gemv3(const __half* x, const uint8_t* Wp, int64_t stride, float gamma, __half* y,
+                        int64_t M, int64_t N, int64_t K, hipStream_t s);
+
 // LDS-tiled MFMA prefill kernel (2-bit).  Needs K % 64 == 0.
 bool mfma_supports(int64_t M, int64_t N, int64_t K);
 hipError_t launch_mfma(const __half* x, const uint32_t* Wp, float gamma, __half* y,

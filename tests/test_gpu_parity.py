@@ -251,3 +251,34 @@ def test_grouped_empty_and_errors():
     assert L.tl_ternary_gemm_grouped(bad, 1, None) == tl.TL_ERR_NULL
     bad = tl.make_jobs([(16, 16, 0, 24, 1, 16, 64)])
     assert L.tl_ternary_gemm_grouped(bad, 1, None) == tl.TL_ERR_ALIGN
+
+
+# ---------------------------------------------------------------- 1.6-bit small-M kernel
+
+GEMV3_SHAPES = [(1, 16, 8), (1, 1, 640), (4, 272, 640), (3, 17, 1280), (16, 100, 648), (7, 33, 4096),
+                (16, 4099, 4096), (3, 40, 11008), (33, 130, 2048), (2, 512, 8192), (64, 48, 4096)]
+
+
+@pytest.mark.parametrize("M,N,K", GEMV3_SHAPES)
+def test_gemv_1p6_matches_oracle(M, N, K):
+    x, W, g = si.layer(9000 + M + N + K, M, N, K)
+    Wp = tl.tl_pack_1p6bit(W)
+    assert np.array_equal(Wp, oracle.pack3le(W))
+    y = run_gemm3(x, Wp, g, N, K)
+    assert_close(y, oracle.gemm_packed3le(x, Wp, g, K), x, g, f"1.6-bit small-M {M}x{N}x{K}")
+
+
+@pytest.mark.parametrize("M", [1, 4, 16])
+def test_gemv_1p6_full_size_agrees_with_2bit_path(M):
+    # config 5: the same weights through both formats; 512 sampled columns against the oracle
+    N, K = 14336, 4096
+    x, W, g = si.layer(si.SEEDS["c5"] + M, M, N, K)
+    y3 = run_gemm3(x, tl.tl_pack_1p6bit(W), g, N, K)
+    y2 = run_gemm(x, tl.tl_pack_2bit(W), g, N, K)
+    cols = np.sort(np.random.default_rng(3).choice(N, 512, replace=False))
+    ref = oracle.gemm(x, np.ascontiguousarray(W[cols]), g)
+    assert_close(y3[:, cols], ref, x, g, "1.6-bit full size")
+    assert_close(y2[:, cols], ref, x, g, "2-bit full size")
+    assert_close(y3, y2.astype(np.float64), x, g, "1.6-bit vs 2-bit")
+    # deterministic
+    assert np.array_equal(run_gemm3(x, tl.tl_pack_1p6bit(W), g, N, K).view(np.uint16), y3.view(np.uint16))
