@@ -31,11 +31,14 @@
 //    4-wave groups, two per CU, so that one group's wait for HBM overlaps the other's MFMAs.
 #include "tl_internal.hpp"
 
+#include <cstddef>
+#include <type_traits>
+
 namespace tl {
 
 namespace {
 
-constexpr int kTMax = 4;          // tiles a workgroup keeps in flight
+constexpr int kTMax = 4;          // tiles per work item
 constexpr int kSliceK = 512;      // K elements a wave owns per pass
 constexpr int kWaveLds = 16384;   // bytes of LDS per wave: 16 activation rows x 1 KB
 constexpr int kMaxJobs = 16;      // jobs per launch
@@ -48,16 +51,18 @@ struct GemvJob {                  // 64 bytes, lives in the kernel argument segm
     int Mrem;                     // 1..16 activation rows
     int N, K;
     int tiles;                    // ceil(N / 16)
-    int groups;                   // workgroups that share this job
-    int group0;                   // index of the job's first workgroup in the launch
+    int items;                    // work items of this job: ceil(tiles / T)
     int slices;                   // ceil(K / 512)
     int mr;                       // staged rows: power of two >= Mrem (surplus rows repeat)
-    int pad;
+    int pad[2];
 };
 
 struct GemvBatch {
     int count;
-    int pad[3];
+    int total_items;
+    int red_off;                  // byte offset in LDS of the split-K reduction area
+    int pad;
+    int item0[kMaxJobs];          // first work item of job j; INT_MAX for unused entries
     GemvJob job[kMaxJobs];
 };
 
@@ -73,19 +78,75 @@ __device__ __forceinline__ f16x8 as_f16x8(u32x4 v)
     return __builtin_bit_cast(f16x8, v);
 }
 
-#ifdef TL_GEMV_TRACE
-__device__ unsigned long long* g_trace;   // [group][wave][16] time stamps, development builds only
-#define TL_STAMP(i) do { tl_stamp[i] = __builtin_amdgcn_s_memtime(); } while (0)
-#define TL_STAMP_DECL unsigned long long tl_stamp[16] = {}
-#define TL_STAMP_FLUSH do { if (lane == 0) for (int i_ = 0; i_ < 16; ++i_) g_trace[(size_t(blockIdx.x) * 8 + wave) * 16 + i_] = tl_stamp[i_]; } while (0)
-#else
-#define TL_STAMP(i) do { } while (0)
-#define TL_STAMP_DECL do { } while (0)
-#define TL_STAMP_FLUSH do { } while (0)
-#endif
+// What a workgroup needs to know about one work item; every member is wave-uniform.
+struct ItemCtx {
+    const unsigned char* Wb;
+    const unsigned char* xb;
+    __half* y;
+    float gamma;
+    int Mrem, MR;
+    int N, K;
+    uint32_t row_bytes;           // bytes per packed row
+    int chunks;                   // 64-weight (16-byte) chunks per row
+    int tiles, items, idx;        // tile t of the item is idx + t * items
+    int slices;
+};
 
-// T: tiles per workgroup; tile t of group g (within its job) is g + t * groups.
-template <int T>
+// The job table of a launch, one job per lane (lane & 15), read from the kernel argument
+// segment with vector loads: every workgroup needs one entry chosen by its index, and a
+// scalar look-up would be two dependent trips to memory before the first weight is requested.
+struct JobTable {
+    uint32_t d[16];               // the 16 dwords of GemvJob
+    int item0;
+};
+
+__device__ __forceinline__ JobTable load_table(int lane)
+{
+    typedef const __attribute__((address_space(4))) unsigned char* kptr;
+    kptr ka = (kptr)__builtin_amdgcn_kernarg_segment_ptr();     // GemvBatch is the only argument
+    const int k = lane & 15;
+    JobTable r;
+    r.item0 = *(const __attribute__((address_space(4))) int*)(ka + offsetof(GemvBatch, item0) + 4 * k);
+    const __attribute__((address_space(4))) u32x4* jp =
+        (const __attribute__((address_space(4))) u32x4*)(ka + offsetof(GemvBatch, job) + sizeof(GemvJob) * k);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const u32x4 q = jp[i];
+        r.d[4 * i] = q[0]; r.d[4 * i + 1] = q[1]; r.d[4 * i + 2] = q[2]; r.d[4 * i + 3] = q[3];
+    }
+    return r;
+}
+
+// Work item g -> its job (the last one whose first item is <= g) and position in it.
+__device__ __forceinline__ ItemCtx load_item(const JobTable& tb, int g)
+{
+    const unsigned long long m = __builtin_amdgcn_ballot_w64(g >= tb.item0) & 0xFFFFull;
+    const int ji = __builtin_popcountll(m) - 1;
+    uint32_t f[16];
+#pragma unroll
+    for (int i = 0; i < 14; ++i) f[i] = __builtin_amdgcn_readlane(tb.d[i], ji);
+    const int item0 = __builtin_amdgcn_readlane(tb.item0, ji);
+    ItemCtx c;
+    c.xb = reinterpret_cast<const unsigned char*>(uintptr_t(f[0]) | (uintptr_t(f[1]) << 32));
+    c.Wb = reinterpret_cast<const unsigned char*>(uintptr_t(f[2]) | (uintptr_t(f[3]) << 32));
+    c.y = reinterpret_cast<__half*>(uintptr_t(f[4]) | (uintptr_t(f[5]) << 32));
+    c.gamma = __builtin_bit_cast(float, f[6]);
+    c.Mrem = int(f[7]);
+    c.N = int(f[8]); c.K = int(f[9]);
+    c.row_bytes = f[9] >> 2;
+    c.chunks = int(f[9] >> 6);
+    c.tiles = int(f[10]); c.items = int(f[11]); c.idx = g - item0;
+    c.slices = int(f[12]);
+    c.MR = int(f[13]);
+    return c;
+}
+
+static_assert(sizeof(GemvJob) == 64 && offsetof(GemvJob, gamma) == 24 && offsetof(GemvJob, mr) == 52,
+              "load_item decodes GemvJob by dword position");
+
+// T: tiles per work item; MULTI: the launch carries more than one job.
+// A workgroup takes the items blockIdx.x, blockIdx.x + gridDim.x, ...
+template <int T, bool MULTI>
 __global__ void __launch_bounds__(512)
 gemv_kernel(GemvBatch b)
 {
@@ -94,18 +155,6 @@ gemv_kernel(GemvBatch b)
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int NW = blockDim.x >> 6;
     unsigned char* const my_lds = lds_raw + wave * kWaveLds;
-    TL_STAMP_DECL;
-    TL_STAMP(0);
-
-    int ji = 0;
-    while (ji + 1 < b.count && int(blockIdx.x) >= b.job[ji + 1].group0) ++ji;
-    const GemvJob& J = b.job[ji];
-    const int grp = int(blockIdx.x) - J.group0;
-    const int groups = J.groups, tiles = J.tiles, slices = J.slices;
-    const int Mrem = J.Mrem, MR = J.mr;
-    const int K = J.K, N = J.N;
-    const uint32_t row_bytes = uint32_t(K) >> 2;
-    const int chunks = K >> 6;                 // 64-weight (16-byte) chunks per row
 
     // ---- coalesced load mapping: 8 lanes per 128-byte line, 8 rows per instruction ----
     const int lr = lane >> 3;                  // row within the half tile
@@ -113,34 +162,30 @@ gemv_kernel(GemvBatch b)
     // ---- MFMA mapping: lane (i, g) = (row / activation column, k group) -----------------
     const int mi = lane & 15;
     const int mg = lane >> 4;
-    const int xrow = mi & (MR - 1);            // staged activation row this lane's column reads
 
     // LDS offsets (bytes, relative to my_lds); immediates add the row / tile / half part
-    const uint32_t xr_off = uint32_t(xrow) * 1024u + uint32_t(mg) * 128u;  // + ((c ^ (xrow & 7)) << 4)
     const uint32_t ww_off = uint32_t(lr) * 128u + (uint32_t(lc ^ lr) << 4);
     const uint32_t wr_off0 = uint32_t(mi) * 128u + (uint32_t((mg) ^ (mi & 7)) << 4);
     const uint32_t wr_off1 = uint32_t(mi) * 128u + (uint32_t((4 + mg) ^ (mi & 7)) << 4);
 
-    const unsigned char* const Wb = reinterpret_cast<const unsigned char*>(J.W);
-    const unsigned char* const xb = reinterpret_cast<const unsigned char*>(J.x);
-
     u32x4 wreg[T][2];
-    const bool ragged_n = (N & 15) != 0;
-    auto issue_w = [&](int t, int slice) {
-        int tile = grp + t * groups;
-        if (tile >= tiles) tile = tiles - 1;               // loaded again, never used
+    auto issue_w = [&](const ItemCtx& c, int t, int slice) {
+        int tile = c.idx + t * c.items;
+        if (tile >= c.tiles) tile = c.tiles - 1;           // loaded again, never used
         int chunk = slice * 8 + lc;
-        if (chunk >= chunks) chunk = 0;                    // multiplied by zero activations
-        const unsigned char* tb = Wb + size_t(tile) * 16u * row_bytes;
-        uint32_t off0 = uint32_t(lr) * row_bytes + uint32_t(chunk) * 16u;
-        uint32_t off1 = off0 + 8u * row_bytes;
-        if (ragged_n && tile == tiles - 1) {               // scalar branch: rows past N read row N-1
-            const int last = N - 1 - tile * 16;
-            off0 = uint32_t(lr < last ? lr : last) * row_bytes + uint32_t(chunk) * 16u;
-            off1 = uint32_t(lr + 8 < last ? lr + 8 : last) * row_bytes + uint32_t(chunk) * 16u;
+        if (chunk >= c.chunks) chunk = 0;                  // multiplied by zero activations
+        const unsigned char* tb = c.Wb + size_t(tile) * 16u * c.row_bytes;
+        uint32_t off0 = uint32_t(lr) * c.row_bytes + uint32_t(chunk) * 16u;
+        uint32_t off1 = off0 + 8u * c.row_bytes;
+        if ((c.N & 15) != 0 && tile == c.tiles - 1) {      // scalar branch: rows past N read row N-1
+            const int last = c.N - 1 - tile * 16;
+            off0 = uint32_t(lr < last ? lr : last) * c.row_bytes + uint32_t(chunk) * 16u;
+            off1 = uint32_t(lr + 8 < last ? lr + 8 : last) * c.row_bytes + uint32_t(chunk) * 16u;
         }
-        wreg[t][0] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tb + off0));
-        wreg[t][1] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tb + off1));
+        // the pointers were put together from table registers: say that they are global
+        typedef const __attribute__((address_space(1))) u32x4* gptr;
+        wreg[t][0] = __builtin_nontemporal_load((gptr)(tb + off0));
+        wreg[t][1] = __builtin_nontemporal_load((gptr)(tb + off1));
     };
 
     // Activation rows go straight from global memory into the LDS staging area (LDS-DMA, no
@@ -148,13 +193,13 @@ gemv_kernel(GemvBatch b)
     // l ^ (r & 7) of the slice and the hardware drops it at slot l, which is the swizzled
     // layout the operand set-up reads.  Rows past Mrem repeat row Mrem-1; lanes past K
     // store zeros instead (their weights are whatever chunk 0 holds).
-    auto issue_x = [&](int slice) {
-        for (int r = 0; r < MR; ++r) {
-            const int rr = r < Mrem ? r : Mrem - 1;
+    auto issue_x = [&](const ItemCtx& c, int slice) {
+        for (int r = 0; r < c.MR; ++r) {
+            const int rr = r < c.Mrem ? r : c.Mrem - 1;
             const int kx = slice * kSliceK + ((lane ^ (r & 7)) << 3);
-            if (kx < K) {
+            if (kx < c.K) {
                 __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void*)(xb + size_t(rr) * K * 2 + uint32_t(kx) * 2u),
+                    (const __attribute__((address_space(1))) void*)(c.xb + size_t(rr) * c.K * 2 + uint32_t(kx) * 2u),
                     (__attribute__((address_space(3))) void*)(my_lds + r * 1024),
                     16, 0, 0);
             } else {
@@ -163,47 +208,42 @@ gemv_kernel(GemvBatch b)
         }
     };
 
-    f32x4 part[T];
-#pragma unroll
-    for (int t = 0; t < T; ++t) part[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // One pass of a wave: 512 k of the T tiles of an item.  FIRST (a compile-time tag) marks
+    // the very first pass of the workgroup, whose activations were requested before its
+    // weights; that copy of the body runs straight from the kernel entry, so the compiler's
+    // wait counts in it are exact and tile t is decoded as soon as its own two loads have
+    // arrived.  Every other pass starts with all of its loads complete.
+    auto do_pass = [&](auto first_tag, const ItemCtx& cur, const ItemCtx& nxt, bool pre, int slice,
+                       f32x4 (&part)[T]) {
+        constexpr bool FIRST = decltype(first_tag)::value;
+        // The compiler does not track LDS-DMA, so wait by hand.  First pass: until only the
+        // 2T weight loads issued after the activation rows are outstanding (loads of a wave
+        // return in order).  Later passes: weights were requested first, so for all.
+        if constexpr (FIRST) __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * T));
+        else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        const bool more = (slice + NW) < cur.slices;
 
-    // Activations go first: they are short L2 hits, and the loads of one wave return in
-    // order, so the weight stream queued behind them overlaps the operand set-up below.
-    int slice = wave;
-    if (slice < slices) {
-        issue_x(slice);
-#pragma unroll
-        for (int t = 0; t < T; ++t) issue_w(t, slice);
-        TL_STAMP(1);
-        // The compiler does not track LDS-DMA: wait by hand until only the 2T weight loads
-        // issued after the activation rows are outstanding (loads of a wave return in order).
-        __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * T));
-        TL_STAMP(2);
-    }
-
-    for (; slice < slices; slice += NW) {                  // wave-uniform trip count
-        const bool more = (slice + NW) < slices;
-        // ---------------- activations of this slice -> MFMA B registers ----------------
+        const int xrow = mi & (cur.MR - 1);                // staged activation row of this lane's column
+        const uint32_t xr_off = uint32_t(xrow) * 1024u + uint32_t(mg) * 128u;
+        const uint32_t sw = uint32_t(xrow & 7);
+        // ---------------- activations of this slice -> MFMA B registers --------------------
         // staging layout: row r, 16-byte piece P at slot P ^ (r & 7)
         // breg[h][wd][e]: (x[k], x[k + 8]) with k = slice0 + 64 (4h + g) + 16 wd + e
         uint32_t breg[2][4][8];
-        {
-            const uint32_t sw = uint32_t(xrow & 7);
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
+        for (int h = 0; h < 2; ++h)
 #pragma unroll
-                for (int wd = 0; wd < 4; ++wd) {
-                    const u32x4 lo = *reinterpret_cast<const u32x4*>(
-                        my_lds + xr_off + h * 512 + ((uint32_t(2 * wd) ^ sw) << 4));
-                    const u32x4 hi = *reinterpret_cast<const u32x4*>(
-                        my_lds + xr_off + h * 512 + ((uint32_t(2 * wd + 1) ^ sw) << 4));
+            for (int wd = 0; wd < 4; ++wd) {
+                const u32x4 lo = *reinterpret_cast<const u32x4*>(
+                    my_lds + xr_off + h * 512 + ((uint32_t(2 * wd) ^ sw) << 4));
+                const u32x4 hi = *reinterpret_cast<const u32x4*>(
+                    my_lds + xr_off + h * 512 + ((uint32_t(2 * wd + 1) ^ sw) << 4));
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        breg[h][wd][2 * r] = __builtin_amdgcn_perm(hi[r], lo[r], 0x05040100u);
-                        breg[h][wd][2 * r + 1] = __builtin_amdgcn_perm(hi[r], lo[r], 0x07060302u);
-                    }
+                for (int r = 0; r < 4; ++r) {
+                    breg[h][wd][2 * r] = __builtin_amdgcn_perm(hi[r], lo[r], 0x05040100u);
+                    breg[h][wd][2 * r + 1] = __builtin_amdgcn_perm(hi[r], lo[r], 0x07060302u);
                 }
-        }
+            }
         // nsx[r] = -2^-20 sum_k x[m][k] over the slice, in the layout of an accumulator:
         // an MFMA whose 16-row operand is the constant -2^-20 in every position.
         f32x4 nsx = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -218,8 +258,7 @@ gemv_kernel(GemvBatch b)
                     nsx = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), as_f16x8(bb), nsx, 0, 0, 0);
                 }
         }
-        TL_STAMP(3);
-        // ---------------- per tile: turn through LDS, decode, MFMA -----------------------
+        // ---------------- per tile: turn through LDS, decode, MFMA ---------------------------
         // The staging rows are dead once breg is built, so region t (2 KB) reuses them; LDS
         // operations of one wave execute in order.
 #pragma unroll
@@ -227,8 +266,9 @@ gemv_kernel(GemvBatch b)
             unsigned char* const reg_t = my_lds + t * 2048;
             *reinterpret_cast<u32x4*>(reg_t + ww_off) = wreg[t][0];
             *reinterpret_cast<u32x4*>(reg_t + 1024 + ww_off) = wreg[t][1];
-            if (more) issue_w(t, slice + NW);              // refill for the next pass
-            if (grp + t * groups < tiles) {                // scalar: tiles past the end are skipped
+            if (more) issue_w(cur, t, slice + NW);         // refill for the next pass
+            else if (pre) issue_w(nxt, t, wave);           // or for the next item
+            if (cur.idx + t * cur.items < cur.tiles) {     // scalar: tiles past the end are skipped
                 // acc[0] starts from -2^-20 sum x: with the 2^20 below it carries the "-1" of c = w + 1
                 f32x4 acc[3] = {nsx, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
@@ -249,64 +289,138 @@ gemv_kernel(GemvBatch b)
                 // fp16 bits c << (2j + 4) are the subnormal c 4^(j+2) 2^-24: undo with 2^(20 - 2j)
                 part[t] += acc[0] * 1048576.f + acc[1] * 262144.f + acc[2] * 65536.f;
             }
-            TL_STAMP(4 + t);
         }
-        // The staging rows share LDS with the tile regions, so the next slice's activations
-        // can only be fetched once the last tile has been read.
-        if (more) {
-            issue_x(slice + NW);
-            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));       // behind the prefetched weights
-        }
-    }
+        // The staging rows share LDS with the tile regions, so the next activations can only
+        // be fetched once the last tile has been read; the next pass waits for them.
+        if (more) issue_x(cur, slice + NW);
+        else if (pre) issue_x(nxt, wave);
+    };
 
-    // ---- split-K reduction across the waves, epilogue -----------------------------------
-    // Layout [t][wave][lane] of f32x4 in LDS (reuses the staging space after a barrier).
-    TL_STAMP(12);
-    __syncthreads();
-    TL_STAMP(13);
-    f32x4* red = reinterpret_cast<f32x4*>(lds_raw);
+    // Split-K reduction across the waves and output.  Layout [t][wave][lane] of f32x4 in LDS.
+    // A workgroup with a single item reuses the staging space (red_off = 0); otherwise the
+    // area lies behind it, because the next item's activations are already arriving there.
+    // The first barrier also keeps this item's partial sums from overtaking a wave that
+    // still reads the previous ones.
+    auto epilogue = [&](const ItemCtx& cur, const f32x4 (&part)[T]) {
+        __syncthreads();
+        f32x4* red = reinterpret_cast<f32x4*>(lds_raw + b.red_off);
 #pragma unroll
-    for (int t = 0; t < T; ++t) red[(t * NW + wave) * 64 + lane] = part[t];
-    __syncthreads();
-    const float gamma = J.gamma;
-    for (int item = threadIdx.x; item < T * 64; item += blockDim.x) {
-        const int t = item >> 6;
-        const int l = item & 63;
-        const int tile = grp + t * groups;
-        if (tile >= tiles) continue;
-        f32x4 v[8];
+        for (int t = 0; t < T; ++t) red[(t * NW + wave) * 64 + lane] = part[t];
+        __syncthreads();
+        const float gamma = cur.gamma;
+        for (int o = threadIdx.x; o < T * 64; o += blockDim.x) {
+            const int t = o >> 6;
+            const int l = o & 63;
+            const int tile = cur.idx + t * cur.items;
+            if (tile >= cur.tiles) continue;
+            f32x4 v[8];
 #pragma unroll
-        for (int w = 0; w < 8; ++w)                         // all reads in flight, then a fixed-order sum
-            v[w] = (w < NW) ? red[(t * NW + w) * 64 + l] : f32x4{0.f, 0.f, 0.f, 0.f};
-        const f32x4 s = ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
-        const int n = tile * 16 + 4 * (l >> 4);
-        if ((l & 15) < Mrem) {
-            __half* dst = J.y + size_t(l & 15) * N + n;
-            if (n + 3 < N && (N & 3) == 0) {                // four consecutive n: one 8-byte store
-                const f16x2 lo = {(_Float16)(gamma * s[0]), (_Float16)(gamma * s[1])};
-                const f16x2 hi = {(_Float16)(gamma * s[2]), (_Float16)(gamma * s[3])};
-                *reinterpret_cast<u32x2*>(dst) = u32x2{__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
-            } else {
+            for (int w = 0; w < 8; ++w)                     // all reads in flight, then a fixed-order sum
+                v[w] = (w < NW) ? red[(t * NW + w) * 64 + l] : f32x4{0.f, 0.f, 0.f, 0.f};
+            const f32x4 s = ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
+            const int n = tile * 16 + 4 * (l >> 4);
+            if ((l & 15) < cur.Mrem) {
+                typedef __attribute__((address_space(1))) __half* gh_ptr;
+                gh_ptr dst = (gh_ptr)(cur.y + size_t(l & 15) * cur.N + n);
+                if (n + 3 < cur.N && (cur.N & 3) == 0) {    // four consecutive n: one 8-byte store
+                    const f16x2 lo = {(_Float16)(gamma * s[0]), (_Float16)(gamma * s[1])};
+                    const f16x2 hi = {(_Float16)(gamma * s[2]), (_Float16)(gamma * s[3])};
+                    *(__attribute__((address_space(1))) u32x2*)dst =
+                        u32x2{__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
+                } else {
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    if (n + r < N) dst[r] = __float2half_rn(gamma * s[r]);
+                    for (int r = 0; r < 4; ++r)
+                        if (n + r < cur.N) *(__attribute__((address_space(1))) _Float16*)(dst + r) = (_Float16)(gamma * s[r]);
+                }
             }
         }
+    };
+
+    int g = blockIdx.x;
+    // A launch of one job reads it with scalar loads at fixed offsets (one trip to memory,
+    // nothing depends on a look-up); several jobs go through the table in registers.
+    JobTable table;
+    if constexpr (MULTI) table = load_table(lane);
+    auto get_item = [&](int gi) -> ItemCtx {
+        if constexpr (MULTI) {
+            return load_item(table, gi);
+        } else {
+            const GemvJob& J = b.job[0];
+            ItemCtx c;
+            c.xb = reinterpret_cast<const unsigned char*>(J.x);
+            c.Wb = reinterpret_cast<const unsigned char*>(J.W);
+            c.y = J.y;
+            c.gamma = J.gamma;
+            c.Mrem = J.Mrem; c.MR = J.mr;
+            c.N = J.N; c.K = J.K;
+            c.row_bytes = uint32_t(J.K) >> 2;
+            c.chunks = J.K >> 6;
+            c.tiles = J.tiles; c.items = J.items; c.idx = gi;
+            c.slices = J.slices;
+            return c;
+        }
+    };
+    ItemCtx cur = get_item(g);
+    // Activations go first: they are short L2 hits, and the loads of one wave return in
+    // order, so the weight stream queued behind them overlaps the operand set-up.
+    if (wave < cur.slices) {
+        issue_x(cur, wave);
+#pragma unroll
+        for (int t = 0; t < T; ++t) issue_w(cur, t, wave);
     }
-    TL_STAMP(14);
-    TL_STAMP_FLUSH;
+    // The next item of this workgroup: its first weights and activations are requested
+    // during the last pass over the current one, so HBM stays busy through the epilogue.
+    int gn = g + int(gridDim.x);
+    bool has_next = gn < b.total_items;
+    ItemCtx nxt = get_item(has_next ? gn : g);
+    bool pre = has_next && wave < nxt.slices;
+
+    f32x4 part[T];
+#pragma unroll
+    for (int t = 0; t < T; ++t) part[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    int slice = wave;
+    if (slice < cur.slices) {
+        do_pass(std::true_type{}, cur, nxt, pre, slice, part);
+        slice += NW;
+    }
+    for (;;) {
+        for (; slice < cur.slices; slice += NW)             // wave-uniform trip count
+            do_pass(std::false_type{}, cur, nxt, pre, slice, part);
+        if (wave >= cur.slices && pre) {                    // a wave with no slice of this item
+            issue_x(nxt, wave);
+#pragma unroll
+            for (int t = 0; t < T; ++t) issue_w(nxt, t, wave);
+        }
+        epilogue(cur, part);
+        if (!has_next) break;
+        cur = nxt;
+        g = gn;
+        gn = g + int(gridDim.x);
+        has_next = gn < b.total_items;
+        nxt = get_item(has_next ? gn : g);
+        pre = has_next && wave < nxt.slices;
+#pragma unroll
+        for (int t = 0; t < T; ++t) part[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        slice = wave;
+    }
 }
 
 using KernelFn = void (*)(GemvBatch);
 
-KernelFn pick_kernel(int T)
+template <bool MULTI>
+KernelFn pick_kernel_t(int T)
 {
     switch (T) {
-        case 1: return gemv_kernel<1>;
-        case 2: return gemv_kernel<2>;
-        case 3: return gemv_kernel<3>;
-        default: return gemv_kernel<4>;
+        case 1: return gemv_kernel<1, MULTI>;
+        case 2: return gemv_kernel<2, MULTI>;
+        case 3: return gemv_kernel<3, MULTI>;
+        default: return gemv_kernel<4, MULTI>;
     }
+}
+
+KernelFn pick_kernel(int T, bool multi)
+{
+    return multi ? pick_kernel_t<true>(T) : pick_kernel_t<false>(T);
 }
 
 int pow2_at_least(int v)
@@ -316,24 +430,75 @@ int pow2_at_least(int v)
     return r;
 }
 
-// Launch one batch (<= kMaxJobs jobs with group0 / groups filled in).
-hipError_t launch_batch(GemvBatch& b, int T, int NW, int total_groups, hipStream_t s)
+constexpr int kMaxLds = 8 * kWaveLds;    // most dynamic LDS any launch asks for (8 waves, one item)
+
+// Launch policy.  One 16-row job alone: 8-wave groups, one per CU, one item each while that
+// covers the matrix.  Several jobs: 4-wave groups (two passes over K = 4096), two per CU, so
+// that one group's wait for HBM overlaps the other's arithmetic, each looping over its items.
+struct GemvPolicy {
+    int nw_single = 8, nw_grouped = 4;
+    int grid_cap = 512;                 // resident workgroups of the grouped form (2 per CU)
+    int t_grouped = 0;                  // 0: pick from the tile count
+};
+GemvPolicy g_policy;
+
+// Launch one batch (<= kMaxJobs jobs, tiles / slices / M filled in): sets items and grid.
+hipError_t launch_batch(GemvBatch& b, bool grouped, hipStream_t s)
 {
-    KernelFn fn = pick_kernel(T);
-    // Groups of 5 or more waves need more than the default 64 KB of dynamic LDS; the
-    // attribute is set once per kernel instance (idempotent, so a race only repeats it).
-    static bool lds_raised[kTMax + 1];
-    if (!lds_raised[T]) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 8 * kWaveLds);
-        if (e != hipSuccess) return e;
-        lds_raised[T] = true;
+    const GemvPolicy pol = g_policy;
+    int64_t total_tiles = 0;
+    int max_slices = 1;
+    for (int j = 0; j < b.count; ++j) {
+        total_tiles += b.job[j].tiles;
+        if (b.job[j].slices > max_slices) max_slices = b.job[j].slices;
     }
-    hipLaunchKernelGGL(fn, dim3(total_groups), dim3(NW * 64), size_t(NW) * kWaveLds, s, b);
+    int NW = grouped ? pol.nw_grouped : pol.nw_single;
+    if (NW > max_slices) NW = max_slices;
+    int resident = grouped ? pol.grid_cap : (NW <= 4 ? 512 : 256);
+    int T = (grouped && pol.t_grouped) ? pol.t_grouped : int((total_tiles + resident - 1) / resident);
+    if (T > kTMax) T = kTMax;
+    if (T < 1) T = 1;
+    int total_items = 0;
+    for (int j = 0; j < kMaxJobs; ++j) b.item0[j] = 0x7fffffff;
+    for (int j = 0; j < b.count; ++j) {
+        b.job[j].items = (b.job[j].tiles + T - 1) / T;
+        b.item0[j] = total_items;
+        total_items += b.job[j].items;
+    }
+    b.total_items = total_items;
+    // Workgroups that loop keep the reduction area behind the staging area; with 8 waves
+    // that is more LDS than a CU has, so a looping launch uses 4-wave groups, two per CU.
+    if (total_items > resident && NW > 4) { NW = 4; resident = 512; }
+    const int grid = total_items < resident ? total_items : resident;
+    const bool looping = total_items > grid;
+    b.red_off = looping ? NW * kWaveLds : 0;
+    const int lds = NW * kWaveLds + (looping ? T * NW * 1024 : 0);
+    b.pad = 0;
+
+    const bool multi = b.count > 1;
+    KernelFn fn = pick_kernel(T, multi);
+    // More than the default 64 KB of dynamic LDS needs the attribute; it is set once per
+    // kernel instance (idempotent, so a race only repeats it).
+    static bool lds_raised[2][kTMax + 1];
+    if (!lds_raised[multi][T]) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds);
+        if (e != hipSuccess) return e;
+        lds_raised[multi][T] = true;
+    }
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(NW * 64), size_t(lds), s, b);
     return hipGetLastError();
 }
 
 }  // namespace
+
+#ifdef TL_DEV_HOOKS
+extern "C" void tl_dev_policy(int nw_single, int nw_grouped, int grid_cap, int t_grouped)
+{
+    g_policy.nw_single = nw_single; g_policy.nw_grouped = nw_grouped;
+    g_policy.grid_cap = grid_cap; g_policy.t_grouped = t_grouped;
+}
+#endif
 
 bool gemv_supports(int64_t M, int64_t N, int64_t K)
 {
@@ -344,24 +509,16 @@ bool gemv_supports(int64_t M, int64_t N, int64_t K)
 hipError_t launch_gemv_jobs(const GemmDesc* jobs, int count, hipStream_t s)
 {
     // A user job with M > 16 becomes ceil(M / 16) kernel jobs (blocks of 16 activation rows).
-    // One job alone gets 8-wave groups, one per CU, each holding up to 4 tiles; several jobs
-    // in one launch get 4-wave groups (two passes over K = 4096), two groups per CU, so that
-    // one group's wait for HBM overlaps the other's arithmetic (measured best of the
-    // (waves, tiles, groups) settings tried on the decode sweep).
     int64_t blocks_total = 0;
     for (int i = 0; i < count; ++i) blocks_total += (jobs[i].M + 15) / 16;
     const bool grouped = blocks_total > 1;
-    const int nw_cap = grouped ? 4 : 8;
-    const int t_cap = kTMax;
-    const int group_cap = 256;
 
     GemvBatch b;
     b.count = 0;
-    int total_groups = 0, Tmax = 1, NW = 1;
     auto flush = [&]() -> hipError_t {
         if (b.count == 0) return hipSuccess;
-        hipError_t e = launch_batch(b, Tmax, NW, total_groups, s);
-        b.count = 0; total_groups = 0; Tmax = 1; NW = 1;
+        hipError_t e = launch_batch(b, grouped, s);
+        b.count = 0;
         return e;
     };
     for (int i = 0; i < count; ++i) {
@@ -375,18 +532,10 @@ hipError_t launch_gemv_jobs(const GemmDesc* jobs, int count, hipStream_t s)
             j.Mrem = int(d.M - m0 < 16 ? d.M - m0 : 16);
             j.N = int(d.N); j.K = int(d.K);
             j.tiles = int((d.N + 15) / 16);
+            j.items = 0;
             j.slices = int((d.K + kSliceK - 1) / kSliceK);
             j.mr = pow2_at_least(j.Mrem);
-            j.pad = 0;
-            int groups = j.tiles < group_cap ? j.tiles : group_cap;
-            int T = (j.tiles + groups - 1) / groups;
-            if (T > t_cap) { T = t_cap; groups = (j.tiles + T - 1) / T; }
-            j.groups = groups;
-            j.group0 = total_groups;
-            total_groups += groups;
-            if (T > Tmax) Tmax = T;
-            const int nw = j.slices < nw_cap ? j.slices : nw_cap;
-            if (nw > NW) NW = nw;
+            j.pad[0] = j.pad[1] = 0;
             b.job[b.count++] = j;
             if (b.count == kMaxJobs) {
                 hipError_t e = flush();
