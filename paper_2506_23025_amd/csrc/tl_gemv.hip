@@ -405,6 +405,217 @@ gemv_kernel(GemvBatch b)
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Stream form of the kernel, for launches in which every job has K <= 512 * (waves per group):
+// wave w owns K slice w for good, so its activations are fetched and turned into MFMA operands
+// once, and all that moves afterwards is the weight stream.  A workgroup serves one job (its
+// index picks the job; GemvBatch::item0[j] is the first workgroup of job j) and walks a run of
+// consecutive items of it (GemvJob::pad: items per workgroup, and how many of the job's first
+// workgroups take one more).  While item i is decoded the loads of item i + 1 are in flight,
+// each tile waits only for its own two loads, and there is one LDS-only barrier per item.
+// The loop body holds nothing but weight loads and the output stores, which is what keeps the
+// compiler's wait counts exact; the last item is a second copy of the body without refills.
+template <int T, bool MULTI>
+__global__ void __launch_bounds__(512)
+gemv_stream_kernel(GemvBatch b)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int NW = blockDim.x >> 6;
+    // LDS of a wave (16 KB): activation rows while the operands are built; afterwards two tile
+    // regions at 0 and 2 KB, and from 4 KB two sets of T partial-sum tiles (1 KB each).
+    unsigned char* const my_lds = lds_raw + wave * kWaveLds;
+
+    const int lr = lane >> 3, lc = lane & 7;   // load mapping: row of the half tile, chunk of the slice
+    const int mi = lane & 15, mg = lane >> 4;  // MFMA mapping: row / activation column, k group
+    const uint32_t ww_off = uint32_t(lr) * 128u + (uint32_t(lc ^ lr) << 4);
+    const uint32_t wr_off0 = uint32_t(mi) * 128u + (uint32_t((mg) ^ (mi & 7)) << 4);
+    const uint32_t wr_off1 = uint32_t(mi) * 128u + (uint32_t((4 + mg) ^ (mi & 7)) << 4);
+
+    // ---- this workgroup's job and run of items ----------------------------------------------
+    ItemCtx J;
+    int ipg, plus;
+    if constexpr (MULTI) {
+        const JobTable table = load_table(lane);
+        J = load_item(table, int(blockIdx.x));             // idx: position among the job's workgroups
+        const unsigned long long m = __builtin_amdgcn_ballot_w64(int(blockIdx.x) >= table.item0) & 0xFFFFull;
+        const int ji = __builtin_popcountll(m) - 1;
+        ipg = int(__builtin_amdgcn_readlane(table.d[14], ji));
+        plus = int(__builtin_amdgcn_readlane(table.d[15], ji));
+    } else {
+        const GemvJob& G = b.job[0];
+        J.xb = reinterpret_cast<const unsigned char*>(G.x);
+        J.Wb = reinterpret_cast<const unsigned char*>(G.W);
+        J.y = G.y;
+        J.gamma = G.gamma;
+        J.Mrem = G.Mrem; J.MR = G.mr;
+        J.N = G.N; J.K = G.K;
+        J.row_bytes = uint32_t(G.K) >> 2;
+        J.chunks = G.K >> 6;
+        J.tiles = G.tiles; J.items = G.items; J.idx = int(blockIdx.x);
+        J.slices = G.slices;
+        ipg = G.pad[0]; plus = G.pad[1];
+    }
+    const int local = J.idx;
+    const int i0 = local * ipg + (local < plus ? local : plus);
+    const int n_items = ipg + (local < plus ? 1 : 0);
+    const bool active = wave < J.slices;
+
+    // chunk of this lane within the row, fixed for the whole kernel (slice = wave)
+    int chunk = wave * 8 + lc;
+    if (chunk >= J.chunks) chunk = 0;                      // past K: multiplied by zero activations
+    const uint32_t col_off = uint32_t(chunk) * 16u;
+    const bool ragged_n = (J.N & 15) != 0;
+    typedef const __attribute__((address_space(1))) u32x4* gptr;
+
+    u32x4 wreg[T][2];
+    auto issue_w = [&](int idx, int t) {
+        int tile = idx + t * J.items;
+        if (tile >= J.tiles) tile = J.tiles - 1;           // loaded again, never used
+        const unsigned char* tb = J.Wb + size_t(tile) * 16u * J.row_bytes;
+        uint32_t off0 = uint32_t(lr) * J.row_bytes + col_off;
+        uint32_t off1 = off0 + 8u * J.row_bytes;
+        if (ragged_n && tile == J.tiles - 1) {             // scalar branch: rows past N read row N-1
+            const int last = J.N - 1 - tile * 16;
+            off0 = uint32_t(lr < last ? lr : last) * J.row_bytes + col_off;
+            off1 = uint32_t(lr + 8 < last ? lr + 8 : last) * J.row_bytes + col_off;
+        }
+        wreg[t][0] = __builtin_nontemporal_load((gptr)(tb + off0));
+        wreg[t][1] = __builtin_nontemporal_load((gptr)(tb + off1));
+    };
+
+    uint32_t breg[2][4][8];                    // this wave's activations as MFMA B operands
+    f32x4 nsx = f32x4{0.f, 0.f, 0.f, 0.f};     // -2^-20 sum_k x[m][k] over the slice, as an accumulator
+    if (active) {
+        // activation rows by LDS-DMA, swizzled: lane l fetches piece l ^ (r & 7) of row r
+        for (int r = 0; r < J.MR; ++r) {
+            const int rr = r < J.Mrem ? r : J.Mrem - 1;
+            const int kx = wave * kSliceK + ((lane ^ (r & 7)) << 3);
+            if (kx < J.K) {
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void*)(J.xb + size_t(rr) * J.K * 2 + uint32_t(kx) * 2u),
+                    (__attribute__((address_space(3))) void*)(my_lds + r * 1024),
+                    16, 0, 0);
+            } else {
+                *reinterpret_cast<u32x4*>(my_lds + r * 1024 + (uint32_t(lane) << 4)) = u32x4{0u, 0u, 0u, 0u};
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < T; ++t) issue_w(i0, t);
+        // the compiler does not track LDS-DMA: wait until only the 2T weight loads are outstanding
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * T));
+        const int xrow = mi & (J.MR - 1);
+        const uint32_t xr_off = uint32_t(xrow) * 1024u + uint32_t(mg) * 128u;
+        const uint32_t sw = uint32_t(xrow & 7);
+        // breg[h][wd][e]: (x[k], x[k + 8]) with k = slice0 + 64 (4h + g) + 16 wd + e
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int wd = 0; wd < 4; ++wd) {
+                const u32x4 lo = *reinterpret_cast<const u32x4*>(
+                    my_lds + xr_off + h * 512 + ((uint32_t(2 * wd) ^ sw) << 4));
+                const u32x4 hi = *reinterpret_cast<const u32x4*>(
+                    my_lds + xr_off + h * 512 + ((uint32_t(2 * wd + 1) ^ sw) << 4));
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    breg[h][wd][2 * r] = __builtin_amdgcn_perm(hi[r], lo[r], 0x05040100u);
+                    breg[h][wd][2 * r + 1] = __builtin_amdgcn_perm(hi[r], lo[r], 0x07060302u);
+                }
+            }
+        const uint32_t c = 0x80108010u;                   // fp16 pair of -2^-20
+        const u32x4 a = u32x4{c, c, c, c};
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const u32x4 bb = u32x4{breg[h][0][e], breg[h][1][e], breg[h][2][e], breg[h][3][e]};
+                nsx = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), as_f16x8(bb), nsx, 0, 0, 0);
+            }
+    } else {
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int wd = 0; wd < 4; ++wd)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) breg[h][wd][e] = 0u;
+    }
+
+    // One item: tile t goes through LDS region t & 1 into MFMA order, is decoded and multiplied;
+    // REFILL: its registers are loaded again at once for item idx + 1.
+    auto item = [&](auto refill_tag, int idx, int parity) {
+        constexpr bool REFILL = decltype(refill_tag)::value;
+        f32x4 part[T];
+#pragma unroll
+        for (int t = 0; t < T; ++t) part[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (active) {
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                unsigned char* const reg_t = my_lds + (t & 1) * 2048;
+                *reinterpret_cast<u32x4*>(reg_t + ww_off) = wreg[t][0];
+                *reinterpret_cast<u32x4*>(reg_t + 1024 + ww_off) = wreg[t][1];
+                if constexpr (REFILL) issue_w(idx + 1, t);
+                if (idx + t * J.items < J.tiles) {         // scalar: tiles past the end are skipped
+                    f32x4 acc[3] = {nsx, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const u32x4 wv = *reinterpret_cast<const u32x4*>(reg_t + (h ? wr_off1 : wr_off0));
+                        const u32x4 sh[3] = {wv << 4, wv >> 2, wv >> 8};
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            const int j = e % 3;
+                            const uint32_t mask = 0x00300030u << (2 * j);
+                            const u32x4 a = sh[e / 3] & mask;
+                            const u32x4 bb = u32x4{breg[h][0][e], breg[h][1][e], breg[h][2][e], breg[h][3][e]};
+                            acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), as_f16x8(bb), acc[j], 0, 0, 0);
+                        }
+                    }
+                    part[t] += acc[0] * 1048576.f + acc[1] * 262144.f + acc[2] * 65536.f;
+                }
+            }
+        }
+        // split-K: partial sums into this wave's set `parity`, one barrier, fixed-order sum.
+        // The other set is still being read by waves that lag one item behind, never more:
+        // they must pass this item's barrier before anybody writes that set again.
+        unsigned char* const red = my_lds + 4096 + parity * (T * 1024);
+#pragma unroll
+        for (int t = 0; t < T; ++t) reinterpret_cast<f32x4*>(red + t * 1024)[lane] = part[t];
+        __builtin_amdgcn_s_waitcnt(0xF | (0x3 << 14) | (0x7 << 4));     // lgkmcnt(0): LDS only, loads stay in flight
+        __builtin_amdgcn_s_barrier();
+        if (const int o = threadIdx.x; o < T * 64) {       // T <= waves: one output quad per thread
+            const int t = o >> 6;
+            const int l = o & 63;
+            const int tile = idx + t * J.items;
+            f32x4 v[8];
+#pragma unroll
+            for (int w = 0; w < 8; ++w)
+                v[w] = (w < NW) ? reinterpret_cast<const f32x4*>(lds_raw + w * kWaveLds + 4096 + parity * (T * 1024) + t * 1024)[l]
+                                : f32x4{0.f, 0.f, 0.f, 0.f};
+            const f32x4 s = ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
+            const int n = tile * 16 + 4 * (l >> 4);
+            if (tile < J.tiles && (l & 15) < J.Mrem) {
+                typedef __attribute__((address_space(1))) __half* gh_ptr;
+                gh_ptr dst = (gh_ptr)(J.y + size_t(l & 15) * J.N + n);
+                const float gamma = J.gamma;
+                if (n + 3 < J.N && (J.N & 3) == 0) {       // four consecutive n: one 8-byte store
+                    const f16x2 lo = {(_Float16)(gamma * s[0]), (_Float16)(gamma * s[1])};
+                    const f16x2 hi = {(_Float16)(gamma * s[2]), (_Float16)(gamma * s[3])};
+                    *(__attribute__((address_space(1))) u32x2*)dst =
+                        u32x2{__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        if (n + r < J.N) *(__attribute__((address_space(1))) _Float16*)(dst + r) = (_Float16)(gamma * s[r]);
+                }
+            }
+        }
+    };
+
+    int i = 0;
+    for (; i + 1 < n_items; ++i) item(std::true_type{}, i0 + i, i & 1);
+    item(std::false_type{}, i0 + i, i & 1);
+}
+
 using KernelFn = void (*)(GemvBatch);
 
 template <bool MULTI>
@@ -423,6 +634,22 @@ KernelFn pick_kernel(int T, bool multi)
     return multi ? pick_kernel_t<true>(T) : pick_kernel_t<false>(T);
 }
 
+template <bool MULTI>
+KernelFn pick_stream_t(int T)
+{
+    switch (T) {
+        case 1: return gemv_stream_kernel<1, MULTI>;
+        case 2: return gemv_stream_kernel<2, MULTI>;
+        case 3: return gemv_stream_kernel<3, MULTI>;
+        default: return gemv_stream_kernel<4, MULTI>;
+    }
+}
+
+KernelFn pick_stream(int T, bool multi)
+{
+    return multi ? pick_stream_t<true>(T) : pick_stream_t<false>(T);
+}
+
 int pow2_at_least(int v)
 {
     int r = 1;
@@ -439,8 +666,76 @@ struct GemvPolicy {
     int nw_single = 8, nw_grouped = 4;
     int grid_cap = 512;                 // resident workgroups of the grouped form (2 per CU)
     int t_grouped = 0;                  // 0: pick from the tile count
+    int stream = 3;                     // bit 0: stream form for one job, bit 1: for several
+    int stream_groups = 256;            // workgroups of the stream form (one per CU)
 };
 GemvPolicy g_policy;
+
+constexpr int kStreamMaxSlices = 8;     // K <= 4096: every wave of an 8-wave group owns one slice
+
+// Stream form: one job per workgroup, a run of consecutive items each.  Workgroups are dealt
+// out to the jobs in proportion to their items; then the job with the longest runs gets the
+// spare ones, one by one, so that the longest run is as short as the group count allows.
+hipError_t launch_stream(GemvBatch& b, int max_slices, int64_t total_tiles, hipStream_t s)
+{
+    const GemvPolicy pol = g_policy;
+    const int NW = max_slices;
+    int T = int((total_tiles + pol.stream_groups - 1) / pol.stream_groups);
+    if (T > kTMax) T = kTMax;
+    if (T > NW) T = NW;                  // the epilogue gives every thread at most one output quad
+    if (T < 1) T = 1;
+    int total_items = 0;
+    for (int j = 0; j < b.count; ++j) {
+        b.job[j].items = (b.job[j].tiles + T - 1) / T;
+        total_items += b.job[j].items;
+    }
+    const int G = total_items < pol.stream_groups ? total_items : pol.stream_groups;
+    int wg[kMaxJobs];
+    int used = 0;
+    for (int j = 0; j < b.count; ++j) {
+        int w = int(int64_t(b.job[j].items) * G / total_items);
+        if (w < 1) w = 1;
+        wg[j] = w;
+        used += w;
+    }
+    auto run_len = [&](int j) { return (b.job[j].items + wg[j] - 1) / wg[j]; };
+    while (used < G) {                                     // spare groups: shorten the longest run
+        int best = -1;
+        for (int j = 0; j < b.count; ++j)
+            if (wg[j] < b.job[j].items && (best < 0 || run_len(j) > run_len(best))) best = j;
+        if (best < 0) break;
+        ++wg[best]; ++used;
+    }
+    while (used > G) {                                     // over by rounding up to 1: lengthen the shortest
+        int best = -1;
+        for (int j = 0; j < b.count; ++j)
+            if (wg[j] > 1 && (best < 0 || run_len(j) < run_len(best))) best = j;
+        if (best < 0) break;
+        --wg[best]; --used;
+    }
+    for (int j = 0; j < kMaxJobs; ++j) b.item0[j] = 0x7fffffff;
+    int grid = 0;
+    for (int j = 0; j < b.count; ++j) {
+        b.item0[j] = grid;
+        b.job[j].pad[0] = b.job[j].items / wg[j];
+        b.job[j].pad[1] = b.job[j].items % wg[j];
+        grid += wg[j];
+    }
+    b.total_items = total_items;
+    b.red_off = 0;
+    b.pad = 0;
+    const bool multi = b.count > 1;
+    KernelFn fn = pick_stream(T, multi);
+    static bool lds_raised[2][kTMax + 1];
+    if (!lds_raised[multi][T]) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 8 * kWaveLds);
+        if (e != hipSuccess) return e;
+        lds_raised[multi][T] = true;
+    }
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(NW * 64), size_t(NW) * kWaveLds, s, b);
+    return hipGetLastError();
+}
 
 // Launch one batch (<= kMaxJobs jobs, tiles / slices / M filled in): sets items and grid.
 hipError_t launch_batch(GemvBatch& b, bool grouped, hipStream_t s)
@@ -452,6 +747,8 @@ hipError_t launch_batch(GemvBatch& b, bool grouped, hipStream_t s)
         total_tiles += b.job[j].tiles;
         if (b.job[j].slices > max_slices) max_slices = b.job[j].slices;
     }
+    if (max_slices <= kStreamMaxSlices && (pol.stream & (b.count > 1 ? 2 : 1)))
+        return launch_stream(b, max_slices, total_tiles, s);
     int NW = grouped ? pol.nw_grouped : pol.nw_single;
     if (NW > max_slices) NW = max_slices;
     int resident = grouped ? pol.grid_cap : (NW <= 4 ? 512 : 256);
@@ -497,6 +794,10 @@ extern "C" void tl_dev_policy(int nw_single, int nw_grouped, int grid_cap, int t
 {
     g_policy.nw_single = nw_single; g_policy.nw_grouped = nw_grouped;
     g_policy.grid_cap = grid_cap; g_policy.t_grouped = t_grouped;
+}
+extern "C" void tl_dev_stream(int stream, int groups)
+{
+    g_policy.stream = stream; g_policy.stream_groups = groups;
 }
 #endif
 
