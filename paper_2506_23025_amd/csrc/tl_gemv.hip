@@ -410,8 +410,8 @@ gemv_kernel(GemvBatch b)
 // wave w owns K slice w for good, so its activations are fetched and turned into MFMA operands
 // once, and all that moves afterwards is the weight stream.  A workgroup serves one job (its
 // index picks the job; GemvBatch::item0[j] is the first workgroup of job j) and walks a run of
-// consecutive items of it (GemvJob::pad: items per workgroup, and how many of the job's first
-// workgroups take one more).  While item i is decoded the loads of item i + 1 are in flight,
+// consecutive tiles of it, T at a time (GemvJob::pad: tiles per workgroup, and how many of the
+// job's first workgroups take one more).  While item i is decoded the loads of item i + 1 are in flight,
 // each tile waits only for its own two loads, and there is one LDS-only barrier per item.
 // The loop body holds nothing but weight loads and the output stores, which is what keeps the
 // compiler's wait counts exact; the last item is a second copy of the body without refills.
@@ -458,8 +458,9 @@ gemv_stream_kernel(GemvBatch b)
         ipg = G.pad[0]; plus = G.pad[1];
     }
     const int local = J.idx;
-    const int i0 = local * ipg + (local < plus ? local : plus);
-    const int n_items = ipg + (local < plus ? 1 : 0);
+    const int tile0 = local * ipg + (local < plus ? local : plus);      // first tile of the run
+    const int tile_end = tile0 + ipg + (local < plus ? 1 : 0);
+    const int n_items = (tile_end - tile0 + T - 1) / T;
     const bool active = wave < J.slices;
 
     // chunk of this lane within the row, fixed for the whole kernel (slice = wave)
@@ -470,17 +471,14 @@ gemv_stream_kernel(GemvBatch b)
     typedef const __attribute__((address_space(1))) u32x4* gptr;
 
     u32x4 wreg[T][2];
-    auto issue_w = [&](int idx, int t) {
-        int tile = idx + t * J.items;
-        if (tile >= J.tiles) tile = J.tiles - 1;           // loaded again, never used
+    auto issue_w = [&](int first, int t) {
+        int tile = first + t;
+        if (tile >= tile_end) tile = tile_end - 1;         // past the run: its last tile again, never stored
         const unsigned char* tb = J.Wb + size_t(tile) * 16u * J.row_bytes;
-        uint32_t off0 = uint32_t(lr) * J.row_bytes + col_off;
-        uint32_t off1 = off0 + 8u * J.row_bytes;
-        if (ragged_n && tile == J.tiles - 1) {             // scalar branch: rows past N read row N-1
-            const int last = J.N - 1 - tile * 16;
-            off0 = uint32_t(lr < last ? lr : last) * J.row_bytes + col_off;
-            off1 = uint32_t(lr + 8 < last ? lr + 8 : last) * J.row_bytes + col_off;
-        }
+        // rows past N read row N-1 (no branch: the loop body stays one scheduling region)
+        const int last = (ragged_n && tile == J.tiles - 1) ? J.N - 1 - tile * 16 : 15;
+        const uint32_t off0 = uint32_t(lr < last ? lr : last) * J.row_bytes + col_off;
+        const uint32_t off1 = uint32_t(lr + 8 < last ? lr + 8 : last) * J.row_bytes + col_off;
         wreg[t][0] = __builtin_nontemporal_load((gptr)(tb + off0));
         wreg[t][1] = __builtin_nontemporal_load((gptr)(tb + off1));
     };
@@ -502,7 +500,7 @@ gemv_stream_kernel(GemvBatch b)
             }
         }
 #pragma unroll
-        for (int t = 0; t < T; ++t) issue_w(i0, t);
+        for (int t = 0; t < T; ++t) issue_w(tile0, t);
         // the compiler does not track LDS-DMA: wait until only the 2T weight loads are outstanding
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * T));
         const int xrow = mi & (J.MR - 1);
@@ -541,9 +539,10 @@ gemv_stream_kernel(GemvBatch b)
                 for (int e = 0; e < 8; ++e) breg[h][wd][e] = 0u;
     }
 
-    // One item: tile t goes through LDS region t & 1 into MFMA order, is decoded and multiplied;
-    // REFILL: its registers are loaded again at once for item idx + 1.
-    auto item = [&](auto refill_tag, int idx, int parity) {
+    // One item (tiles first .. first + T - 1): tile t goes through LDS region t & 1 into MFMA
+    // order, is decoded and multiplied; REFILL: its registers are loaded again at once for the
+    // next item.  Tiles past the run are computed from whatever was loaded and never stored.
+    auto item = [&](auto refill_tag, int first, int parity) {
         constexpr bool REFILL = decltype(refill_tag)::value;
         f32x4 part[T];
 #pragma unroll
@@ -554,8 +553,8 @@ gemv_stream_kernel(GemvBatch b)
                 unsigned char* const reg_t = my_lds + (t & 1) * 2048;
                 *reinterpret_cast<u32x4*>(reg_t + ww_off) = wreg[t][0];
                 *reinterpret_cast<u32x4*>(reg_t + 1024 + ww_off) = wreg[t][1];
-                if constexpr (REFILL) issue_w(idx + 1, t);
-                if (idx + t * J.items < J.tiles) {         // scalar: tiles past the end are skipped
+                if constexpr (REFILL) issue_w(first + T, t);
+                {
                     f32x4 acc[3] = {nsx, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
                     for (int h = 0; h < 2; ++h) {
@@ -585,7 +584,7 @@ gemv_stream_kernel(GemvBatch b)
         if (const int o = threadIdx.x; o < T * 64) {       // T <= waves: one output quad per thread
             const int t = o >> 6;
             const int l = o & 63;
-            const int tile = idx + t * J.items;
+            const int tile = first + t;
             f32x4 v[8];
 #pragma unroll
             for (int w = 0; w < 8; ++w)
@@ -593,7 +592,7 @@ gemv_stream_kernel(GemvBatch b)
                                 : f32x4{0.f, 0.f, 0.f, 0.f};
             const f32x4 s = ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
             const int n = tile * 16 + 4 * (l >> 4);
-            if (tile < J.tiles && (l & 15) < J.Mrem) {
+            if (tile < tile_end && (l & 15) < J.Mrem) {
                 typedef __attribute__((address_space(1))) __half* gh_ptr;
                 gh_ptr dst = (gh_ptr)(J.y + size_t(l & 15) * J.N + n);
                 const float gamma = J.gamma;
@@ -612,8 +611,8 @@ gemv_stream_kernel(GemvBatch b)
     };
 
     int i = 0;
-    for (; i + 1 < n_items; ++i) item(std::true_type{}, i0 + i, i & 1);
-    item(std::false_type{}, i0 + i, i & 1);
+    for (; i + 1 < n_items; ++i) item(std::true_type{}, tile0 + i * T, i & 1);
+    item(std::false_type{}, tile0 + i * T, i & 1);
 }
 
 using KernelFn = void (*)(GemvBatch);
@@ -673,36 +672,31 @@ GemvPolicy g_policy;
 
 constexpr int kStreamMaxSlices = 8;     // K <= 4096: every wave of an 8-wave group owns one slice
 
-// Stream form: one job per workgroup, a run of consecutive items each.  Workgroups are dealt
-// out to the jobs in proportion to their items; then the job with the longest runs gets the
+// Stream form: one job per workgroup, a run of consecutive tiles each.  Workgroups are dealt
+// out to the jobs in proportion to their tiles; then the job with the longest runs gets the
 // spare ones, one by one, so that the longest run is as short as the group count allows.
 hipError_t launch_stream(GemvBatch& b, int max_slices, int64_t total_tiles, hipStream_t s)
 {
     const GemvPolicy pol = g_policy;
     const int NW = max_slices;
-    int T = int((total_tiles + pol.stream_groups - 1) / pol.stream_groups);
+    const int G = total_tiles < pol.stream_groups ? int(total_tiles) : pol.stream_groups;
+    int T = int((total_tiles + G - 1) / G);
     if (T > kTMax) T = kTMax;
     if (T > NW) T = NW;                  // the epilogue gives every thread at most one output quad
     if (T < 1) T = 1;
-    int total_items = 0;
-    for (int j = 0; j < b.count; ++j) {
-        b.job[j].items = (b.job[j].tiles + T - 1) / T;
-        total_items += b.job[j].items;
-    }
-    const int G = total_items < pol.stream_groups ? total_items : pol.stream_groups;
     int wg[kMaxJobs];
     int used = 0;
     for (int j = 0; j < b.count; ++j) {
-        int w = int(int64_t(b.job[j].items) * G / total_items);
+        int w = int(int64_t(b.job[j].tiles) * G / total_tiles);
         if (w < 1) w = 1;
         wg[j] = w;
         used += w;
     }
-    auto run_len = [&](int j) { return (b.job[j].items + wg[j] - 1) / wg[j]; };
+    auto run_len = [&](int j) { return (b.job[j].tiles + wg[j] - 1) / wg[j]; };
     while (used < G) {                                     // spare groups: shorten the longest run
         int best = -1;
         for (int j = 0; j < b.count; ++j)
-            if (wg[j] < b.job[j].items && (best < 0 || run_len(j) > run_len(best))) best = j;
+            if (wg[j] < b.job[j].tiles && (best < 0 || run_len(j) > run_len(best))) best = j;
         if (best < 0) break;
         ++wg[best]; ++used;
     }
@@ -717,10 +711,12 @@ hipError_t launch_stream(GemvBatch& b, int max_slices, int64_t total_tiles, hipS
     int grid = 0;
     for (int j = 0; j < b.count; ++j) {
         b.item0[j] = grid;
-        b.job[j].pad[0] = b.job[j].items / wg[j];
-        b.job[j].pad[1] = b.job[j].items % wg[j];
+        b.job[j].items = 0;
+        b.job[j].pad[0] = b.job[j].tiles / wg[j];
+        b.job[j].pad[1] = b.job[j].tiles % wg[j];
         grid += wg[j];
     }
+    const int total_items = 0;
     b.total_items = total_items;
     b.red_off = 0;
     b.pad = 0;
