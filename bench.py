@@ -36,8 +36,8 @@ def algorithmic_bytes(M, N, K):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--mode", choices=("sweep", "dominant", "copy"), default="sweep",
                     help="sweep: the benchmark; dominant / copy: run only the dominant kernel, or only "
@@ -199,7 +199,7 @@ def main():
         for line in open(tpath):
             if line.startswith("grouped_sweep_bytes_per_launch"):
                 traffic = float(line.split("=")[1])
-    roofline = dict(bound="hbm", kernel="gemv_kernel<4>, grouped launch of the ten GEMMs of a step",
+    roofline = dict(bound="hbm", kernel="gemv_stream_kernel<4, true>, grouped launch of the ten GEMMs of a step",
                     achieved=round(step_bytes / us_launch / 1e3, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(step_bytes / us_launch / 1e3 / HBM_PEAK_GBS, 4),
                     bytes_per_launch=step_bytes, us_per_launch=round(us_launch, 3), traffic=traffic)

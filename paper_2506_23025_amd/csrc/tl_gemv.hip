@@ -810,9 +810,12 @@ hipError_t launch_gemv_jobs(const GemmDesc* jobs, int count, hipStream_t s)
     for (int i = 0; i < count; ++i) blocks_total += (jobs[i].M + 15) / 16;
     const bool grouped = blocks_total > 1;
 
-    GemvBatch b;
-    b.count = 0;
-    auto flush = [&]() -> hipError_t {
+    // Two batches fill side by side: jobs the stream form takes (K <= 4096) and the others,
+    // so that one long-K job does not pull a whole block of layers onto the general kernel.
+    GemvBatch bs, bg;
+    bs.count = 0;
+    bg.count = 0;
+    auto flush = [&](GemvBatch& b) -> hipError_t {
         if (b.count == 0) return hipSuccess;
         hipError_t e = launch_batch(b, grouped, s);
         b.count = 0;
@@ -833,14 +836,17 @@ hipError_t launch_gemv_jobs(const GemmDesc* jobs, int count, hipStream_t s)
             j.slices = int((d.K + kSliceK - 1) / kSliceK);
             j.mr = pow2_at_least(j.Mrem);
             j.pad[0] = j.pad[1] = 0;
+            GemvBatch& b = j.slices <= kStreamMaxSlices ? bs : bg;
             b.job[b.count++] = j;
             if (b.count == kMaxJobs) {
-                hipError_t e = flush();
+                hipError_t e = flush(b);
                 if (e != hipSuccess) return e;
             }
         }
     }
-    return flush();
+    hipError_t e = flush(bs);
+    if (e != hipSuccess) return e;
+    return flush(bg);
 }
 
 hipError_t launch_gemv(const __half* x, const uint32_t* Wp, float gamma, __half* y,

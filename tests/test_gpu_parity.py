@@ -243,6 +243,44 @@ def test_grouped_matches_oracle_and_single_calls():
         assert_close(y1, y.astype(np.float64), x, g, "grouped vs single")
 
 
+def test_grouped_many_small_k_jobs():
+    # more jobs than one launch carries, all of them short enough in K for the kernel form that
+    # keeps a wave's activations in registers: ragged N and M, a K slice that ends inside a
+    # 512-block, one-tile jobs next to jobs that give every workgroup a run of several items
+    import torch
+    specs = [(1, 14336, 4096), (16, 4099, 4096), (3, 17, 576), (9, 1, 64), (2, 300, 1024), (16, 16, 4096),
+             (5, 2048, 2048), (1, 12288, 4096), (12, 33, 3136), (4, 640, 512), (1, 4096, 4096), (7, 95, 128),
+             (16, 22016, 4096), (2, 48, 2048), (13, 1000, 1600), (1, 31, 4096), (8, 777, 960), (6, 16, 64),
+             (24, 130, 1024), (1, 5000, 2560)]
+    host, dev, jobs = [], [], []
+    for i, (M, N, K) in enumerate(specs):
+        x, W, g = si.layer(7100 + i, M, N, K)
+        Wp = tl.tl_pack_2bit(W)
+        xd, wd = to_dev(x.view(np.int16)), dev_u32(Wp)
+        yd = torch.full((M, N), -21555, dtype=torch.int16, device="cuda")
+        host.append((x, W, Wp, g))
+        dev.append((xd, wd, yd))
+        jobs.append((xd, wd, si.gamma_bits(g), yd, M, N, K))
+    tl.tl_ternary_gemm_grouped(jobs)
+    torch.cuda.synchronize()
+    first = [yd.cpu().numpy().copy() for _, _, yd in dev]
+    for (M, N, K), (x, W, Wp, g), y16 in zip(specs, host, first):
+        y = y16.view(np.float16)
+        if N * K <= 4096 * 4096:
+            assert_close(y, oracle.gemm_packed2(x, Wp, g, K), x, g, f"grouped {M}x{N}x{K}")
+        else:
+            cols = np.sort(np.random.default_rng(3).choice(N, 512, replace=False))
+            assert_close(y[:, cols], oracle.gemm(x, np.ascontiguousarray(W[cols]), g), x, g,
+                         f"grouped {M}x{N}x{K} sampled")
+    # same call again: bit for bit the same
+    for _, _, yd in dev:
+        yd.fill_(-21555)
+    tl.tl_ternary_gemm_grouped(jobs)
+    torch.cuda.synchronize()
+    for (M, N, K), y16, (_, _, yd) in zip(specs, first, dev):
+        assert np.array_equal(y16, yd.cpu().numpy()), f"grouped {M}x{N}x{K} not deterministic"
+
+
 def test_grouped_empty_and_errors():
     L = tl.raw()
     assert L.tl_ternary_gemm_grouped(None, 0, None) == tl.TL_OK
