@@ -405,6 +405,13 @@ gemv_kernel(GemvBatch b)
     }
 }
 
+// LDS per wave of the stream form: 16 KB of activation staging, or two tile regions and two
+// sets of T partial-sum tiles, whichever is more.
+constexpr int stream_wave_lds(int T)
+{
+    return 4096 + 2 * T * 1024 > kWaveLds ? 4096 + 2 * T * 1024 : kWaveLds;
+}
+
 // ------------------------------------------------------------------------------------------
 // Stream form of the kernel, for launches in which every job has K <= 512 * (waves per group):
 // wave w owns K slice w for good, so its activations are fetched and turned into MFMA operands
@@ -423,9 +430,10 @@ gemv_stream_kernel(GemvBatch b)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int NW = blockDim.x >> 6;
-    // LDS of a wave (16 KB): activation rows while the operands are built; afterwards two tile
+    // LDS of a wave: activation rows (16 KB) while the operands are built; afterwards two tile
     // regions at 0 and 2 KB, and from 4 KB two sets of T partial-sum tiles (1 KB each).
-    unsigned char* const my_lds = lds_raw + wave * kWaveLds;
+    constexpr int kStride = stream_wave_lds(T);
+    unsigned char* const my_lds = lds_raw + wave * kStride;
 
     const int lr = lane >> 3, lc = lane & 7;   // load mapping: row of the half tile, chunk of the slice
     const int mi = lane & 15, mg = lane >> 4;  // MFMA mapping: row / activation column, k group
@@ -554,22 +562,26 @@ gemv_stream_kernel(GemvBatch b)
                 *reinterpret_cast<u32x4*>(reg_t + ww_off) = wreg[t][0];
                 *reinterpret_cast<u32x4*>(reg_t + 1024 + ww_off) = wreg[t][1];
                 if constexpr (REFILL) issue_w(first + T, t);
-                {
+                if (REFILL || first + t < tile_end) {      // the last item may be short
                     f32x4 acc[3] = {nsx, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
                     for (int h = 0; h < 2; ++h) {
                         const u32x4 wv = *reinterpret_cast<const u32x4*>(reg_t + (h ? wr_off1 : wr_off0));
-                        const u32x4 sh[3] = {wv << 4, wv >> 2, wv >> 8};
+                        // element e of each half-word sits at bits 2e, 2e+1; the mantissa bits
+                        // 4..9 (classes 0..2 -> accumulators) hold e = 2,3,4 as loaded, e = 0,1
+                        // after << 4 and e = 5,6,7 after >> 6
+                        const u32x4 sh[3] = {wv << 4, wv, wv >> 6};
 #pragma unroll
                         for (int e = 0; e < 8; ++e) {
-                            const int j = e % 3;
+                            const int src = e < 2 ? 0 : (e < 5 ? 1 : 2);
+                            const int j = e < 2 ? e : (e < 5 ? e - 2 : e - 5);
                             const uint32_t mask = 0x00300030u << (2 * j);
-                            const u32x4 a = sh[e / 3] & mask;
+                            const u32x4 a = sh[src] & mask;
                             const u32x4 bb = u32x4{breg[h][0][e], breg[h][1][e], breg[h][2][e], breg[h][3][e]};
                             acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), as_f16x8(bb), acc[j], 0, 0, 0);
                         }
                     }
-                    part[t] += acc[0] * 1048576.f + acc[1] * 262144.f + acc[2] * 65536.f;
+                    part[t] = acc[0] * 1048576.f + acc[1] * 262144.f + acc[2] * 65536.f;
                 }
             }
         }
@@ -588,7 +600,7 @@ gemv_stream_kernel(GemvBatch b)
             f32x4 v[8];
 #pragma unroll
             for (int w = 0; w < 8; ++w)
-                v[w] = (w < NW) ? reinterpret_cast<const f32x4*>(lds_raw + w * kWaveLds + 4096 + parity * (T * 1024) + t * 1024)[l]
+                v[w] = (w < NW) ? reinterpret_cast<const f32x4*>(lds_raw + w * kStride + 4096 + parity * (T * 1024) + t * 1024)[l]
                                 : f32x4{0.f, 0.f, 0.f, 0.f};
             const f32x4 s = ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
             const int n = tile * 16 + 4 * (l >> 4);
@@ -680,8 +692,8 @@ hipError_t launch_stream(GemvBatch& b, int max_slices, int64_t total_tiles, hipS
     const GemvPolicy pol = g_policy;
     const int NW = max_slices;
     const int G = total_tiles < pol.stream_groups ? int(total_tiles) : pol.stream_groups;
-    int T = int((total_tiles + G - 1) / G);
-    if (T > kTMax) T = kTMax;
+    int T = int((total_tiles + G - 1) / G);  // tiles per item: the whole run if it is short
+    if (T > kTMax) T = kTMax;            // (8 tiles per item measured slower: 23.9 against 21.4 us)
     if (T > NW) T = NW;                  // the epilogue gives every thread at most one output quad
     if (T < 1) T = 1;
     int wg[kMaxJobs];
@@ -725,11 +737,11 @@ hipError_t launch_stream(GemvBatch& b, int max_slices, int64_t total_tiles, hipS
     static bool lds_raised[2][kTMax + 1];
     if (!lds_raised[multi][T]) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 8 * kWaveLds);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 8 * stream_wave_lds(T));
         if (e != hipSuccess) return e;
         lds_raised[multi][T] = true;
     }
-    hipLaunchKernelGGL(fn, dim3(grid), dim3(NW * 64), size_t(NW) * kWaveLds, s, b);
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(NW * 64), size_t(NW) * stream_wave_lds(T), s, b);
     return hipGetLastError();
 }
 
@@ -791,7 +803,7 @@ extern "C" void tl_dev_policy(int nw_single, int nw_grouped, int grid_cap, int t
     g_policy.nw_single = nw_single; g_policy.nw_grouped = nw_grouped;
     g_policy.grid_cap = grid_cap; g_policy.t_grouped = t_grouped;
 }
-extern "C" void tl_dev_stream(int stream, int groups)
+extern "C" void tl_dev_stream(int stream, int groups, int)
 {
     g_policy.stream = stream; g_policy.stream_groups = groups;
 }
