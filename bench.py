@@ -24,6 +24,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = 2500.0          # dense fp16
 PAPER_CONTEXT = ("paper (arXiv 2506.23025): up to 5x end-to-end generation speed-up over PyTorch FP16 "
                  "on one NVIDIA L40S at 64 input / 64 output tokens; no absolute kernel figures published")
 
@@ -39,9 +40,10 @@ def main():
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--mode", choices=("sweep", "dominant", "copy"), default="sweep",
-                    help="sweep: the benchmark; dominant / copy: run only the dominant kernel, or only "
-                         "the plain copy probe, `steps` times (for rocprofv3 counter collection)")
+    ap.add_argument("--mode", choices=("sweep", "dominant", "copy", "prefill"), default="sweep",
+                    help="sweep: the benchmark; dominant / copy / prefill: run only the dominant kernel, "
+                         "only the plain copy probe, or only the large-M kernel at M = 2048, `steps` times "
+                         "(for rocprofv3 counter collection)")
     ap.add_argument("--no-per-call", action="store_true", help="skip the ten-separate-calls measurements")
     ap.add_argument("--eager", action="store_true",
                     help="launch every call from the host instead of replaying a captured HIP graph")
@@ -136,6 +138,30 @@ def main():
                           "algorithmic_bytes_per_launch": step_bytes}))
         return
 
+    # large-M inputs: 4096 -> 14336 at the prefill batch sizes (MFMA-bound leg of the metric)
+    pre_name = "mlp_up_8b"
+    pre_N = layers[pre_name]["N"]
+    pre_M = si.PREFILL_M
+    pre_x = torch.from_numpy(si.activations(rng, max(pre_M), K).view(np.int16)).to(dev)
+    pre_y = torch.empty((max(pre_M), pre_N), dtype=torch.int16, device=dev)
+
+    def launch_prefill(M):
+        lay = layers[pre_name]
+        i = cursor[pre_name]
+        cursor[pre_name] = (i + 1) % lay["copies"]
+        st = L.tl_ternary_gemm(pre_x.data_ptr(), lay["ring"][i].data_ptr(), lay["gbits"],
+                               pre_y.data_ptr(), M, pre_N, K, stream)
+        if st != tl.TL_OK:
+            raise tl.TlError(st, "tl_ternary_gemm")
+
+    if args.mode == "prefill":
+        for _ in range(args.steps):
+            launch_prefill(max(pre_M))
+        torch.cuda.synchronize()
+        print(json.dumps({"mode": "prefill", "launches": args.steps, "M": max(pre_M), "N": pre_N, "K": K,
+                          "flops_per_launch": 2 * max(pre_M) * pre_N * K}))
+        return
+
     # ---------------- timed region: exactly `steps` steps ---------------------------------
     # The launches are captured once into a HIP graph (as a serving loop would do for a decode
     # step) and replayed, so that the host's per-call cost is not part of the figure.
@@ -191,6 +217,15 @@ def main():
                              hbm_frac=round(b / us / 1e3 / HBM_PEAK_GBS, 4),
                              TFLOPs=round(2.0 * M * N * K / us / 1e6, 3)))
 
+    # large M: the LDS-tiled MFMA kernel against the dense fp16 MFMA peak
+    prefill = []
+    for M in ([] if args.no_per_call else pre_M):
+        reps = max(1, min(args.steps, 40))
+        us = timed(lambda: launch_prefill(M), reps) * 1e3 / reps
+        fl = 2.0 * M * pre_N * K
+        prefill.append(dict(layer=pre_name, M=M, N=pre_N, K=K, us=round(us, 2), TFLOPs=round(fl / us / 1e6, 1),
+                            mfma_frac=round(fl / us / 1e6 / MFMA_PEAK_TFLOPS, 4)))
+
     # dominant kernel: the small-M kernel in its grouped launch; one launch = one step
     us_launch = ms_per_step * 1e3
     traffic = None
@@ -237,7 +272,7 @@ def main():
                    "gemms_per_step": len(calls), "launches_per_step": 1, "weight_ring_copies": {n: layers[n]["copies"] for n in layers},
                    "algorithmic_bytes_per_step": step_bytes},
         "hbm_frac_of_peak": round(value / HBM_PEAK_GBS, 4),
-        "roofline": roofline, "cpu_baseline": cpu, "single_calls": single, "per_call": per_call,
+        "roofline": roofline, "cpu_baseline": cpu, "single_calls": single, "per_call": per_call, "prefill": prefill,
         "launch_mode": "eager" if args.eager else "hip_graph_replay",
         "host_wall_ms_timed_region_incl_capture": round(wall_ms, 2), "context": PAPER_CONTEXT,
     }
