@@ -145,14 +145,14 @@ def main():
     pre_x = torch.from_numpy(si.activations(rng, max(pre_M), K).view(np.int16)).to(dev)
     pre_y = torch.empty((max(pre_M), pre_N), dtype=torch.int16, device=dev)
 
-    def launch_prefill(M):
+    def launch_prefill(M, path=tl.TL_PATH_MFMA):
         lay = layers[pre_name]
         i = cursor[pre_name]
         cursor[pre_name] = (i + 1) % lay["copies"]
-        st = L.tl_ternary_gemm(pre_x.data_ptr(), lay["ring"][i].data_ptr(), lay["gbits"],
-                               pre_y.data_ptr(), M, pre_N, K, stream)
+        st = L.tl_ternary_gemm_path(pre_x.data_ptr(), lay["ring"][i].data_ptr(), lay["gbits"],
+                                    pre_y.data_ptr(), M, pre_N, K, stream, path)
         if st != tl.TL_OK:
-            raise tl.TlError(st, "tl_ternary_gemm")
+            raise tl.TlError(st, "tl_ternary_gemm_path")
 
     if args.mode == "prefill":
         for _ in range(args.steps):
@@ -217,14 +217,21 @@ def main():
                              hbm_frac=round(b / us / 1e3 / HBM_PEAK_GBS, 4),
                              TFLOPs=round(2.0 * M * N * K / us / 1e6, 3)))
 
-    # large M: the LDS-tiled MFMA kernel against the dense fp16 MFMA peak
-    prefill = []
+    # large M: the LDS-tiled MFMA kernel against the dense fp16 MFMA peak; and the batch sizes
+    # in between with whichever kernel the library picks
+    prefill, mid_batch = [], []
     for M in ([] if args.no_per_call else pre_M):
         reps = max(1, min(args.steps, 40))
         us = timed(lambda: launch_prefill(M), reps) * 1e3 / reps
         fl = 2.0 * M * pre_N * K
-        prefill.append(dict(layer=pre_name, M=M, N=pre_N, K=K, us=round(us, 2), TFLOPs=round(fl / us / 1e6, 1),
-                            mfma_frac=round(fl / us / 1e6 / MFMA_PEAK_TFLOPS, 4)))
+        prefill.append(dict(layer=pre_name, M=M, N=pre_N, K=K, kernel="mfma_kernel", us=round(us, 2),
+                            TFLOPs=round(fl / us / 1e6, 1), mfma_frac=round(fl / us / 1e6 / MFMA_PEAK_TFLOPS, 4)))
+    for M in ([] if args.no_per_call else (32, 64, 128, 256, 512)):
+        reps = max(1, min(args.steps, 40))
+        us = timed(lambda: launch_prefill(M, tl.TL_PATH_AUTO), reps) * 1e3 / reps
+        fl = 2.0 * M * pre_N * K
+        mid_batch.append(dict(layer=pre_name, M=M, N=pre_N, K=K, kernel="picked by tl_ternary_gemm", us=round(us, 2),
+                              TFLOPs=round(fl / us / 1e6, 1), GBps=round(algorithmic_bytes(M, pre_N, K) / us / 1e3, 1)))
 
     # dominant kernel: the small-M kernel in its grouped launch; one launch = one step
     us_launch = ms_per_step * 1e3
@@ -272,7 +279,7 @@ def main():
                    "gemms_per_step": len(calls), "launches_per_step": 1, "weight_ring_copies": {n: layers[n]["copies"] for n in layers},
                    "algorithmic_bytes_per_step": step_bytes},
         "hbm_frac_of_peak": round(value / HBM_PEAK_GBS, 4),
-        "roofline": roofline, "cpu_baseline": cpu, "single_calls": single, "per_call": per_call, "prefill": prefill,
+        "roofline": roofline, "cpu_baseline": cpu, "single_calls": single, "per_call": per_call, "prefill": prefill, "mid_batch": mid_batch,
         "launch_mode": "eager" if args.eager else "hip_graph_replay",
         "host_wall_ms_timed_region_incl_capture": round(wall_ms, 2), "context": PAPER_CONTEXT,
     }

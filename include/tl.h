@@ -143,8 +143,8 @@ tl_status tl_ternary_gemm_path(const void* x, const void* Wpacked, uint16_t gamm
  * the paper's kernel benchmark is quoted on, App. G "performance benchmark"), or any list
  * of (x, W, gamma, y).  Each job has the contract of tl_ternary_gemm.  No job reads what
  * another writes, and jobs must not alias
- * each other's outputs; they are enqueued in as few kernel launches as possible (jobs with
- * M <= 128 and K % 64 == 0 share launches, 16 blocks of 16 activation rows per launch) and
+ * each other's outputs; they are enqueued in as few kernel launches as possible (jobs that
+ * go to the small-M kernel share launches, 16 blocks of 16 activation rows per launch) and
  * may run concurrently.  `jobs` is host memory, read before the call returns.
  */
 typedef struct tl_gemm_job {

@@ -190,19 +190,22 @@ def test_mfma_exact_cases():
     assert not (y0.view(np.uint16) & 0x7FFF).any()
 
 
-@pytest.mark.parametrize("M", [256, 2048])
+@pytest.mark.parametrize("M", [256, 1024, 2048])
 def test_prefill_full_size_sampled(M):
-    # 4096 -> 14336 through tl_ternary_gemm (picks the MFMA kernel); 256 sampled columns
+    # 4096 -> 14336 through the LDS-tiled MFMA kernel; 256 sampled columns
     N, K = 14336, 4096
     x, W, g = si.layer(si.SEEDS["c4"] + M, M, N, K)
     Wp = tl.tl_pack_2bit(W)
-    y = run_gemm(x, Wp, g, N, K)
+    y = run_gemm(x, Wp, g, N, K, tl.TL_PATH_MFMA)
     cols = np.sort(np.random.default_rng(1).choice(N, 256, replace=False))
     ref = oracle.gemm(x, np.ascontiguousarray(W[cols]), g)
     assert_close(y[:, cols], ref, x, g, f"prefill full size M={M}")
+    # whichever kernel tl_ternary_gemm picks for this M on its own
+    ya = run_gemm(x, Wp, g, N, K)
+    assert_close(ya[:, cols], ref, x, g, f"full size, kernel picked by the library, M={M}")
     # y(-W) = -y: the matrix core's internal alignment is not exactly sign-symmetric, so a
     # few outputs may land on the neighbouring fp16 value; nothing may be further off
-    y2 = run_gemm(x, tl.tl_pack_2bit(-W), g, N, K)
+    y2 = run_gemm(x, tl.tl_pack_2bit(-W), g, N, K, tl.TL_PATH_MFMA)
     assert_close(-y2[:, cols], ref, x, g, f"prefill full size, negated W, M={M}")
     a = y.view(np.int16).astype(np.int32)
     b = (y2.view(np.uint16) ^ 0x8000).view(np.int16).astype(np.int32)
