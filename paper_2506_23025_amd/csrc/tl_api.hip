@@ -34,15 +34,20 @@ inline tl_status from_hip(hipError_t e) { return e == hipSuccess ? TL_OK : TL_ER
 constexpr int64_t kGemvMaxM = 128;
 
 // Small-M kernel (blocks of 16 activation rows that each stream W) or LDS-tiled MFMA kernel,
-// when both can run the shape.  The MFMA kernel walks K in steps of 64 at about a microsecond
-// per step however few tiles there are, so it only pays once its 128 x 256 tiles give every CU
-// more than one workgroup; measured crossover at 4096 -> 14336: M = 640..768 (336 tiles), at
-// 4096 -> 4096 beyond M = 1024.
-inline bool prefer_small_m(int64_t M, int64_t N)
+// when both can run the shape: whichever the measured cost models below make cheaper.  The
+// small-M kernel streams W once per block of 16 rows at about 5.6 TB/s (0.9 us at least); the
+// MFMA kernel walks K in steps of 64 at 0.72 us per step while its 128 x 128 tiles number at
+// most one per CU, else at 0.95 us per step and 256 tiles of 128 x 256.
+inline bool prefer_small_m(int64_t M, int64_t N, int64_t K)
 {
     if (M <= 16) return true;
-    const int64_t tiles = ((M + 127) / 128) * ((N + 255) / 256);
-    return M <= 1024 && tiles < 336;
+    const double w_bytes = double(N) * double(K) / 4.0;
+    const double per_block = w_bytes / 5.6e6 > 0.9 ? w_bytes / 5.6e6 : 0.9;
+    const double t_small = double((M + 15) / 16) * per_block;
+    const double wide = double((M + 127) / 128) * double((N + 255) / 256);
+    const double per_step = wide <= 128.0 ? 0.72 : 0.95 * (wide > 256.0 ? wide / 256.0 : 1.0);
+    const double t_mfma = double(K / 64) * per_step;
+    return t_small < t_mfma;
 }
 
 }  // namespace
@@ -78,7 +83,7 @@ tl_status tl_ternary_gemm_path(const void* x, const void* Wpacked, uint16_t gamm
     __half* yh = static_cast<__half*>(y);
 
     if (path == TL_PATH_AUTO) {
-        if (tl::gemv_supports(M, N, K) && (tl::prefer_small_m(M, N) || !tl::mfma_supports(M, N, K))) path = TL_PATH_GEMV;
+        if (tl::gemv_supports(M, N, K) && (tl::prefer_small_m(M, N, K) || !tl::mfma_supports(M, N, K))) path = TL_PATH_GEMV;
         else if (tl::mfma_supports(M, N, K)) path = TL_PATH_MFMA;
         else if (tl::gemv_supports(M, N, K)) path = TL_PATH_GEMV;
         else path = TL_PATH_GENERIC;
@@ -126,7 +131,7 @@ tl_status tl_ternary_gemm_grouped(const tl_gemm_job* jobs, int64_t count, void* 
     };
     for (int64_t i = 0; i < count; ++i) {
         const tl_gemm_job& j = jobs[i];
-        if (tl::gemv_supports(j.M, j.N, j.K) && (tl::prefer_small_m(j.M, j.N) || !tl::mfma_supports(j.M, j.N, j.K))) {
+        if (tl::gemv_supports(j.M, j.N, j.K) && (tl::prefer_small_m(j.M, j.N, j.K) || !tl::mfma_supports(j.M, j.N, j.K))) {
             fused[nf++] = tl::GemmDesc{static_cast<const __half*>(j.x), static_cast<const uint32_t*>(j.Wpacked),
                                        static_cast<__half*>(j.y), tl::half_bits_to_float(j.gamma_fp16_bits),
                                        j.M, j.N, j.K};

@@ -1,19 +1,26 @@
 // LDS-tiled fp16 MFMA kernel for large M (prefill): Y = X (gamma What)^T of App. B, where the
-// 2-bit codes of Sec. 3.1 are decoded to fp16 -1/0/+1 on their way into LDS.
+// 2-bit codes of Sec. 3.1 are decoded to fp16 -1/0/+1 in registers, right before the matrix
+// instruction that consumes them.
 //
-// A workgroup of 4 waves (2 x 2) owns a BM x BN tile of Y (128 x 256 or 128 x 128; at least two
-// groups are resident per CU) and walks K in steps of 64.
-// Per step: the X tile [BM][64] is copied into LDS as it is; each packed row slice (one
-// dwordx4 = 64 codes) is decoded in registers and written as 64 fp16 values; then every
-// wave runs v_mfma_f32_32x32x16_f16 over its (BM/2) x (BN/2) sub-tile, X as the 32-row
-// operand and W as the 32-column operand, so that a lane's accumulator registers hold
-// consecutive n of one output row.  The loads of step s+1 are issued before the MFMAs of
-// step s (register prefetch, one LDS buffer, two barriers per step).
+// A workgroup of 4 waves owns a 128 x (4 NW) tile of Y: the waves sit side by side along N,
+// NW = 64 or 32 columns each, and all four use the same 128 rows of X.  K is walked in steps
+// of 64.
 //
-// Decode (per 32-bit word, 16 codes): `(w & (3 << 2j | 3 << (2j+16))) | 0x64006400` is the
-// fp16 pair (1024 + 4^j c_j, 1024 + 4^j c_{j+8}); one packed fma with 4^-j and
-// -(1024 4^-j + 1) turns it into (c_j - 1, c_{j+8} - 1) exactly.  Codes 5..7 come from the
-// word shifted right by 10.  v_perm_b32 then pairs neighbours so that LDS holds k in order.
+//  * W stays packed all the way into LDS.  Per step a wave needs 16 bytes (64 codes) of each
+//    of its NW rows: one `global_load_lds_dwordx4` drops them into a wave-private ring of
+//    stages, several steps ahead, with no registers and no barrier involved.  A lane
+//    (column i, k half g) reads its row's 16 bytes back (one ds_read_b128 per 32 columns and
+//    step) and decodes, per 16-k block, the half-word it needs: `(w >> 8g) & (3 << 2j | 3 <<
+//    (2j+16)) | 0x64006400` is the fp16 pair (1024 + 4^j c_j', 1024 + 4^j c_j'+8), j' = 4g + j,
+//    and one packed fma with 4^-j and -(1024 4^-j + 1) turns it into (c - 1, c - 1) exactly:
+//    2 VALU operations per operand register, and an operand register set feeds 4 MFMAs.
+//  * That pairs k with k + 8 inside every 16-k block.  The matrix instruction does not care
+//    in which order k runs as long as both operands agree, so X is stored to LDS in the same
+//    order: on its way from global memory through registers (prefetched two steps ahead) each
+//    thread interleaves the two 8-k pieces of a block with v_perm_b32.  X is double-buffered
+//    in LDS (padded rows, conflict-free b128 reads), so a step costs one barrier.
+//  * Every wave runs v_mfma_f32_32x32x16_f16 over a 128 x NW sub-tile (4 x NW/32 fragments),
+//    X as the 32-row operand and W as the 32-column operand.
 #include "tl_internal.hpp"
 
 namespace tl {
@@ -21,7 +28,13 @@ namespace tl {
 namespace {
 
 constexpr int BK = 64;                 // K elements per step
-constexpr int LDS_ROW = BK + 8;        // halves per LDS row: 144 bytes, keeps b128 reads conflict-free
+constexpr int BM = 128;                // rows of X per workgroup
+constexpr int XROW = 144;              // bytes per X row in LDS: 128 + 16, keeps b128 reads conflict-free
+constexpr int XBUF = BM * XROW;        // one X buffer
+constexpr int WSTAGES = 8;             // steps of packed W in flight per wave
+constexpr int WSTAGE = 1024;           // bytes per stage: 64 rows x 16 bytes
+
+int g_wide_min = 129;                  // 128 x 256 tiles from this many of them on (measured crossover)
 
 struct MfmaParams {
     const __half* x;
@@ -32,6 +45,12 @@ struct MfmaParams {
     int tiles_m, tiles_n;
 };
 
+// s_waitcnt immediate for "vmcnt <= n" only (gfx9 layout)
+constexpr int vm_imm(int n)
+{
+    return (n & 0xF) | ((n >> 4) << 14) | (0x7 << 4) | (0xF << 8);
+}
+
 __device__ __forceinline__ uint32_t pk_fma(uint32_t a, uint32_t b, uint32_t c)
 {
     const f16x2 r = __builtin_elementwise_fma(__builtin_bit_cast(f16x2, a), __builtin_bit_cast(f16x2, b),
@@ -39,44 +58,34 @@ __device__ __forceinline__ uint32_t pk_fma(uint32_t a, uint32_t b, uint32_t c)
     return __builtin_bit_cast(uint32_t, r);
 }
 
-// 16 codes of one word -> 16 fp16 weights in k order, as 8 packed pairs (k, k+1).
-__device__ __forceinline__ void decode_word(uint32_t w, uint32_t (&out)[8])
+// The 8 codes (j, j + 8), j = 0..3, of a half-word-shifted packed word -> 4 fp16 pairs (w_j, w_j+8).
+__device__ __forceinline__ f16x8 decode_half(uint32_t hw)
 {
-    // scale 4^-j and offset -(1024 4^-j + 1) as fp16 pairs, j = 0..4
-    constexpr uint32_t kScale[5] = {0x3C003C00u, 0x34003400u, 0x2C002C00u, 0x24002400u, 0x1C001C00u};
-    constexpr uint32_t kOff[5] = {0xE401E401u, 0xDC04DC04u, 0xD410D410u, 0xCC40CC40u, 0xC500C500u};
-    uint32_t p[8];                                     // p[j] = (w_j, w_{j+8})
-    const uint32_t ws = w >> 10;
+    constexpr uint32_t kScale[4] = {0x3C003C00u, 0x34003400u, 0x2C002C00u, 0x24002400u};   // 4^-j
+    constexpr uint32_t kOff[4] = {0xE401E401u, 0xDC04DC04u, 0xD410D410u, 0xCC40CC40u};     // -(1024 4^-j + 1)
+    u32x4 o;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const int jj = (j < 5) ? j : j - 5;
-        const uint32_t src = (j < 5) ? w : ws;
-        const uint32_t t = (src & (0x00030003u << (2 * jj))) | 0x64006400u;
-        p[j] = pk_fma(t, kScale[jj], kOff[jj]);
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t t = (hw & (0x00030003u << (2 * j))) | 0x64006400u;
+        o[j] = pk_fma(t, kScale[j], kOff[j]);
     }
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        out[r] = __builtin_amdgcn_perm(p[2 * r + 1], p[2 * r], 0x05040100u);       // (w_2r, w_2r+1)
-        out[4 + r] = __builtin_amdgcn_perm(p[2 * r + 1], p[2 * r], 0x07060302u);   // (w_2r+8, w_2r+9)
-    }
+    return __builtin_bit_cast(f16x8, o);
 }
 
-template <int BM, int BN>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 8)))
+// NW: columns of Y per wave (64 or 32); XS: steps of X in flight in registers (even)
+template <int NW, int XS>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
 mfma_kernel(MfmaParams p)
 {
-    constexpr int PD = 1;                              // steps of global loads in flight
-    constexpr int WM = BM / 2, WN = BN / 2;            // per-wave sub-tile
-    constexpr int FM = WM / 32, FN = WN / 32;          // 32x32 fragments per wave
-    constexpr int XL = BM * 8 / 256;                   // dwordx4 loads of X per thread and step
-    constexpr int WL = (BN + 255) / 256;               // packed rows per thread and step
-    __shared__ __attribute__((aligned(16))) _Float16 As[BM * LDS_ROW];
-    __shared__ __attribute__((aligned(16))) _Float16 Bs[BN * LDS_ROW];
+    constexpr int FM = BM / 32;                        // 4 fragments down
+    constexpr int FN = NW / 32;                        // 2 or 1 fragments across
+    constexpr int BN = 4 * NW;
+    __shared__ __attribute__((aligned(16))) unsigned char Xs[2 * XBUF];
+    __shared__ __attribute__((aligned(16))) unsigned char Ws[4 * WSTAGES * WSTAGE];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
     // XCD-aware tile order: consecutive workgroup ids go to different XCDs (8 of them), so a
     // group's position inside its XCD picks neighbouring tiles that share a W column block.
@@ -90,59 +99,72 @@ mfma_kernel(MfmaParams p)
     const int tn = id / p.tiles_m;
     const int tm = id - tn * p.tiles_m;
     const int m_base = tm * BM;
-    const int n_base = tn * BN;
+    const int n_base = tn * BN + wave * NW;            // this wave's first column
     const int K = p.K;
-    const int row_words = K >> 4;
+    const int steps = K / BK;
 
-    // ---- global load plan ---------------------------------------------------------------
-    // X: thread t copies, for i < XL, the 16 bytes at row (t/8 + 32 i), halves 8 (t%8) .. +7
-    const int xr = tid >> 3, xc = tid & 7;
-    const __half* xsrc[XL];
-#pragma unroll
-    for (int i = 0; i < XL; ++i) {
-        int m = m_base + xr + 32 * i;
-        if (m >= p.M) m = p.M - 1;                        // rows past M are computed, not stored
-        xsrc[i] = p.x + size_t(m) * K + xc * 8;
+    // ---- X: thread t copies the 64 bytes (32 k) at row t / 2, half t % 2 of every step --------
+    const int xr = tid >> 1, xh = tid & 1;
+    const unsigned char* xsrc;
+    {
+        int m = m_base + xr;
+        if (m >= p.M) m = p.M - 1;                     // rows past M are computed, not stored
+        xsrc = reinterpret_cast<const unsigned char*>(p.x + size_t(m) * K) + xh * 64;
     }
-    // W: thread t owns packed row t (+256 i) of the tile
-    const uint32_t* wsrc[WL];
+    unsigned char* const xdst = Xs + xr * XROW + xh * 64;
+    typedef const __attribute__((address_space(1))) u32x4* gptr;
+    u32x4 xreg[XS][4];                                  // XS steps in flight
+    auto load_x = [&](int slot, int step) {
+        if (step >= steps) step = steps - 1;            // past the end: loaded again, never used
+        const unsigned char* src = xsrc + size_t(step) * (BK * 2);
 #pragma unroll
-    for (int i = 0; i < WL; ++i) {
-        int n = n_base + tid + 256 * i;
-        if (n >= p.N) n = p.N - 1;
-        wsrc[i] = p.W + size_t(n) * row_words;
-    }
-    const bool w_active = (WL > 1) || (tid < BN);
-
-    // Register ring of PD steps: the loads of step s + PD are issued while step s is computed,
-    // because one step of MFMAs (about 0.9 us) is shorter than a trip to L2 / Infinity Cache.
-    u32x4 xreg[PD][XL];
-    u32x4 wreg[PD][WL];
-    auto load_step = [&](int slot, int k0) {
+        for (int i = 0; i < 4; ++i) xreg[slot][i] = *(gptr)(src + 16 * i);
+    };
+    // pieces (k 0..7 | k 8..15) of a 16-k block -> (k0 k8 k1 k9 k2 k10 k3 k11 | k4 k12 .. k7 k15)
+    auto store_x = [&](int slot, int buf) {
+        unsigned char* dst = xdst + buf * XBUF;
 #pragma unroll
-        for (int i = 0; i < XL; ++i) xreg[slot][i] = *reinterpret_cast<const u32x4*>(xsrc[i] + k0);
-        if (w_active) {
+        for (int blk = 0; blk < 2; ++blk) {
+            const u32x4 d = xreg[slot][2 * blk], e = xreg[slot][2 * blk + 1];
+            u32x4 g0, g1;
 #pragma unroll
-            for (int i = 0; i < WL; ++i) wreg[slot][i] = *reinterpret_cast<const u32x4*>(wsrc[i] + (k0 >> 4));
+            for (int r = 0; r < 2; ++r) {
+                g0[2 * r] = __builtin_amdgcn_perm(e[r], d[r], 0x05040100u);
+                g0[2 * r + 1] = __builtin_amdgcn_perm(e[r], d[r], 0x07060302u);
+                g1[2 * r] = __builtin_amdgcn_perm(e[2 + r], d[2 + r], 0x05040100u);
+                g1[2 * r + 1] = __builtin_amdgcn_perm(e[2 + r], d[2 + r], 0x07060302u);
+            }
+            *reinterpret_cast<u32x4*>(dst + blk * 32) = g0;
+            *reinterpret_cast<u32x4*>(dst + blk * 32 + 16) = g1;
         }
     };
-    auto store_step = [&](int slot) {
-#pragma unroll
-        for (int i = 0; i < XL; ++i)
-            *reinterpret_cast<u32x4*>(&As[(xr + 32 * i) * LDS_ROW + xc * 8]) = xreg[slot][i];
-        if (w_active) {
-#pragma unroll
-            for (int i = 0; i < WL; ++i) {
-                _Float16* dst = &Bs[(tid + 256 * i) * LDS_ROW];
-#pragma unroll
-                for (int wd = 0; wd < 4; ++wd) {
-                    uint32_t o[8];
-                    decode_word(wreg[slot][i][wd], o);
-                    *reinterpret_cast<u32x4*>(dst + wd * 16) = u32x4{o[0], o[1], o[2], o[3]};
-                    *reinterpret_cast<u32x4*>(dst + wd * 16 + 8) = u32x4{o[4], o[5], o[6], o[7]};
-                }
-            }
-        }
+
+    // ---- W: lane l fetches the 16 bytes of row n_base + l (NW = 32: lanes 32.. repeat) --------
+    unsigned char* const wring = Ws + wave * (WSTAGES * WSTAGE);
+    const unsigned char* wsrc;
+    {
+        int n = n_base + (lane & (NW - 1));
+        if (n >= p.N) n = p.N - 1;
+        wsrc = reinterpret_cast<const unsigned char*>(p.W) + size_t(n) * (size_t(K) >> 2);
+    }
+    // The transfer is written out by hand (LDS base in M0, lane l lands at base + 16 l): a
+    // transfer the compiler knows of makes it drain the whole memory pipeline before every
+    // later LDS access, because it cannot tell that those touch other addresses.  Unknown to
+    // it, the transfers only make its own wait counts for the X loads a little stricter.
+    const uint32_t wring_addr = uint32_t(uintptr_t((const __attribute__((address_space(3))) unsigned char*)wring));
+    auto issue_w = [&](int step) {
+        const uint32_t stage = uint32_t(step & (WSTAGES - 1));
+        if (step >= steps) step = steps - 1;
+        const unsigned char* src = wsrc + size_t(step) * 16;
+        const uint32_t base = __builtin_amdgcn_readfirstlane(wring_addr + stage * WSTAGE);
+        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(base) : "memory");
+    };
+
+    // Barrier that waits for this wave's LDS traffic only: global loads and W transfers stay in
+    // flight across it (__syncthreads would drain them).
+    auto lds_barrier = [&]() {
+        __builtin_amdgcn_s_waitcnt(0xF | (0x3 << 14) | (0x7 << 4));      // lgkmcnt(0)
+        __builtin_amdgcn_s_barrier();
     };
 
     f32x16 acc[FM][FN];
@@ -153,40 +175,77 @@ mfma_kernel(MfmaParams p)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-    // fragment addresses: lane (i = lane % 32, kg = lane / 32) reads 8 halves of row i
-    const int fi = lane & 31, fk = (lane >> 5) * 8;
-    const _Float16* a_frag = &As[(wm * WM + fi) * LDS_ROW + fk];
-    const _Float16* b_frag = &Bs[(wn * WN + fi) * LDS_ROW + fk];
+    // fragment addresses: lane (i = lane % 32, g = lane / 32)
+    const int fi = lane & 31, fg = lane >> 5;
+    const unsigned char* const a_frag = Xs + fi * XROW + fg * 16;
+    const uint32_t b_addr =                                 // LDS byte address of this lane's row in stage 0
+        uint32_t(uintptr_t((const __attribute__((address_space(3))) unsigned char*)(wring + fi * 16)));
+    const uint32_t hshift = 8u * uint32_t(fg);
 
+    // ---- prologue ---------------------------------------------------------------------------
+    // Order of the memory operations of a wave, per step: 4 X loads, then 1 W transfer.  The
+    // compiler counts the X loads itself; the W transfers (LDS-DMA) are waited for by hand.
+    load_x(0, 0);
+    issue_w(0);
+    store_x(0, 0);
 #pragma unroll
-    for (int d = 0; d < PD; ++d)
-        if (d * BK < K) load_step(d, d * BK);
-    for (int kb = 0; kb < K; kb += PD * BK) {
+    for (int d = 1; d <= XS; ++d) load_x(d % XS, d);   // slot j % XS holds X of step j
 #pragma unroll
-      for (int d = 0; d < PD; ++d) {
-        const int k0 = kb + d * BK;
-        if (k0 >= K) break;
-        store_step(d);
-        __syncthreads();
-        if (k0 + PD * BK < K) load_step(d, k0 + PD * BK);
+    for (int d = 1; d < WSTAGES - 1; ++d) issue_w(d);
+    lds_barrier();
+
+    auto step_body = [&](auto slot_tag, int s) {
+        constexpr int SLOT = decltype(slot_tag)::value;        // (s + 1) % XS
+        constexpr int PAR = (SLOT + 1) & 1;                    // s & 1 (XS is even)
+        // X of step s + 1 (loaded XS steps ago) -> the other buffer; then fetch step s + 1 + XS
+        store_x(SLOT, PAR ^ 1);
+        load_x(SLOT, s + 1 + XS);
+        issue_w(s + WSTAGES - 1);
+        // W of step s: at least WSTAGES - 1 transfers and 8 X loads were issued after it
+        __builtin_amdgcn_s_waitcnt(vm_imm(WSTAGES - 1 + 8));
+        const unsigned char* const xb = a_frag + PAR * XBUF;
+        // The ring is read with hand-written ds_read: for an LDS read it can see, the compiler
+        // waits until every LDS-DMA transfer in flight has landed, which would undo the ring.
+        u32x4 wq[FN];
+        const uint32_t waddr = b_addr + uint32_t(s & (WSTAGES - 1)) * WSTAGE;
+        if constexpr (FN == 2) {
+            asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:512\n\ts_waitcnt lgkmcnt(0)"
+                         : "=&v"(wq[0]), "=&v"(wq[1]) : "v"(waddr));
+        } else {
+            asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(wq[0]) : "v"(waddr));
+        }
 #pragma unroll
-        for (int ks = 0; ks < BK; ks += 16) {
+        for (int ks = 0; ks < 4; ++ks) {
             f16x8 af[FM], bf[FN];
 #pragma unroll
             for (int a = 0; a < FM; ++a)
-                af[a] = *reinterpret_cast<const f16x8*>(a_frag + a * 32 * LDS_ROW + ks);
+                af[a] = *reinterpret_cast<const f16x8*>(xb + a * 32 * XROW + ks * 32);
 #pragma unroll
-            for (int b = 0; b < FN; ++b)
-                bf[b] = *reinterpret_cast<const f16x8*>(b_frag + b * 32 * LDS_ROW + ks);
+            for (int b = 0; b < FN; ++b) bf[b] = decode_half(wq[b][ks] >> hshift);
 #pragma unroll
             for (int a = 0; a < FM; ++a)
 #pragma unroll
                 for (int b = 0; b < FN; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[a], bf[b], acc[a][b], 0, 0, 0);
         }
-        __syncthreads();
-      }
+        lds_barrier();
+    };
+
+    // steps in groups of XS, so that register slots and buffer parity are compile-time
+    int s = 0;
+    for (; s + XS <= steps; s += XS) {
+        step_body(std::integral_constant<int, 1 % XS>{}, s);
+        step_body(std::integral_constant<int, 2 % XS>{}, s + 1);
+        if constexpr (XS == 4) {
+            step_body(std::integral_constant<int, 3>{}, s + 2);
+            step_body(std::integral_constant<int, 0>{}, s + 3);
+        }
     }
+    if (s < steps) { step_body(std::integral_constant<int, 1 % XS>{}, s); ++s; }
+    if (s < steps) { step_body(std::integral_constant<int, 2 % XS>{}, s); ++s; }
+    if constexpr (XS == 4)
+        if (s < steps) { step_body(std::integral_constant<int, 3>{}, s); ++s; }
+    __builtin_amdgcn_s_waitcnt(vm_imm(0));             // nothing of this wave's ring is left in flight
 
     // ---- epilogue: y[m][n] = fp16(gamma * acc) ---------------------------------------------
     // D[i][j] of a 32x32 fragment: j = lane % 32, i = 8 (r / 4) + 4 (lane / 32) + r % 4.
@@ -196,16 +255,20 @@ mfma_kernel(MfmaParams p)
     for (int a = 0; a < FM; ++a)
 #pragma unroll
         for (int b = 0; b < FN; ++b) {
-            const int n = n_base + wn * WN + b * 32 + col;
+            const int n = n_base + b * 32 + col;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int m = m_base + wm * WM + a * 32 + 8 * (r >> 2) + rsub + (r & 3);
+                const int m = m_base + a * 32 + 8 * (r >> 2) + rsub + (r & 3);
                 if (m < p.M && n < p.N) p.y[size_t(m) * p.N + n] = __float2half_rn(p.gamma * acc[a][b][r]);
             }
         }
 }
 
 }  // namespace
+
+#ifdef TL_DEV_HOOKS
+extern "C" void tl_dev_mfma(int wide_min) { g_wide_min = wide_min; }
+#endif
 
 bool mfma_supports(int64_t M, int64_t N, int64_t K)
 {
@@ -219,16 +282,16 @@ hipError_t launch_mfma(const __half* x, const uint32_t* Wp, float gamma, __half*
     MfmaParams p;
     p.x = x; p.W = Wp; p.y = y; p.gamma = gamma;
     p.M = int(M); p.N = int(N); p.K = int(K);
-    // 128 x 256 tiles keep two workgroups resident per CU (128 accumulator registers per
-    // wave), so one group's decode / barrier phase hides behind the other's MFMAs: measured
-    // 1.0 PFLOP/s at M = 2048 against 0.87 for one resident 256 x 256 group.  Small M takes
-    // 128 x 128 tiles to give every CU work.
-    if (M > 256) {
-        p.tiles_m = int((M + 127) / 128); p.tiles_n = int((N + 255) / 256);
-        hipLaunchKernelGGL((mfma_kernel<128, 256>), dim3(p.tiles_m * p.tiles_n), dim3(256), 0, s, p);
+    p.tiles_m = int((M + BM - 1) / BM);
+    // 128 x 256 tiles, two workgroups resident per CU; 128 x 128 tiles while those would leave
+    // half of the CUs without work
+    const int64_t wide = int64_t(p.tiles_m) * ((N + 255) / 256);
+    if (wide >= g_wide_min) {
+        p.tiles_n = int((N + 255) / 256);
+        hipLaunchKernelGGL((mfma_kernel<64, 4>), dim3(p.tiles_m * p.tiles_n), dim3(256), 0, s, p);
     } else {
-        p.tiles_m = int((M + 127) / 128); p.tiles_n = int((N + 127) / 128);
-        hipLaunchKernelGGL((mfma_kernel<128, 128>), dim3(p.tiles_m * p.tiles_n), dim3(256), 0, s, p);
+        p.tiles_n = int((N + 127) / 128);
+        hipLaunchKernelGGL((mfma_kernel<32, 4>), dim3(p.tiles_m * p.tiles_n), dim3(256), 0, s, p);
     }
     return hipGetLastError();
 }
