@@ -46,7 +46,9 @@ typedef enum tl_status {
 
 typedef enum tl_format {
     TL_FMT_2BIT = 0,   /* paper Sec. 3.1 with k = 16 digits per 32-bit word      */
-    TL_FMT_1P6BIT = 1  /* 5 trits per byte, plain base 3 (see tl_pack_1p6bit)    */
+    TL_FMT_1P6BIT = 1, /* 5 trits per byte, plain base 3 (see tl_pack_1p6bit)    */
+    TL_FMT_1P6BIT_FX = 2 /* 5 trits per byte, the fixed-point code as the paper prints it
+                            (see tl_pack_1p6bit_fx); same row geometry as TL_FMT_1P6BIT */
 } tl_format;
 
 /* Kernel choice for tl_ternary_gemm_path.  AUTO is what tl_ternary_gemm uses. */
@@ -97,7 +99,8 @@ tl_status tl_pack_1p6bit(const int8_t* W, int64_t N, int64_t K, uint8_t* out);
  * (k = 5, p = 8): digits big-endian, Nval = sum_j d'_j 3^(4-j), byte =
  * floor((Nval * 256 + 242) / 243).  Same row geometry as tl_pack_1p6bit.
  * Decoded by tl_unpack_1p6bit_fx with the multiply-by-3 digit extraction of
- * paper App. F, Alg. 1.  Host only.
+ * paper App. F, Alg. 1 (on the GPU: tl_unpack_dev / tl_ternary_gemm_1p6_fx with
+ * TL_FMT_1P6BIT_FX).
  */
 tl_status tl_pack_1p6bit_fx(const int8_t* W, int64_t N, int64_t K, uint8_t* out);
 tl_status tl_unpack_1p6bit_fx(const uint8_t* packed, int64_t N, int64_t K, int8_t* W_out);
@@ -160,6 +163,15 @@ tl_status tl_ternary_gemm_grouped(const tl_gemm_job* jobs, int64_t count, void* 
 /* Same contract for weights in the TL_FMT_1P6BIT layout of tl_pack_1p6bit. */
 tl_status tl_ternary_gemm_1p6(const void* x, const void* Wpacked, uint16_t gamma_fp16_bits,
                               void* y, int64_t M, int64_t N, int64_t K, void* stream);
+
+/*
+ * Same contract for weights in the TL_FMT_1P6BIT_FX layout of tl_pack_1p6bit_fx: the
+ * 1.6-bit code of paper Sec. 3.2 as printed, decoded on the GPU by the multiply-by-3 digit
+ * extraction of App. F, Alg. 1 (the paper leaves a GPU kernel for this format as future
+ * work, Sec. 3.3 "Limitations").
+ */
+tl_status tl_ternary_gemm_1p6_fx(const void* x, const void* Wpacked, uint16_t gamma_fp16_bits,
+                                 void* y, int64_t M, int64_t N, int64_t K, void* stream);
 
 /*
  * Bandwidth calibration: a plain streaming copy dst[i] = src[i] of `bytes` bytes

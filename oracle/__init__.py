@@ -169,6 +169,44 @@ def unpack3le(packed, K):
     return W
 
 
+def pack3fx(W):
+    """Rows of the fixed-point 1.6-bit code (Sec. 3.2, k = 5, p = 8): per block of five weights,
+    big-endian value Nval = sum_j (w_j + 1) 3^(4-j), byte = ceil(256 Nval / 243) written as
+    floor((256 Nval + 242) / 243); a short last block is filled with weight 0; row stride as for
+    the plain 1.6-bit form, padding zero."""
+    W = _w(W)
+    N, K = W.shape
+    nb = (K + 4) // 5
+    d = np.ones((N, nb * 5), dtype=np.int64)              # digit 1 = weight 0
+    d[:, :K] = W.astype(np.int64) + 1
+    if d.min() < 0 or d.max() > 2:
+        raise ValueError("weight outside {-1,0,1}")
+    d = d.reshape(N, nb, 5)
+    nval = np.zeros((N, nb), dtype=np.int64)
+    for j in range(5):
+        nval += d[:, :, j] * 3 ** (4 - j)
+    out = np.zeros((N, stride3le(K)), dtype=np.uint8)
+    out[:, :nb] = ((nval * 256 + 242) // 243).astype(np.uint8)
+    return out
+
+
+def unpack3fx(packed, K):
+    """Digits of the fixed-point code by the closed form of App. E: d'_j = floor(b 3^(j+1) / 2^8) mod 3."""
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    N = packed.shape[0]
+    assert packed.shape[1] == stride3le(K)
+    nb = (K + 4) // 5
+    b = packed[:, :nb].astype(np.int64)
+    W = np.zeros((N, nb, 5), dtype=np.int8)
+    for j in range(5):
+        W[:, :, j] = ((b * 3 ** (j + 1)) >> 8) % 3 - 1
+    return np.ascontiguousarray(W.reshape(N, nb * 5)[:, :K])
+
+
+def gemm_packed3fx(x, Wp, gamma, K):
+    return gemm(x, unpack3fx(Wp, K), gamma)
+
+
 # --- numbers and GEMM ---------------------------------------------------------
 
 def half_to_double(bits):

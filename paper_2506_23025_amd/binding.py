@@ -15,13 +15,14 @@ LIB_PATH = os.path.join(_HERE, "libtl.so")
 
 TL_OK = 0
 TL_ERR_NULL, TL_ERR_SHAPE, TL_ERR_VALUE, TL_ERR_ALIGN, TL_ERR_UNSUPPORTED, TL_ERR_HIP = 1, 2, 3, 4, 5, 6
-TL_FMT_2BIT, TL_FMT_1P6BIT = 0, 1
+TL_FMT_2BIT, TL_FMT_1P6BIT, TL_FMT_1P6BIT_FX = 0, 1, 2
 TL_PATH_AUTO, TL_PATH_GENERIC, TL_PATH_GEMV, TL_PATH_MFMA = 0, 1, 2, 3
 
 EXPORTS = (
     "tl_status_str", "tl_row_stride_bytes", "tl_packed_bytes", "tl_pack_2bit", "tl_pack_1p6bit",
     "tl_pack_1p6bit_fx", "tl_unpack_1p6bit_fx", "tl_unpack", "tl_unpack_dev", "tl_ternary_gemm",
-    "tl_ternary_gemm_path", "tl_ternary_gemm_grouped", "tl_ternary_gemm_1p6", "tl_probe_copy",
+    "tl_ternary_gemm_path", "tl_ternary_gemm_grouped", "tl_ternary_gemm_1p6", "tl_ternary_gemm_1p6_fx",
+    "tl_probe_copy",
 )
 
 
@@ -74,6 +75,8 @@ def _load():
     L.tl_ternary_gemm_grouped.restype = ci
     L.tl_ternary_gemm_1p6.argtypes = [vp, vp, u16, vp, i64, i64, i64, vp]
     L.tl_ternary_gemm_1p6.restype = ci
+    L.tl_ternary_gemm_1p6_fx.argtypes = [vp, vp, u16, vp, i64, i64, i64, vp]
+    L.tl_ternary_gemm_1p6_fx.restype = ci
     L.tl_probe_copy.argtypes = [vp, vp, sz, vp]
     L.tl_probe_copy.restype = ci
     return L
@@ -207,6 +210,11 @@ def tl_ternary_gemm_grouped(jobs, stream=None):
 def tl_ternary_gemm_1p6(x, Wpacked, gamma_fp16_bits, y, M, N, K, stream=None):
     _check(_lib.tl_ternary_gemm_1p6(_ptr(x), _ptr(Wpacked), gamma_fp16_bits, _ptr(y), M, N, K,
                                     _stream(stream)), "tl_ternary_gemm_1p6")
+
+
+def tl_ternary_gemm_1p6_fx(x, Wpacked, gamma_fp16_bits, y, M, N, K, stream=None):
+    _check(_lib.tl_ternary_gemm_1p6_fx(_ptr(x), _ptr(Wpacked), gamma_fp16_bits, _ptr(y), M, N, K,
+                                       _stream(stream)), "tl_ternary_gemm_1p6_fx")
 
 
 def tl_probe_copy(dst, src, nbytes, stream=None):

@@ -63,10 +63,10 @@ tl_status tl_unpack_dev(tl_format fmt, const void* packed, int64_t N, int64_t K,
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (fmt == TL_FMT_2BIT)
         return tl::from_hip(tl::launch_unpack2(static_cast<const uint32_t*>(packed), N, K, W_out, s));
-    if (fmt == TL_FMT_1P6BIT)
+    if (fmt == TL_FMT_1P6BIT || fmt == TL_FMT_1P6BIT_FX)
         return tl::from_hip(tl::launch_unpack3(static_cast<const uint8_t*>(packed), N, K,
                                                static_cast<int64_t>(tl_row_stride_bytes(fmt, K)),
-                                               W_out, s));
+                                               W_out, fmt == TL_FMT_1P6BIT_FX, s));
     return TL_ERR_UNSUPPORTED;
 }
 
@@ -146,8 +146,10 @@ tl_status tl_ternary_gemm_grouped(const tl_gemm_job* jobs, int64_t count, void* 
     return flush();
 }
 
-tl_status tl_ternary_gemm_1p6(const void* x, const void* Wpacked, uint16_t gamma_fp16_bits, void* y,
-                              int64_t M, int64_t N, int64_t K, void* stream)
+namespace {
+
+tl_status gemm_1p6(const void* x, const void* Wpacked, uint16_t gamma_fp16_bits, void* y,
+                   int64_t M, int64_t N, int64_t K, void* stream, bool fx)
 {
     if (!x || !Wpacked || !y) return TL_ERR_NULL;
     if (!tl::dims_ok(M, N, K)) return TL_ERR_SHAPE;
@@ -157,10 +159,24 @@ tl_status tl_ternary_gemm_1p6(const void* x, const void* Wpacked, uint16_t gamma
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (M <= tl::kGemvMaxM && tl::gemv3_supports(M, N, K))
         return tl::from_hip(tl::launch_gemv3(static_cast<const __half*>(x), static_cast<const uint8_t*>(Wpacked),
-                                             stride, gamma, static_cast<__half*>(y), M, N, K, s));
+                                             stride, gamma, static_cast<__half*>(y), M, N, K, fx, s));
     return tl::from_hip(tl::launch_gemm3_generic(static_cast<const __half*>(x),
                                                  static_cast<const uint8_t*>(Wpacked), stride, gamma,
-                                                 static_cast<__half*>(y), M, N, K, s));
+                                                 static_cast<__half*>(y), M, N, K, fx, s));
+}
+
+}  // namespace
+
+tl_status tl_ternary_gemm_1p6(const void* x, const void* Wpacked, uint16_t gamma_fp16_bits, void* y,
+                              int64_t M, int64_t N, int64_t K, void* stream)
+{
+    return gemm_1p6(x, Wpacked, gamma_fp16_bits, y, M, N, K, stream, false);
+}
+
+tl_status tl_ternary_gemm_1p6_fx(const void* x, const void* Wpacked, uint16_t gamma_fp16_bits, void* y,
+                                 int64_t M, int64_t N, int64_t K, void* stream)
+{
+    return gemm_1p6(x, Wpacked, gamma_fp16_bits, y, M, N, K, stream, true);
 }
 
 tl_status tl_probe_copy(void* dst, const void* src, size_t bytes, void* stream)

@@ -22,24 +22,45 @@ unpack2_kernel(const uint32_t* __restrict__ packed, int64_t N, int64_t K, int64_
     for (int j = 0; j < len; ++j, word >>= 2) dst[j] = int8_t(int(word & 3u) - 1);
 }
 
+// Digit i (0..4) of a 1.6-bit byte as w + 1.  Plain form: base-3 digits, least significant
+// first.  Fixed-point form (Sec. 3.2 with k = 5, p = 8): App. F, Alg. 1 -- multiply by 3, the
+// digit is what spills over the byte, the low byte goes on; most significant digit first.
+__device__ __forceinline__ void digits5(unsigned v, bool fx, unsigned (&d)[5])
+{
+    if (fx) {
+#pragma unroll
+        for (int i = 0; i < 5; ++i) {
+            const unsigned t = v * 3u;
+            d[i] = t >> 8;
+            v = t & 0xFFu;
+        }
+    } else {
+        v = (v >= 243u) ? v - 243u : v;
+#pragma unroll
+        for (int i = 0; i < 5; ++i) {
+            const unsigned q = v / 3u;
+            d[i] = v - 3u * q;
+            v = q;
+        }
+    }
+}
+
 // ---- base-3 byte decode: one thread per byte, up to 5 weights out ------------------
 __global__ void __launch_bounds__(256)
 unpack3_kernel(const uint8_t* __restrict__ packed, int64_t N, int64_t K, int64_t stride,
-               int64_t nbytes, int8_t* __restrict__ out)
+               int64_t nbytes, int8_t* __restrict__ out, bool fx)
 {
     const int64_t gid = blockIdx.x * int64_t(256) + threadIdx.x;
     if (gid >= N * nbytes) return;
     const int64_t n = gid / nbytes;
     const int64_t b = gid - n * nbytes;
-    unsigned v = packed[n * stride + b];
-    v = (v >= 243u) ? v - 243u : v;
+    unsigned d[5];
+    digits5(packed[n * stride + b], fx, d);
     const int64_t base = 5 * b;
     int8_t* dst = out + n * K + base;
-    for (int i = 0; i < 5 && base + i < K; ++i) {
-        const unsigned q = v / 3u;
-        dst[i] = int8_t(int(v - 3u * q) - 1);
-        v = q;
-    }
+#pragma unroll
+    for (int i = 0; i < 5; ++i)
+        if (base + i < K) dst[i] = int8_t(int(d[i]) - 1);
 }
 
 __global__ void __launch_bounds__(256)
@@ -96,7 +117,7 @@ gemm_generic_kernel(const __half* __restrict__ x, const uint32_t* __restrict__ W
 
 __global__ void __launch_bounds__(256)
 gemm3_generic_kernel(const __half* __restrict__ x, const uint8_t* __restrict__ Wp, int64_t stride,
-                     float gamma, __half* __restrict__ y, int64_t M, int64_t N, int64_t K)
+                     float gamma, __half* __restrict__ y, int64_t M, int64_t N, int64_t K, bool fx)
 {
     const int lane = threadIdx.x & 63;
     const int64_t n = blockIdx.x * int64_t(4) + (threadIdx.x >> 6);
@@ -107,13 +128,11 @@ gemm3_generic_kernel(const __half* __restrict__ x, const uint8_t* __restrict__ W
     const uint8_t* row = Wp + n * stride;
     const int64_t nbytes = (K + 4) / 5;
     for (int64_t b = lane; b < nbytes; b += 64) {
-        unsigned v = row[b];
-        v = (v >= 243u) ? v - 243u : v;
+        unsigned d[5];
+        digits5(row[b], fx, d);
         const int64_t base = 5 * b;
         for (int i = 0; i < 5 && base + i < K; ++i) {
-            const unsigned q = v / 3u;
-            const int w = int(v - 3u * q) - 1;
-            v = q;
+            const int w = int(d[i]) - 1;
             for (int r = 0; r < MB; ++r) {
                 if (m0 + r < M) {
                     const float xv = __half2float(x[(m0 + r) * K + base + i]);
@@ -144,11 +163,11 @@ hipError_t launch_unpack2(const uint32_t* packed, int64_t N, int64_t K, int8_t* 
 }
 
 hipError_t launch_unpack3(const uint8_t* packed, int64_t N, int64_t K, int64_t stride, int8_t* out,
-                          hipStream_t s)
+                          bool fx, hipStream_t s)
 {
     const int64_t nbytes = (K + 4) / 5;
     hipLaunchKernelGGL(unpack3_kernel, dim3(blocks_for(N * nbytes, 256)), dim3(256), 0, s,
-                       packed, N, K, stride, nbytes, out);
+                       packed, N, K, stride, nbytes, out, fx);
     return hipGetLastError();
 }
 
@@ -173,10 +192,10 @@ hipError_t launch_gemm_generic(const __half* x, const uint32_t* Wp, float gamma,
 }
 
 hipError_t launch_gemm3_generic(const __half* x, const uint8_t* Wp, int64_t stride, float gamma,
-                                __half* y, int64_t M, int64_t N, int64_t K, hipStream_t s)
+                                __half* y, int64_t M, int64_t N, int64_t K, bool fx, hipStream_t s)
 {
     dim3 grid(blocks_for(N, 4), blocks_for(M, MB));
-    hipLaunchKernelGGL(gemm3_generic_kernel, grid, dim3(256), 0, s, x, Wp, stride, gamma, y, M, N, K);
+    hipLaunchKernelGGL(gemm3_generic_kernel, grid, dim3(256), 0, s, x, Wp, stride, gamma, y, M, N, K, fx);
     return hipGetLastError();
 }
 

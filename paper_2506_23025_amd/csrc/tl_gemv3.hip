@@ -40,6 +40,7 @@ struct Gemv3Params {
     int tiles;       // ceil(N / 16)
     int groups;      // gridDim.x
     int slices;      // ceil(stride / 128)
+    int fx;          // bytes hold the fixed-point code of Sec. 3.2 instead of plain base 3
 };
 
 constexpr int vmcnt_imm3(int n)
@@ -135,12 +136,21 @@ gemv3_kernel(Gemv3Params p)
         for (int t = 0; t < T; ++t) issue_w(t, slice);
     }
 
-    // byte -> digits table (bytes 243..255 never occur; they decode like byte - 243)
+    // byte -> digits table.  Plain form: base-3 digits, least significant first (bytes
+    // 243..255 never occur; they decode like byte - 243).  Fixed-point form: App. F, Alg. 1,
+    // run here once per byte value -- multiply by 3, the digit is what spills over the byte,
+    // most significant digit first; all 256 bytes decode.
     for (unsigned b = threadIdx.x; b < 256; b += blockDim.x) {
-        unsigned v = b >= 243 ? b - 243 : b;
         unsigned c[5];
+        if (p.fx) {
+            unsigned v = b;
 #pragma unroll
-        for (int i = 0; i < 5; ++i) { c[i] = v % 3u; v /= 3u; }
+            for (int i = 0; i < 5; ++i) { const unsigned t = v * 3u; c[i] = t >> 8; v = t & 0xFFu; }
+        } else {
+            unsigned v = b >= 243 ? b - 243 : b;
+#pragma unroll
+            for (int i = 0; i < 5; ++i) { c[i] = v % 3u; v /= 3u; }
+        }
         lut[b] = (c[0] << 4) | (c[1] << 6) | (c[2] << 8) | (c[3] << 20) | (c[4] << 22);
     }
     __syncthreads();
@@ -266,9 +276,10 @@ bool gemv3_supports(int64_t M, int64_t N, int64_t K)
 }
 
 hipError_t launch_gemv3(const __half* x, const uint8_t* Wp, int64_t stride, float gamma, __half* y,
-                        int64_t M, int64_t N, int64_t K, hipStream_t s)
+                        int64_t M, int64_t N, int64_t K, bool fx, hipStream_t s)
 {
     Gemv3Params p;
+    p.fx = fx ? 1 : 0;
     p.x = x; p.W = Wp; p.y = y; p.gamma = gamma;
     p.M = int(M); p.N = int(N); p.K = int(K);
     p.stride = int(stride);

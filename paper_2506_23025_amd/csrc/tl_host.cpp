@@ -54,7 +54,8 @@ size_t tl_row_stride_bytes(tl_format fmt, int64_t K) {
     if (K < 1 || K >= (int64_t(1) << 40)) return 0;
     switch (fmt) {
         case TL_FMT_2BIT: return static_cast<size_t>(4 * ceil_div(K, 16));
-        case TL_FMT_1P6BIT: return static_cast<size_t>(16 * ceil_div(ceil_div(K, kTritsPerByte), 16));
+        case TL_FMT_1P6BIT:
+        case TL_FMT_1P6BIT_FX: return static_cast<size_t>(16 * ceil_div(ceil_div(K, kTritsPerByte), 16));
     }
     return 0;
 }
@@ -196,6 +197,8 @@ tl_status tl_unpack(tl_format fmt, const void* packed, int64_t N, int64_t K, int
         }
         return bad ? TL_ERR_VALUE : TL_OK;
     }
+    if (fmt == TL_FMT_1P6BIT_FX)
+        return tl_unpack_1p6bit_fx(static_cast<const uint8_t*>(packed), N, K, W_out);
     return TL_ERR_UNSUPPORTED;
 }
 

@@ -18,15 +18,16 @@ typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 
 // Launchers return hipGetLastError() of their launch.  All pointers are device pointers.
 hipError_t launch_unpack2(const uint32_t* packed, int64_t N, int64_t K, int8_t* out, hipStream_t s);
+// fx: the fixed-point byte code of Sec. 3.2 (decoded by App. F, Alg. 1) instead of plain base 3
 hipError_t launch_unpack3(const uint8_t* packed, int64_t N, int64_t K, int64_t stride, int8_t* out,
-                          hipStream_t s);
+                          bool fx, hipStream_t s);
 hipError_t launch_probe_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
 
 // Plain VALU kernel: any M, N, K.
 hipError_t launch_gemm_generic(const __half* x, const uint32_t* Wp, float gamma, __half* y,
                                int64_t M, int64_t N, int64_t K, hipStream_t s);
 hipError_t launch_gemm3_generic(const __half* x, const uint8_t* Wp, int64_t stride, float gamma,
-                                __half* y, int64_t M, int64_t N, int64_t K, hipStream_t s);
+                                __half* y, int64_t M, int64_t N, int64_t K, bool fx, hipStream_t s);
 
 // One GEMM of a grouped call, device pointers, gamma already widened.
 struct GemmDesc {
@@ -47,7 +48,7 @@ hipError_t launch_gemv_jobs(const GemmDesc* jobs, int count, hipStream_t s);
 // Weight-streaming small-M kernel for the 1.6-bit format.  Needs K % 8 == 0.
 bool gemv3_supports(int64_t M, int64_t N, int64_t K);
 hipError_t launch_gemv3(const __half* x, const uint8_t* Wp, int64_t stride, float gamma, __half* y,
-                        int64_t M, int64_t N, int64_t K, hipStream_t s);
+                        int64_t M, int64_t N, int64_t K, bool fx, hipStream_t s);
 
 // LDS-tiled MFMA prefill kernel (2-bit).  Needs K % 64 == 0.
 bool mfma_supports(int64_t M, int64_t N, int64_t K);

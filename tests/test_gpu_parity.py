@@ -309,6 +309,49 @@ def test_gemv_1p6_matches_oracle(M, N, K):
     assert_close(y, oracle.gemm_packed3le(x, Wp, g, K), x, g, f"1.6-bit small-M {M}x{N}x{K}")
 
 
+# ------------------------------------------------- the paper's fixed-point 1.6-bit code on the GPU
+
+@pytest.mark.parametrize("N,K", [(1, 1), (5, 17), (33, 101), (64, 4096), (7, 11008)])
+def test_unpack_dev_1p6bit_fx_bit_exact(N, K):
+    # Alg. 1 (App. F) on the GPU against the closed-form decode of App. E in the oracle
+    import torch
+    W = si.ternary_weights(np.random.default_rng(N + K + 1), N, K)
+    P = oracle.pack3fx(W)
+    out = torch.full((N, K), 77, dtype=torch.int8, device="cuda")
+    tl.tl_unpack_dev(tl.TL_FMT_1P6BIT_FX, to_dev(P), N, K, out)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), W)
+    # every byte value, not only the 243 the packer produces
+    every = np.zeros((256, 16), dtype=np.uint8)
+    every[:, 0] = np.arange(256)
+    out = torch.full((256, 5), 77, dtype=torch.int8, device="cuda")
+    tl.tl_unpack_dev(tl.TL_FMT_1P6BIT_FX, to_dev(every), 256, 5, out)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), oracle.unpack3fx(every, 5))
+
+
+FX_SHAPES = [(1, 16, 8), (4, 272, 640), (3, 17, 1280), (16, 100, 648), (7, 33, 4096), (16, 4099, 4096),
+             (3, 40, 11008), (33, 130, 2048), (2, 5, 17), (5, 129, 4095), (200, 48, 640)]
+
+
+@pytest.mark.parametrize("M,N,K", FX_SHAPES)
+def test_gemm_1p6_fx_matches_oracle(M, N, K):
+    # small-M kernel (table filled by Alg. 1) where K % 8 == 0 and M <= 128, generic kernel otherwise
+    import torch
+    x, W, g = si.layer(9500 + M + N + K, M, N, K)
+    Wp = tl.tl_pack_1p6bit_fx(W)
+    assert np.array_equal(Wp, oracle.pack3fx(W))
+    xd, wd = to_dev(x.view(np.uint16).view(np.int16)), to_dev(Wp)
+    yd = torch.full((M, N), -21555, dtype=torch.int16, device="cuda")
+    tl.tl_ternary_gemm_1p6_fx(xd, wd, si.gamma_bits(g), yd, M, N, K)
+    torch.cuda.synchronize()
+    y = yd.cpu().numpy().view(np.float16)
+    assert_close(y, oracle.gemm_packed3fx(x, Wp, g, K), x, g, f"1.6-bit fixed-point code {M}x{N}x{K}")
+    # the same weights in the plain base-3 form give the same bits: only the byte code differs
+    y3 = run_gemm3(x, tl.tl_pack_1p6bit(W), g, N, K)
+    assert np.array_equal(y.view(np.uint16), y3.view(np.uint16))
+
+
 @pytest.mark.parametrize("M", [1, 4, 16])
 def test_gemv_1p6_full_size_agrees_with_2bit_path(M):
     # config 5: the same weights through both formats; 512 sampled columns against the oracle

@@ -72,6 +72,17 @@ def test_pack_1p6bit_fx_matches_paper_code_and_alg1_decode():
         assert oracle.unpack_fx_alg1_block(int(Pw[1, b])).tolist() == W[1, 5 * b:5 * b + 5].tolist()
 
 
+def test_fx_format_through_the_format_enum():
+    # TL_FMT_1P6BIT_FX: same geometry as the plain 1.6-bit form; host unpack = Alg. 1 decode;
+    # the library's rows equal the oracle's rows byte for byte
+    for K in (5, 64, 4096, 11008):
+        assert tl.tl_row_stride_bytes(tl.TL_FMT_1P6BIT_FX, K) == tl.tl_row_stride_bytes(tl.TL_FMT_1P6BIT, K)
+    W = si.ternary_weights(np.random.default_rng(9), 5, 643)
+    P = tl.tl_pack_1p6bit_fx(W)
+    assert np.array_equal(P, oracle.pack3fx(W))
+    assert np.array_equal(tl.tl_unpack(tl.TL_FMT_1P6BIT_FX, P, 5, 643), W)
+
+
 def test_error_codes():
     L = tl.raw()
     W = np.zeros((2, 16), dtype=np.int8)

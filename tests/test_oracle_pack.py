@@ -11,6 +11,7 @@ import numpy as np
 import pytest
 
 import oracle
+import synth_inputs as si
 
 GOLD = os.path.join(os.path.dirname(__file__), "golden")
 
@@ -152,6 +153,28 @@ def test_fx_alg1_equals_division_decode_on_every_block():
         a1 = oracle.unpack_fx_alg1_block(b).tolist()
         dv = oracle.unpack_fx_div_block(b, 5, 8).tolist()
         assert a1 == dv == d.tolist()                      # digits come out d_0 first
+
+
+def test_fx_rows_agree_with_the_block_forms():
+    # the row-level packer / decoder (numpy closed forms) against the block-level C forms,
+    # on every block and on ragged rows; all 256 byte values decode like Alg. 1
+    P = oracle.pack3fx(ALL5)
+    assert P[:, 0].tolist() == [oracle.pack_fx_block(d, 5, 8) for d in ALL5]
+    assert not P[:, 1:].any()                              # stride padding is zero
+    assert np.array_equal(oracle.unpack3fx(P, 5), ALL5)
+    every = np.zeros((256, 16), dtype=np.uint8)
+    every[:, 0] = np.arange(256)
+    got = oracle.unpack3fx(every, 5)
+    for b in range(256):
+        assert got[b].tolist() == oracle.unpack_fx_alg1_block(b).tolist()
+    for K in (1, 4, 5, 6, 79, 80, 81, 4096):
+        W = si.ternary_weights(np.random.default_rng(700 + K), 3, K)
+        Pk = oracle.pack3fx(W)
+        assert Pk.shape == (3, oracle.stride3le(K))
+        assert np.array_equal(oracle.unpack3fx(Pk, K), W)
+        assert not Pk[:, (K + 4) // 5:].any()
+    with pytest.raises(ValueError):
+        oracle.pack3fx(np.array([[0, 2, 0, 0, 0]], dtype=np.int8))
 
 
 # -------------------------------------------- little-endian base-3 byte
