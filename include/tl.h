@@ -75,6 +75,21 @@ size_t tl_row_stride_bytes(tl_format fmt, int64_t K);
 size_t tl_packed_bytes(tl_format fmt, int64_t N, int64_t K);
 
 /*
+ * Ternarisation of a trained weight matrix, paper App. B "Forward Pass":
+ *   gamma = eps + mean |W_ij|,   What_ij = round(min(max(W_ij / gamma, -1), 1)).
+ * The mean and the quotient are taken in fp64; round is round-half-to-even (the paper does
+ * not say which; ties have measure zero for trained weights).  Per tensor only.
+ *   W     host, float [N][K] row-major, finite
+ *   What  host, int8 [N][K], written with values in {-1,0,1} (ready for tl_pack_*)
+ *   gamma            if not NULL: the scale as computed (fp64)
+ *   gamma_fp16_bits  if not NULL: the same rounded to fp16 (round to nearest even), the
+ *                    form tl_ternary_gemm takes
+ * TL_ERR_VALUE if W holds a NaN or an infinity, or eps is negative or not finite.
+ */
+tl_status tl_quantize(const float* W, int64_t N, int64_t K, double eps, int8_t* What,
+                      double* gamma, uint16_t* gamma_fp16_bits);
+
+/*
  * 2-bit packing P of paper Sec. 3.1 with k = 16: digit d' = w + 1 in {0,1,2};
  * word i of a row holds weights 16i .. 16i+15, weight 16i+j in bits [2j+1:2j].
  * A short last word is filled with weight 0 (digit 1), as the paper prescribes.

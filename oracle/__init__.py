@@ -207,6 +207,21 @@ def gemm_packed3fx(x, Wp, gamma, K):
     return gemm(x, unpack3fx(Wp, K), gamma)
 
 
+# --- App. B: ternarisation of trained weights ---------------------------------------
+
+def quantize(W, eps=1e-5):
+    """gamma = eps + mean |W| (exactly rounded fp64 sum), What = round(clip(W / gamma, -1, 1)),
+    round half to even.  Returns (What int8, gamma float)."""
+    import math
+    W64 = np.asarray(W, dtype=np.float64)
+    gamma = float(eps) + math.fsum(np.abs(W64).ravel().tolist()) / W64.size
+    if gamma > 0.0:
+        q = np.clip(W64 / gamma, -1.0, 1.0)
+    else:
+        q = np.zeros_like(W64)
+    return np.rint(q).astype(np.int8), gamma
+
+
 # --- numbers and GEMM ---------------------------------------------------------
 
 def half_to_double(bits):

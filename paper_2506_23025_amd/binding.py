@@ -19,7 +19,7 @@ TL_FMT_2BIT, TL_FMT_1P6BIT, TL_FMT_1P6BIT_FX = 0, 1, 2
 TL_PATH_AUTO, TL_PATH_GENERIC, TL_PATH_GEMV, TL_PATH_MFMA = 0, 1, 2, 3
 
 EXPORTS = (
-    "tl_status_str", "tl_row_stride_bytes", "tl_packed_bytes", "tl_pack_2bit", "tl_pack_1p6bit",
+    "tl_status_str", "tl_row_stride_bytes", "tl_packed_bytes", "tl_quantize", "tl_pack_2bit", "tl_pack_1p6bit",
     "tl_pack_1p6bit_fx", "tl_unpack_1p6bit_fx", "tl_unpack", "tl_unpack_dev", "tl_ternary_gemm",
     "tl_ternary_gemm_path", "tl_ternary_gemm_grouped", "tl_ternary_gemm_1p6", "tl_ternary_gemm_1p6_fx",
     "tl_probe_copy",
@@ -63,6 +63,8 @@ def _load():
     for name in ("tl_pack_2bit", "tl_pack_1p6bit", "tl_pack_1p6bit_fx", "tl_unpack_1p6bit_fx"):
         getattr(L, name).argtypes = [vp, i64, i64, vp]
         getattr(L, name).restype = ci
+    L.tl_quantize.argtypes = [vp, i64, i64, ctypes.c_double, vp, vp, vp]
+    L.tl_quantize.restype = ci
     L.tl_unpack.argtypes = [ci, vp, i64, i64, vp]
     L.tl_unpack.restype = ci
     L.tl_unpack_dev.argtypes = [ci, vp, i64, i64, vp, vp]
@@ -148,6 +150,18 @@ def tl_pack_1p6bit(W):
     out = np.empty((N, tl_row_stride_bytes(TL_FMT_1P6BIT, K)), dtype=np.uint8)
     _check(_lib.tl_pack_1p6bit(W.ctypes.data, N, K, out.ctypes.data), "tl_pack_1p6bit")
     return out
+
+
+def tl_quantize(W, eps=1e-5):
+    """float32 [N][K] -> (What int8 [N][K], gamma float, gamma_fp16_bits int)."""
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    N, K = W.shape
+    What = np.empty((N, K), dtype=np.int8)
+    g = ctypes.c_double(0.0)
+    gb = ctypes.c_uint16(0)
+    _check(_lib.tl_quantize(W.ctypes.data, N, K, float(eps), What.ctypes.data, ctypes.addressof(g),
+                            ctypes.addressof(gb)), "tl_quantize")
+    return What, g.value, gb.value
 
 
 def tl_pack_1p6bit_fx(W):

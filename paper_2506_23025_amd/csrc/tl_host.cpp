@@ -2,6 +2,7 @@
 // Pure C++ (no HIP calls); compiled into libtl.so together with the kernels.
 #include "tl.h"
 
+#include <cmath>
 #include <cstring>
 
 namespace {
@@ -67,6 +68,59 @@ size_t tl_packed_bytes(tl_format fmt, int64_t N, int64_t K) {
 
 // Sec. 3.1 with k = 16: the word is built from its top digit down (Horner in base 4),
 // which leaves weight 16i+j in bits [2j+1:2j].
+namespace {
+
+// fp64 -> fp16 bits, round to nearest even; subnormals kept, overflow to infinity.
+uint16_t double_to_half_bits(double v) {
+    const uint16_t sign = std::signbit(v) ? 0x8000u : 0u;
+    const double a = std::fabs(v);
+    if (std::isnan(a)) return static_cast<uint16_t>(sign | 0x7E00u);
+    if (a >= 65520.0) return static_cast<uint16_t>(sign | 0x7C00u);
+    int e = 0;
+    (void)std::frexp(a, &e);                        // a = f * 2^e, f in [0.5, 1)
+    e -= 1;                                         // a in [2^e, 2^(e+1))
+    if (a == 0.0 || e < -14) {                      // subnormal range: units of 2^-24
+        const double q = std::nearbyint(std::ldexp(a, 24));
+        return static_cast<uint16_t>(sign | static_cast<uint16_t>(q));   // q = 1024 is the least normal
+    }
+    double m = std::nearbyint(std::ldexp(a, 10 - e));                    // in [1024, 2048]
+    if (m >= 2048.0) { m = 1024.0; e += 1; }
+    if (e > 15) return static_cast<uint16_t>(sign | 0x7C00u);
+    return static_cast<uint16_t>(sign | ((e + 15) << 10) | (static_cast<int>(m) - 1024));
+}
+
+}  // namespace
+
+// App. B "Forward Pass": gamma = eps + mean |W|, What = round(clip(W / gamma, -1, 1)).
+tl_status tl_quantize(const float* W, int64_t N, int64_t K, double eps, int8_t* What,
+                      double* gamma, uint16_t* gamma_fp16_bits) {
+    if (!W || !What) return TL_ERR_NULL;
+    if (!shape_ok(N, K)) return TL_ERR_SHAPE;
+    if (!(eps >= 0.0) || !std::isfinite(eps)) return TL_ERR_VALUE;
+    const int64_t count = N * K;
+    // sum of |W| in fp64 with a running compensation (Neumaier), so that the result does not
+    // depend on the order more than in its last bit
+    double sum = 0.0, comp = 0.0;
+    bool bad = false;
+    for (int64_t i = 0; i < count; ++i) {
+        const double a = std::fabs(static_cast<double>(W[i]));
+        bad |= !std::isfinite(a);
+        const double t = sum + a;
+        comp += (sum >= a) ? (sum - t) + a : (a - t) + sum;
+        sum = t;
+    }
+    if (bad) return TL_ERR_VALUE;
+    const double g = eps + (sum + comp) / static_cast<double>(count);
+    if (gamma) *gamma = g;
+    if (gamma_fp16_bits) *gamma_fp16_bits = double_to_half_bits(g);
+    for (int64_t i = 0; i < count; ++i) {
+        double q = (g > 0.0) ? static_cast<double>(W[i]) / g : 0.0;
+        q = q < -1.0 ? -1.0 : (q > 1.0 ? 1.0 : q);
+        What[i] = static_cast<int8_t>(std::nearbyint(q));              // half to even
+    }
+    return TL_OK;
+}
+
 tl_status tl_pack_2bit(const int8_t* W, int64_t N, int64_t K, uint32_t* out) {
     if (!W || !out) return TL_ERR_NULL;
     if (!shape_ok(N, K)) return TL_ERR_SHAPE;

@@ -83,6 +83,58 @@ def test_fx_format_through_the_format_enum():
     assert np.array_equal(tl.tl_unpack(tl.TL_FMT_1P6BIT_FX, P, 5, 643), W)
 
 
+def test_quantize_hand_worked_and_invariants():
+    # App. B: gamma = eps + mean|W|, What = round(clip(W / gamma, -1, 1))
+    W = np.array([[0.5, -0.5, 0.1, 2.0]], dtype=np.float32)        # mean |W| = 0.775
+    What, g, gb = tl.tl_quantize(W, eps=0.0)
+    assert g == pytest.approx(0.775, rel=1e-7) and What.tolist() == [[1, -1, 0, 1]]
+    assert gb == int(np.float16(g).view(np.uint16))
+    # eps enters additively; all-zero weights give gamma = eps and What = 0
+    What, g, _ = tl.tl_quantize(np.zeros((3, 5), np.float32), eps=1e-5)
+    assert g == 1e-5 and not What.any()
+    What, g, _ = tl.tl_quantize(np.zeros((3, 5), np.float32), eps=0.0)
+    assert g == 0.0 and not What.any()
+    # scaling W by a power of two scales gamma and leaves What alone (eps = 0)
+    rng = np.random.default_rng(3)
+    W = rng.standard_normal((64, 96)).astype(np.float32)
+    Wh1, g1, _ = tl.tl_quantize(W, eps=0.0)
+    Wh2, g2, _ = tl.tl_quantize(W * np.float32(8.0), eps=0.0)
+    assert g2 == 8.0 * g1 and np.array_equal(Wh1, Wh2)
+    # near-Gaussian weights: |W| < gamma / 2 becomes 0, i.e. P(0) = 2 Phi(0.5 sqrt(2 / pi)) - 1 = 0.31
+    W = rng.standard_normal((512, 512)).astype(np.float32)
+    Wh, g, _ = tl.tl_quantize(W, eps=0.0)
+    assert abs(g - np.sqrt(2 / np.pi)) < 5e-3
+    assert abs((Wh == 0).mean() - 0.310) < 5e-3 and abs((Wh == 1).mean() - (Wh == -1).mean()) < 5e-3
+    assert set(np.unique(Wh).tolist()) == {-1, 0, 1}
+
+
+def test_quantize_against_oracle_and_fp16_gamma():
+    rng = np.random.default_rng(4)
+    for shape, eps in (((7, 33), 1e-5), ((128, 257), 0.0), ((1, 4096), 1e-3)):
+        W = (rng.standard_normal(shape) * rng.uniform(0.01, 3.0)).astype(np.float32)
+        Wh, g, gb = tl.tl_quantize(W, eps=eps)
+        Wo, go = oracle.quantize(W, eps)
+        assert abs(g - go) <= 4e-16 * go
+        away_from_tie = np.abs(np.abs(W.astype(np.float64) / go) - 0.5) > 1e-9
+        assert np.array_equal(Wh[away_from_tie], Wo[away_from_tie])
+        assert gb == int(np.float16(g).view(np.uint16))
+    # the fp64 -> fp16 rounding of gamma, through 1 x 1 matrices (gamma = |w|): normal, subnormal,
+    # halfway cases, overflow
+    vals = [1.0, 0.02, 65504.0, 65519.9, 65520.0, 1e6, 6.1035e-5, 6.0e-8, 2.98e-8, 2.9802322387695312e-8,
+            8.940696716308594e-08, 0.333251953125, 0.3333740234375, 1.00048828125, 1.0009765625 * 1.5]
+    vals += list(np.abs(rng.standard_normal(200)) * 10.0 ** rng.integers(-8, 5, 200))
+    for v in vals:
+        w = np.array([[v]], dtype=np.float32)
+        _, g, gb = tl.tl_quantize(w, eps=0.0)
+        assert g == float(w[0, 0])
+        with np.errstate(over="ignore"):
+            assert gb == int(np.float64(g).astype(np.float16).view(np.uint16)), v
+    with pytest.raises(tl.TlError):
+        tl.tl_quantize(np.array([[np.nan]], np.float32))
+    with pytest.raises(tl.TlError):
+        tl.tl_quantize(np.ones((2, 2), np.float32), eps=-1.0)
+
+
 def test_error_codes():
     L = tl.raw()
     W = np.zeros((2, 16), dtype=np.int8)
