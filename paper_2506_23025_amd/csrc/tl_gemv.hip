@@ -301,12 +301,18 @@ gemv_kernel(GemvBatch b)
     // area lies behind it, because the next item's activations are already arriving there.
     // The first barrier also keeps this item's partial sums from overtaking a wave that
     // still reads the previous ones.
+    // The barriers wait for LDS traffic only (s_waitcnt lgkmcnt(0); s_barrier): the next item's
+    // weights and activations stay in flight across them, which __syncthreads would drain.
+    auto lds_barrier = [&]() {
+        __builtin_amdgcn_s_waitcnt(0xF | (0x3 << 14) | (0x7 << 4));
+        __builtin_amdgcn_s_barrier();
+    };
     auto epilogue = [&](const ItemCtx& cur, const f32x4 (&part)[T]) {
-        __syncthreads();
+        lds_barrier();
         f32x4* red = reinterpret_cast<f32x4*>(lds_raw + b.red_off);
 #pragma unroll
         for (int t = 0; t < T; ++t) red[(t * NW + wave) * 64 + lane] = part[t];
-        __syncthreads();
+        lds_barrier();
         const float gamma = cur.gamma;
         for (int o = threadIdx.x; o < T * 64; o += blockDim.x) {
             const int t = o >> 6;
