@@ -284,6 +284,38 @@ def test_grouped_many_small_k_jobs():
         assert np.array_equal(y16, yd.cpu().numpy()), f"grouped {M}x{N}x{K} not deterministic"
 
 
+def test_grouped_decode_sweep_as_benchmarked():
+    # the benchmark's step, exactly as bench.py launches it: the ten GEMMs of the decode sweep
+    # (K = 4096; N = 4096 and 14336; M = 1, 2, 4, 8, 16) in one tl_ternary_gemm_grouped call, each
+    # with its own weights; 384 sampled columns per GEMM against the oracle, all rows
+    import torch
+    K = 4096
+    rng = np.random.default_rng(si.SEEDS["c2"] + 77)
+    host, dev, jobs = [], [], []
+    for name in si.DECODE_SWEEP_SHAPES:
+        k, N = si.SHAPES[name]
+        assert k == K
+        for M in si.DECODE_SWEEP_M:
+            W = si.ternary_weights(rng, N, K)
+            g = si.gamma_uniform(rng)
+            x = si.activations(rng, M, K)
+            Wp = tl.tl_pack_2bit(W)
+            xd, wd = to_dev(x.view(np.int16)), dev_u32(Wp)
+            yd = torch.full((M, N), -21555, dtype=torch.int16, device="cuda")
+            host.append((M, N, x, W, g))
+            dev.append((xd, wd, yd))
+            jobs.append((xd, wd, si.gamma_bits(g), yd, M, N, K))
+    tl.tl_ternary_gemm_grouped(jobs)
+    torch.cuda.synchronize()
+    for (M, N, x, W, g), (_, _, yd) in zip(host, dev):
+        y = yd.cpu().numpy().view(np.float16)
+        cols = np.sort(np.random.default_rng(M + N).choice(N, 384, replace=False))
+        cols[0], cols[-1] = 0, N - 1                       # first and last column of the matrix
+        assert_close(y[:, cols], oracle.gemm(x, np.ascontiguousarray(W[cols]), g), x, g,
+                     f"sweep {M}x{N}x{K}")
+        assert not (y.view(np.int16) == -21555).all(axis=0).any()   # every column was written
+
+
 def test_grouped_empty_and_errors():
     L = tl.raw()
     assert L.tl_ternary_gemm_grouped(None, 0, None) == tl.TL_OK
