@@ -159,6 +159,46 @@ def test_auto_path_full_size_sampled_columns():
     assert_close(y[:, cols], ref, x, g, "full size sampled")
 
 
+def test_config1_square_2048():
+    # config 1: 2048 -> 2048, M = 1, gamma = fp16(0.02); the whole matrix against the oracle
+    M, N, K = 1, 2048, 2048
+    x, W, g = si.layer(si.SEEDS["c1"], M, N, K, fixed_gamma=0.02)
+    Wp = tl.tl_pack_2bit(W)
+    assert np.array_equal(Wp, oracle.pack2(W))
+    y = run_gemm(x, Wp, g, N, K)
+    assert_close(y, oracle.gemm_packed2(x, Wp, g, K), x, g, "config 1")
+
+
+@pytest.mark.parametrize("M", [1, 16, 64])
+def test_config3_block_single_and_grouped(M):
+    # config 3: the four linears of a block (QKV, O, gate+up, down) at their full shapes, each as
+    # its own call and all four in one grouped call; 256 sampled columns per matrix
+    import torch
+    rng = np.random.default_rng(si.SEEDS["c3"] + M)
+    host, dev, jobs = [], [], []
+    for name in si.BLOCK_SHAPES:
+        K, N = si.SHAPES[name]
+        W = si.ternary_weights(rng, N, K)
+        g = si.gamma_uniform(rng)
+        x = si.activations(rng, M, K)
+        Wp = tl.tl_pack_2bit(W)
+        cols = np.sort(np.random.default_rng(N + M).choice(N, 256, replace=False))
+        ref = oracle.gemm(x, np.ascontiguousarray(W[cols]), g)
+        y1 = run_gemm(x, Wp, g, N, K)
+        assert_close(y1[:, cols], ref, x, g, f"block {name} M={M}, single call")
+        xd, wd = to_dev(x.view(np.int16)), dev_u32(Wp)
+        yd = torch.full((M, N), -21555, dtype=torch.int16, device="cuda")
+        host.append((name, N, K, x, g, cols, ref, y1))
+        dev.append((xd, wd, yd))
+        jobs.append((xd, wd, si.gamma_bits(g), yd, M, N, K))
+    tl.tl_ternary_gemm_grouped(jobs)
+    torch.cuda.synchronize()
+    for (name, N, K, x, g, cols, ref, y1), (_, _, yd) in zip(host, dev):
+        y = yd.cpu().numpy().view(np.float16)
+        assert_close(y[:, cols], ref, x, g, f"block {name} M={M}, grouped call")
+        assert_close(y, y1.astype(np.float64), x, g, f"block {name} M={M}, grouped against single")
+
+
 # ---------------------------------------------------------------- MFMA prefill kernel
 
 MFMA_SHAPES = [
