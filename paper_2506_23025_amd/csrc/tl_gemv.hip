@@ -428,7 +428,8 @@ constexpr int stream_wave_lds(int T)
 // each tile waits only for its own two loads, and there is one LDS-only barrier per item.
 // The loop body holds nothing but weight loads and the output stores, which is what keeps the
 // compiler's wait counts exact; the last item is a second copy of the body without refills.
-template <int T, bool MULTI>
+// PASSES: some job of the launch has K longer than the waves' slices together.
+template <int T, bool MULTI, bool PASSES>
 __global__ void __launch_bounds__(512)
 gemv_stream_kernel(GemvBatch b)
 {
@@ -475,12 +476,14 @@ gemv_stream_kernel(GemvBatch b)
     const int tile0 = local * ipg + (local < plus ? local : plus);      // first tile of the run
     const int tile_end = tile0 + ipg + (local < plus ? 1 : 0);
     const int n_items = (tile_end - tile0 + T - 1) / T;
-    const bool active = wave < J.slices;
-
-    // chunk of this lane within the row, fixed for the whole kernel (slice = wave)
-    int chunk = wave * 8 + lc;
-    if (chunk >= J.chunks) chunk = 0;                      // past K: multiplied by zero activations
-    const uint32_t col_off = uint32_t(chunk) * 16u;
+    // K longer than the waves' slices together (NW x 512) is walked in passes: pass c gives wave
+    // w the slice c NW + w, streams the whole run of tiles, and leaves the sums of the run in
+    // LDS (1 KB per tile behind the waves' areas) for the next pass to add to.
+    const int n_pass = PASSES ? (J.slices + NW - 1) / NW : 1;
+    unsigned char* const ysum = lds_raw + NW * kStride;
+    int slice = wave;
+    bool active = slice < J.slices;
+    uint32_t col_off = 0;
     const bool ragged_n = (J.N & 15) != 0;
     typedef const __attribute__((address_space(1))) u32x4* gptr;
 
@@ -499,11 +502,22 @@ gemv_stream_kernel(GemvBatch b)
 
     uint32_t breg[2][4][8];                    // this wave's activations as MFMA B operands
     f32x4 nsx = f32x4{0.f, 0.f, 0.f, 0.f};     // -2^-20 sum_k x[m][k] over the slice, as an accumulator
+    // Start of a pass: fetch this wave's activation slice and the first item's weights together,
+    // then turn the activations into operand registers.
+    auto begin_pass = [&](int pass) {
+    slice = pass * NW + wave;
+    active = slice < J.slices;
+    {
+        int chunk = slice * 8 + lc;                        // 16-byte chunk of this lane within the row
+        if (chunk >= J.chunks) chunk = 0;                  // past K: multiplied by zero activations
+        col_off = uint32_t(chunk) * 16u;
+    }
+    nsx = f32x4{0.f, 0.f, 0.f, 0.f};
     if (active) {
         // activation rows by LDS-DMA, swizzled: lane l fetches piece l ^ (r & 7) of row r
         for (int r = 0; r < J.MR; ++r) {
             const int rr = r < J.Mrem ? r : J.Mrem - 1;
-            const int kx = wave * kSliceK + ((lane ^ (r & 7)) << 3);
+            const int kx = slice * kSliceK + ((lane ^ (r & 7)) << 3);
             if (kx < J.K) {
                 __builtin_amdgcn_global_load_lds(
                     (const __attribute__((address_space(1))) void*)(J.xb + size_t(rr) * J.K * 2 + uint32_t(kx) * 2u),
@@ -552,12 +566,15 @@ gemv_stream_kernel(GemvBatch b)
 #pragma unroll
                 for (int e = 0; e < 8; ++e) breg[h][wd][e] = 0u;
     }
+    };
 
     // One item (tiles first .. first + T - 1): tile t goes through LDS region t & 1 into MFMA
     // order, is decoded and multiplied; REFILL: its registers are loaded again at once for the
     // next item.  Tiles past the run are computed from whatever was loaded and never stored.
-    auto item = [&](auto refill_tag, int first, int parity) {
+    auto item = [&](auto refill_tag, int first, int parity, bool first_pass_rt, bool last_pass_rt) {
         constexpr bool REFILL = decltype(refill_tag)::value;
+        const bool first_pass = PASSES ? first_pass_rt : true;
+        const bool last_pass = PASSES ? last_pass_rt : true;
         f32x4 part[T];
 #pragma unroll
         for (int t = 0; t < T; ++t) part[t] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -608,9 +625,13 @@ gemv_stream_kernel(GemvBatch b)
             for (int w = 0; w < 8; ++w)
                 v[w] = (w < NW) ? reinterpret_cast<const f32x4*>(lds_raw + w * kStride + 4096 + parity * (T * 1024) + t * 1024)[l]
                                 : f32x4{0.f, 0.f, 0.f, 0.f};
-            const f32x4 s = ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
+            f32x4 s = ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
+            // sums of the earlier passes over K: kept by the thread that owns this output quad
+            f32x4* const keep = reinterpret_cast<f32x4*>(ysum + (tile - tile0) * 1024) + l;
+            if (!first_pass && tile < tile_end) s += *keep;
+            if (!last_pass && tile < tile_end) *keep = s;
             const int n = tile * 16 + 4 * (l >> 4);
-            if (tile < tile_end && (l & 15) < J.Mrem) {
+            if (last_pass && tile < tile_end && (l & 15) < J.Mrem) {
                 typedef __attribute__((address_space(1))) __half* gh_ptr;
                 gh_ptr dst = (gh_ptr)(J.y + size_t(l & 15) * J.N + n);
                 const float gamma = J.gamma;
@@ -628,9 +649,18 @@ gemv_stream_kernel(GemvBatch b)
         }
     };
 
-    int i = 0;
-    for (; i + 1 < n_items; ++i) item(std::true_type{}, tile0 + i * T, i & 1);
-    item(std::false_type{}, tile0 + i * T, i & 1);
+    for (int pass = 0; pass < n_pass; ++pass) {
+        const bool first_pass = pass == 0, last_pass = pass + 1 == n_pass;
+        begin_pass(PASSES ? pass : 0);
+        int i = 0;
+        for (; i + 1 < n_items; ++i) item(std::true_type{}, tile0 + i * T, i & 1, first_pass, last_pass);
+        item(std::false_type{}, tile0 + i * T, i & 1, first_pass, last_pass);
+        if (PASSES && !last_pass) {
+            // the next pass stages activations over the partial-sum sets: everybody must be done reading
+            __builtin_amdgcn_s_waitcnt(0xF | (0x3 << 14) | (0x7 << 4));
+            __builtin_amdgcn_s_barrier();
+        }
+    }
 }
 
 using KernelFn = void (*)(GemvBatch);
@@ -651,20 +681,21 @@ KernelFn pick_kernel(int T, bool multi)
     return multi ? pick_kernel_t<true>(T) : pick_kernel_t<false>(T);
 }
 
-template <bool MULTI>
+template <bool MULTI, bool PASSES>
 KernelFn pick_stream_t(int T)
 {
     switch (T) {
-        case 1: return gemv_stream_kernel<1, MULTI>;
-        case 2: return gemv_stream_kernel<2, MULTI>;
-        case 3: return gemv_stream_kernel<3, MULTI>;
-        default: return gemv_stream_kernel<4, MULTI>;
+        case 1: return gemv_stream_kernel<1, MULTI, PASSES>;
+        case 2: return gemv_stream_kernel<2, MULTI, PASSES>;
+        case 3: return gemv_stream_kernel<3, MULTI, PASSES>;
+        default: return gemv_stream_kernel<4, MULTI, PASSES>;
     }
 }
 
-KernelFn pick_stream(int T, bool multi)
+KernelFn pick_stream(int T, bool multi, bool passes)
 {
-    return multi ? pick_stream_t<true>(T) : pick_stream_t<false>(T);
+    if (passes) return multi ? pick_stream_t<true, true>(T) : pick_stream_t<false, true>(T);
+    return multi ? pick_stream_t<true, false>(T) : pick_stream_t<false, false>(T);
 }
 
 int pow2_at_least(int v)
@@ -685,46 +716,76 @@ struct GemvPolicy {
     int t_grouped = 0;                  // 0: pick from the tile count
     int stream = 3;                     // bit 0: stream form for one job, bit 1: for several
     int stream_groups = 256;            // workgroups of the stream form (one per CU)
+    int long_k_min_run = 3;             // K > 4096 streams if the call averages this many tile passes per workgroup
 };
 GemvPolicy g_policy;
 
-constexpr int kStreamMaxSlices = 8;     // K <= 4096: every wave of an 8-wave group owns one slice
+constexpr int kStreamWaves = 8;         // waves of a stream-form workgroup when K >= 4096
+constexpr int kStreamMaxPasses = 8;     // passes over K the stream form takes: K <= 32768
+constexpr int kStreamMaxRun = 32;       // tiles of a run whose sums fit the 32 KB of LDS left over
 
 // Stream form: one job per workgroup, a run of consecutive tiles each.  Workgroups are dealt
-// out to the jobs in proportion to their tiles; then the job with the longest runs gets the
-// spare ones, one by one, so that the longest run is as short as the group count allows.
-hipError_t launch_stream(GemvBatch& b, int max_slices, int64_t total_tiles, hipStream_t s)
+// out to the jobs so that all finish together (see run_cost below); spare ones go to the job
+// with the costliest runs, one by one.  Returns hipErrorInvalidValue without launching if a multi-pass job's
+// runs would not fit the LDS (the caller then uses the general kernel).
+hipError_t launch_stream(GemvBatch& b, int max_slices, hipStream_t s)
 {
     const GemvPolicy pol = g_policy;
-    const int NW = max_slices;
+    const int NW = max_slices < kStreamWaves ? max_slices : kStreamWaves;
+    auto passes = [&](int j) { return (b.job[j].slices + NW - 1) / NW; };
+    int64_t total_cost = 0, total_tiles = 0;
+    bool multi_pass = false;
+    for (int j = 0; j < b.count; ++j) {
+        total_cost += int64_t(b.job[j].tiles) * passes(j);
+        total_tiles += b.job[j].tiles;
+        multi_pass |= passes(j) > 1;
+    }
     const int G = total_tiles < pol.stream_groups ? int(total_tiles) : pol.stream_groups;
-    int T = int((total_tiles + G - 1) / G);  // tiles per item: the whole run if it is short
+    int T = int((total_cost + G - 1) / G);   // tiles per item: the whole run if it is short
     if (T > kTMax) T = kTMax;            // (8 tiles per item measured slower: 23.9 against 21.4 us)
     if (T > NW) T = NW;                  // the epilogue gives every thread at most one output quad
     if (T < 1) T = 1;
+    // Time of a workgroup of job j with w groups, in tile units: passes x (run + start-up), where
+    // the start-up of a pass (a round trip for the activations) counts as 3 tiles for jobs of
+    // several passes.  Bisection on the common finishing time gives the group counts.
+    auto run_cost = [&](int j, int w) {
+        const int p = passes(j);
+        return double(p) * (double((b.job[j].tiles + w - 1) / w) + (p > 1 ? 3.0 : 0.0));
+    };
+    auto groups_for = [&](int j, double tau) {            // fewest groups that finish job j by tau
+        const int p = passes(j);
+        const double per = tau / double(p) - (p > 1 ? 3.0 : 0.0);
+        if (per < 1.0) return b.job[j].tiles;
+        const int w = int((double(b.job[j].tiles) + per - 1.0) / per);
+        return w < 1 ? 1 : (w > b.job[j].tiles ? b.job[j].tiles : w);
+    };
+    double lo = 0.0, hi = 0.0;
+    for (int j = 0; j < b.count; ++j) { const double c = run_cost(j, 1); if (c > hi) hi = c; }
+    for (int it = 0; it < 24; ++it) {
+        const double mid = 0.5 * (lo + hi);
+        int need = 0;
+        for (int j = 0; j < b.count; ++j) need += groups_for(j, mid);
+        if (need <= G) hi = mid; else lo = mid;
+    }
     int wg[kMaxJobs];
     int used = 0;
-    for (int j = 0; j < b.count; ++j) {
-        int w = int(int64_t(b.job[j].tiles) * G / total_tiles);
-        if (w < 1) w = 1;
-        wg[j] = w;
-        used += w;
-    }
-    auto run_len = [&](int j) { return (b.job[j].tiles + wg[j] - 1) / wg[j]; };
-    while (used < G) {                                     // spare groups: shorten the longest run
+    for (int j = 0; j < b.count; ++j) { wg[j] = groups_for(j, hi); used += wg[j]; }
+    while (used < G) {                                     // spare groups: shorten the costliest run
         int best = -1;
         for (int j = 0; j < b.count; ++j)
-            if (wg[j] < b.job[j].tiles && (best < 0 || run_len(j) > run_len(best))) best = j;
+            if (wg[j] < b.job[j].tiles && (best < 0 || run_cost(j, wg[j]) > run_cost(best, wg[best]))) best = j;
         if (best < 0) break;
         ++wg[best]; ++used;
     }
-    while (used > G) {                                     // over by rounding up to 1: lengthen the shortest
+    while (used > G) {                                     // cannot happen unless there are more jobs than groups
         int best = -1;
         for (int j = 0; j < b.count; ++j)
-            if (wg[j] > 1 && (best < 0 || run_len(j) < run_len(best))) best = j;
+            if (wg[j] > 1 && (best < 0 || run_cost(j, wg[j]) < run_cost(best, wg[best]))) best = j;
         if (best < 0) break;
         --wg[best]; --used;
     }
+    for (int j = 0; j < b.count; ++j)
+        if (passes(j) > 1 && (b.job[j].tiles + wg[j] - 1) / wg[j] > kStreamMaxRun) return hipErrorInvalidValue;
     for (int j = 0; j < kMaxJobs; ++j) b.item0[j] = 0x7fffffff;
     int grid = 0;
     for (int j = 0; j < b.count; ++j) {
@@ -735,24 +796,26 @@ hipError_t launch_stream(GemvBatch& b, int max_slices, int64_t total_tiles, hipS
         grid += wg[j];
     }
     const int total_items = 0;
+    const size_t lds = size_t(NW) * stream_wave_lds(T) + (multi_pass ? size_t(kStreamMaxRun) * 1024 : 0);
     b.total_items = total_items;
     b.red_off = 0;
     b.pad = 0;
     const bool multi = b.count > 1;
-    KernelFn fn = pick_stream(T, multi);
-    static bool lds_raised[2][kTMax + 1];
-    if (!lds_raised[multi][T]) {
+    KernelFn fn = pick_stream(T, multi, multi_pass);
+    static bool lds_raised[2][2][kTMax + 1];
+    if (!lds_raised[multi_pass][multi][T]) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 8 * stream_wave_lds(T));
+                                           hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           8 * stream_wave_lds(T) + kStreamMaxRun * 1024);
         if (e != hipSuccess) return e;
-        lds_raised[multi][T] = true;
+        lds_raised[multi_pass][multi][T] = true;
     }
-    hipLaunchKernelGGL(fn, dim3(grid), dim3(NW * 64), size_t(NW) * stream_wave_lds(T), s, b);
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(NW * 64), lds, s, b);
     return hipGetLastError();
 }
 
 // Launch one batch (<= kMaxJobs jobs, tiles / slices / M filled in): sets items and grid.
-hipError_t launch_batch(GemvBatch& b, bool grouped, hipStream_t s)
+hipError_t launch_batch(GemvBatch& b, bool grouped, bool stream_form, hipStream_t s)
 {
     const GemvPolicy pol = g_policy;
     int64_t total_tiles = 0;
@@ -761,8 +824,10 @@ hipError_t launch_batch(GemvBatch& b, bool grouped, hipStream_t s)
         total_tiles += b.job[j].tiles;
         if (b.job[j].slices > max_slices) max_slices = b.job[j].slices;
     }
-    if (max_slices <= kStreamMaxSlices && (pol.stream & (b.count > 1 ? 2 : 1)))
-        return launch_stream(b, max_slices, total_tiles, s);
+    if (stream_form && max_slices <= kStreamWaves * kStreamMaxPasses && (pol.stream & (b.count > 1 ? 2 : 1))) {
+        const hipError_t e = launch_stream(b, max_slices, s);
+        if (e != hipErrorInvalidValue) return e;           // else: runs too long for its LDS, general kernel
+    }
     int NW = grouped ? pol.nw_grouped : pol.nw_single;
     if (NW > max_slices) NW = max_slices;
     int resident = grouped ? pol.grid_cap : (NW <= 4 ? 512 : 256);
@@ -809,9 +874,10 @@ extern "C" void tl_dev_policy(int nw_single, int nw_grouped, int grid_cap, int t
     g_policy.nw_single = nw_single; g_policy.nw_grouped = nw_grouped;
     g_policy.grid_cap = grid_cap; g_policy.t_grouped = t_grouped;
 }
-extern "C" void tl_dev_stream(int stream, int groups, int)
+extern "C" void tl_dev_stream(int stream, int groups, int long_k_min_run)
 {
     g_policy.stream = stream; g_policy.stream_groups = groups;
+    if (long_k_min_run > 0) g_policy.long_k_min_run = long_k_min_run;
 }
 #endif
 
@@ -828,14 +894,24 @@ hipError_t launch_gemv_jobs(const GemmDesc* jobs, int count, hipStream_t s)
     for (int i = 0; i < count; ++i) blocks_total += (jobs[i].M + 15) / 16;
     const bool grouped = blocks_total > 1;
 
-    // Two batches fill side by side: jobs the stream form takes (K <= 4096) and the others,
-    // so that one long-K job does not pull a whole block of layers onto the general kernel.
+    // Two batches fill side by side: jobs for the stream form and jobs for the general kernel.
+    // K <= 4096 always streams.  Longer K streams in several passes, each of which starts with
+    // a round trip to memory for the activations; that pays once the call holds enough work to
+    // give every workgroup a run of a few tiles (e.g. the linears of a whole block), otherwise
+    // the general kernel takes those jobs.
+    int64_t call_cost = 0;
+    for (int i = 0; i < count; ++i) {
+        const int64_t slices = (jobs[i].K + kSliceK - 1) / kSliceK;
+        (void)slices;
+        call_cost += ((jobs[i].M + 15) / 16) * ((jobs[i].N + 15) / 16);      // tiles of the whole call
+    }
+    const bool long_k_streams = call_cost >= int64_t(g_policy.stream_groups) * g_policy.long_k_min_run;
     GemvBatch bs, bg;
     bs.count = 0;
     bg.count = 0;
     auto flush = [&](GemvBatch& b) -> hipError_t {
         if (b.count == 0) return hipSuccess;
-        hipError_t e = launch_batch(b, grouped, s);
+        hipError_t e = launch_batch(b, grouped, &b == &bs, s);
         b.count = 0;
         return e;
     };
@@ -854,7 +930,9 @@ hipError_t launch_gemv_jobs(const GemmDesc* jobs, int count, hipStream_t s)
             j.slices = int((d.K + kSliceK - 1) / kSliceK);
             j.mr = pow2_at_least(j.Mrem);
             j.pad[0] = j.pad[1] = 0;
-            GemvBatch& b = j.slices <= kStreamMaxSlices ? bs : bg;
+            const bool streams = j.slices <= kStreamWaves ||
+                                 (long_k_streams && j.slices <= kStreamWaves * kStreamMaxPasses);
+            GemvBatch& b = streams ? bs : bg;
             b.job[b.count++] = j;
             if (b.count == kMaxJobs) {
                 hipError_t e = flush(b);

@@ -294,7 +294,9 @@ def test_grouped_many_small_k_jobs():
     specs = [(1, 14336, 4096), (16, 4099, 4096), (3, 17, 576), (9, 1, 64), (2, 300, 1024), (16, 16, 4096),
              (5, 2048, 2048), (1, 12288, 4096), (12, 33, 3136), (4, 640, 512), (1, 4096, 4096), (7, 95, 128),
              (16, 22016, 4096), (2, 48, 2048), (13, 1000, 1600), (1, 31, 4096), (8, 777, 960), (6, 16, 64),
-             (24, 130, 1024), (1, 5000, 2560)]
+             (24, 130, 1024), (1, 5000, 2560),
+             # K longer than one pass of the register-resident form: several passes, sums kept in LDS
+             (5, 300, 6144), (16, 64, 11008), (1, 1000, 14336), (3, 17, 32768)]
     host, dev, jobs = [], [], []
     for i, (M, N, K) in enumerate(specs):
         x, W, g = si.layer(7100 + i, M, N, K)
