@@ -233,6 +233,41 @@ def main():
         mid_batch.append(dict(layer=pre_name, M=M, N=pre_N, K=K, kernel="picked by tl_ternary_gemm", us=round(us, 2),
                               TFLOPs=round(fl / us / 1e6, 1), GBps=round(algorithmic_bytes(M, pre_N, K) / us / 1e3, 1)))
 
+    # the linears of a block (QKV, O, gate+up, down) as one grouped call: the unit the paper's
+    # kernel benchmark is quoted on (App. G)
+    block = []
+    if not args.no_per_call:
+        brng = np.random.default_rng(si.SEEDS["c3"])
+        blay = []
+        for name in si.BLOCK_SHAPES:
+            k, N = si.SHAPES[name]
+            Wp = tl.tl_pack_2bit(si.ternary_weights(brng, N, k))
+            copies = 6
+            ring = torch.empty((copies,) + Wp.shape, dtype=torch.int32, device=dev)
+            ring[0].copy_(torch.from_numpy(Wp.view(np.int32)))
+            for i in range(1, copies):
+                ring[i].copy_(ring[0])
+            blay.append(dict(name=name, K=k, N=N, ring=ring, copies=copies, gbits=si.gamma_bits(si.gamma_uniform(brng))))
+        for M in (1, 16):
+            bx = {k: torch.from_numpy(si.activations(brng, M, k).view(np.int16)).to(dev) for k in {l["K"] for l in blay}}
+            by = [torch.empty((M, l["N"]), dtype=torch.int16, device=dev) for l in blay]
+            bcur = [0]
+
+            def block_step():
+                i = bcur[0]
+                bcur[0] = (i + 1) % 6
+                arr = tl.make_jobs([(bx[l["K"]], l["ring"][i], l["gbits"], y, M, l["N"], l["K"]) for l, y in zip(blay, by)])
+                st = L.tl_ternary_gemm_grouped(arr, len(arr), stream)
+                if st != tl.TL_OK:
+                    raise tl.TlError(st, "tl_ternary_gemm_grouped")
+
+            reps = max(1, min(args.steps, 60))
+            us = timed(block_step, reps) * 1e3 / reps
+            bb = sum(algorithmic_bytes(M, l["N"], l["K"]) for l in blay)
+            block.append(dict(M=M, layers=[l["name"] for l in blay], algorithmic_bytes=bb, us=round(us, 2),
+                              GBps=round(bb / us / 1e3, 1), hbm_frac=round(bb / us / 1e3 / HBM_PEAK_GBS, 4)))
+        del blay
+
     # dominant kernel: the small-M kernel in its grouped launch; one launch = one step
     us_launch = ms_per_step * 1e3
     traffic = None
@@ -279,7 +314,7 @@ def main():
                    "gemms_per_step": len(calls), "launches_per_step": 1, "weight_ring_copies": {n: layers[n]["copies"] for n in layers},
                    "algorithmic_bytes_per_step": step_bytes},
         "hbm_frac_of_peak": round(value / HBM_PEAK_GBS, 4),
-        "roofline": roofline, "cpu_baseline": cpu, "single_calls": single, "per_call": per_call, "prefill": prefill, "mid_batch": mid_batch,
+        "roofline": roofline, "cpu_baseline": cpu, "single_calls": single, "per_call": per_call, "prefill": prefill, "mid_batch": mid_batch, "block": block,
         "launch_mode": "eager" if args.eager else "hip_graph_replay",
         "host_wall_ms_timed_region_incl_capture": round(wall_ms, 2), "context": PAPER_CONTEXT,
     }
