@@ -35,7 +35,8 @@ constexpr int64_t kGemvMaxM = 128;
 
 // Small-M kernel (blocks of 16 activation rows that each stream W) or LDS-tiled MFMA kernel,
 // when both can run the shape: whichever the measured cost models below make cheaper.  The
-// small-M kernel streams W once per block of 16 rows at about 5.6 TB/s (0.9 us at least); the
+// small-M kernel streams W once per block of 16 rows at about 5.6 TB/s (0.9 us at least; blocks
+// of 32 rows cost 1.35 times as much, plus 4 us for their shorter items); the
 // MFMA kernel walks K in steps of 64 at 0.72 us per step while its 128 x 128 tiles number at
 // most one per CU, else at 0.95 us per step and 256 tiles of 128 x 256.
 inline bool prefer_small_m(int64_t M, int64_t N, int64_t K)
@@ -43,7 +44,8 @@ inline bool prefer_small_m(int64_t M, int64_t N, int64_t K)
     if (M <= 16) return true;
     const double w_bytes = double(N) * double(K) / 4.0;
     const double per_block = w_bytes / 5.6e6 > 0.9 ? w_bytes / 5.6e6 : 0.9;
-    const double t_small = double((M + 15) / 16) * per_block;
+    const double t_small = tl::gemv_two_blocks(M, N, K) ? 4.0 + double((M + 31) / 32) * 1.35 * per_block
+                                                        : double((M + 15) / 16) * per_block;
     const double wide = double((M + 127) / 128) * double((N + 255) / 256);
     const double per_step = wide <= 128.0 ? 0.72 : 0.95 * (wide > 256.0 ? wide / 256.0 : 1.0);
     const double t_mfma = double(K / 64) * per_step;

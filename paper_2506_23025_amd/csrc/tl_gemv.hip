@@ -429,7 +429,10 @@ constexpr int stream_wave_lds(int T)
 // The loop body holds nothing but weight loads and the output stores, which is what keeps the
 // compiler's wait counts exact; the last item is a second copy of the body without refills.
 // PASSES: some job of the launch has K longer than the waves' slices together.
-template <int T, bool MULTI, bool PASSES>
+// NB: blocks of 16 activation rows a job may have (1 or 2).  With two, every decoded weight
+// operand feeds two MFMAs, one per block: the decode, which is what limits the kernel, is paid
+// once for 32 rows (not combined with PASSES).
+template <int T, bool MULTI, bool PASSES, int NB>
 __global__ void __launch_bounds__(512)
 gemv_stream_kernel(GemvBatch b)
 {
@@ -438,8 +441,9 @@ gemv_stream_kernel(GemvBatch b)
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int NW = blockDim.x >> 6;
     // LDS of a wave: activation rows (16 KB) while the operands are built; afterwards two tile
-    // regions at 0 and 2 KB, and from 4 KB two sets of T partial-sum tiles (1 KB each).
-    constexpr int kStride = stream_wave_lds(T);
+    // regions at 0 and 2 KB, and from 4 KB two sets of T NB partial-sum tiles (1 KB each).
+    static_assert(NB == 1 || !PASSES, "two row blocks are not combined with passes over K");
+    constexpr int kStride = stream_wave_lds(T * NB);
     unsigned char* const my_lds = lds_raw + wave * kStride;
 
     const int lr = lane >> 3, lc = lane & 7;   // load mapping: row of the half tile, chunk of the slice
@@ -500,8 +504,10 @@ gemv_stream_kernel(GemvBatch b)
         wreg[t][1] = __builtin_nontemporal_load((gptr)(tb + off1));
     };
 
-    uint32_t breg[2][4][8];                    // this wave's activations as MFMA B operands
-    f32x4 nsx = f32x4{0.f, 0.f, 0.f, 0.f};     // -2^-20 sum_k x[m][k] over the slice, as an accumulator
+    uint32_t breg[NB][2][4][8];                // this wave's activations as MFMA B operands, per row block
+    f32x4 nsx[NB];                             // -2^-20 sum_k x[m][k] over the slice, as an accumulator
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) nsx[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
     // Start of a pass: fetch this wave's activation slice and the first item's weights together,
     // then turn the activations into operand registers.
     auto begin_pass = [&](int pass) {
@@ -512,59 +518,72 @@ gemv_stream_kernel(GemvBatch b)
         if (chunk >= J.chunks) chunk = 0;                  // past K: multiplied by zero activations
         col_off = uint32_t(chunk) * 16u;
     }
-    nsx = f32x4{0.f, 0.f, 0.f, 0.f};
-    if (active) {
-        // activation rows by LDS-DMA, swizzled: lane l fetches piece l ^ (r & 7) of row r
-        for (int r = 0; r < J.MR; ++r) {
-            const int rr = r < J.Mrem ? r : J.Mrem - 1;
-            const int kx = slice * kSliceK + ((lane ^ (r & 7)) << 3);
-            if (kx < J.K) {
-                __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void*)(J.xb + size_t(rr) * J.K * 2 + uint32_t(kx) * 2u),
-                    (__attribute__((address_space(3))) void*)(my_lds + r * 1024),
-                    16, 0, 0);
-            } else {
-                *reinterpret_cast<u32x4*>(my_lds + r * 1024 + (uint32_t(lane) << 4)) = u32x4{0u, 0u, 0u, 0u};
-            }
-        }
 #pragma unroll
-        for (int t = 0; t < T; ++t) issue_w(tile0, t);
-        // the compiler does not track LDS-DMA: wait until only the 2T weight loads are outstanding
-        __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * T));
-        const int xrow = mi & (J.MR - 1);
-        const uint32_t xr_off = uint32_t(xrow) * 1024u + uint32_t(mg) * 128u;
-        const uint32_t sw = uint32_t(xrow & 7);
-        // breg[h][wd][e]: (x[k], x[k + 8]) with k = slice0 + 64 (4h + g) + 16 wd + e
+    for (int nb = 0; nb < NB; ++nb) nsx[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int h = 0; h < 2; ++h)
-#pragma unroll
-            for (int wd = 0; wd < 4; ++wd) {
-                const u32x4 lo = *reinterpret_cast<const u32x4*>(
-                    my_lds + xr_off + h * 512 + ((uint32_t(2 * wd) ^ sw) << 4));
-                const u32x4 hi = *reinterpret_cast<const u32x4*>(
-                    my_lds + xr_off + h * 512 + ((uint32_t(2 * wd + 1) ^ sw) << 4));
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    breg[h][wd][2 * r] = __builtin_amdgcn_perm(hi[r], lo[r], 0x05040100u);
-                    breg[h][wd][2 * r + 1] = __builtin_amdgcn_perm(hi[r], lo[r], 0x07060302u);
+    for (int nb = 0; nb < NB; ++nb) {
+        // rows of this block: block 0 takes the first 16 (or fewer), block 1 what is left
+        const int rows = nb == 0 ? (J.Mrem < 16 ? J.Mrem : 16) : J.Mrem - 16;
+        int mr = 1;
+        while (mr < rows) mr *= 2;
+        if (active && rows > 0) {
+            // activation rows by LDS-DMA, swizzled: lane l fetches piece l ^ (r & 7) of row r
+            for (int r = 0; r < mr; ++r) {
+                const int rr = 16 * nb + (r < rows ? r : rows - 1);
+                const int kx = slice * kSliceK + ((lane ^ (r & 7)) << 3);
+                if (kx < J.K) {
+                    __builtin_amdgcn_global_load_lds(
+                        (const __attribute__((address_space(1))) void*)(J.xb + size_t(rr) * J.K * 2 + uint32_t(kx) * 2u),
+                        (__attribute__((address_space(3))) void*)(my_lds + r * 1024),
+                        16, 0, 0);
+                } else {
+                    *reinterpret_cast<u32x4*>(my_lds + r * 1024 + (uint32_t(lane) << 4)) = u32x4{0u, 0u, 0u, 0u};
                 }
             }
-        const uint32_t c = 0x80108010u;                   // fp16 pair of -2^-20
-        const u32x4 a = u32x4{c, c, c, c};
+            if (nb == 0) {
 #pragma unroll
-        for (int h = 0; h < 2; ++h)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const u32x4 bb = u32x4{breg[h][0][e], breg[h][1][e], breg[h][2][e], breg[h][3][e]};
-                nsx = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), as_f16x8(bb), nsx, 0, 0, 0);
+                for (int t = 0; t < T; ++t) issue_w(tile0, t);
+                // the compiler does not track LDS-DMA: wait until only the 2T weight loads are outstanding
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * T));
+            } else {
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // requested after the weights: wait for all
             }
-    } else {
+            const int xrow = mi & (mr - 1);
+            const uint32_t xr_off = uint32_t(xrow) * 1024u + uint32_t(mg) * 128u;
+            const uint32_t sw = uint32_t(xrow & 7);
+            // breg[nb][h][wd][e]: (x[k], x[k + 8]) with k = slice0 + 64 (4h + g) + 16 wd + e
 #pragma unroll
-        for (int h = 0; h < 2; ++h)
+            for (int h = 0; h < 2; ++h)
 #pragma unroll
-            for (int wd = 0; wd < 4; ++wd)
+                for (int wd = 0; wd < 4; ++wd) {
+                    const u32x4 lo = *reinterpret_cast<const u32x4*>(
+                        my_lds + xr_off + h * 512 + ((uint32_t(2 * wd) ^ sw) << 4));
+                    const u32x4 hi = *reinterpret_cast<const u32x4*>(
+                        my_lds + xr_off + h * 512 + ((uint32_t(2 * wd + 1) ^ sw) << 4));
 #pragma unroll
-                for (int e = 0; e < 8; ++e) breg[h][wd][e] = 0u;
+                    for (int r = 0; r < 4; ++r) {
+                        breg[nb][h][wd][2 * r] = __builtin_amdgcn_perm(hi[r], lo[r], 0x05040100u);
+                        breg[nb][h][wd][2 * r + 1] = __builtin_amdgcn_perm(hi[r], lo[r], 0x07060302u);
+                    }
+                }
+            const uint32_t c = 0x80108010u;               // fp16 pair of -2^-20
+            const u32x4 a = u32x4{c, c, c, c};
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const u32x4 bb = u32x4{breg[nb][h][0][e], breg[nb][h][1][e], breg[nb][h][2][e], breg[nb][h][3][e]};
+                    nsx[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), as_f16x8(bb), nsx[nb], 0, 0, 0);
+                }
+            if (NB > 1 && nb == 0) __builtin_amdgcn_s_waitcnt(0xF | (0x3 << 14) | (0x7 << 4));   // staging read before it is refilled
+        } else {
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int wd = 0; wd < 4; ++wd)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) breg[nb][h][wd][e] = 0u;
+        }
     }
     };
 
@@ -575,9 +594,11 @@ gemv_stream_kernel(GemvBatch b)
         constexpr bool REFILL = decltype(refill_tag)::value;
         const bool first_pass = PASSES ? first_pass_rt : true;
         const bool last_pass = PASSES ? last_pass_rt : true;
-        f32x4 part[T];
+        f32x4 part[NB][T];
 #pragma unroll
-        for (int t = 0; t < T; ++t) part[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int t = 0; t < T; ++t) part[nb][t] = f32x4{0.f, 0.f, 0.f, 0.f};
         if (active) {
 #pragma unroll
             for (int t = 0; t < T; ++t) {
@@ -586,7 +607,13 @@ gemv_stream_kernel(GemvBatch b)
                 *reinterpret_cast<u32x4*>(reg_t + 1024 + ww_off) = wreg[t][1];
                 if constexpr (REFILL) issue_w(first + T, t);
                 if (REFILL || first + t < tile_end) {      // the last item may be short
-                    f32x4 acc[3] = {nsx, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+                    f32x4 acc[NB][3];
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) {
+                        acc[nb][0] = nsx[nb];
+                        acc[nb][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+                        acc[nb][2] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    }
 #pragma unroll
                     for (int h = 0; h < 2; ++h) {
                         const u32x4 wv = *reinterpret_cast<const u32x4*>(reg_t + (h ? wr_off1 : wr_off0));
@@ -600,30 +627,40 @@ gemv_stream_kernel(GemvBatch b)
                             const int j = e < 2 ? e : (e < 5 ? e - 2 : e - 5);
                             const uint32_t mask = 0x00300030u << (2 * j);
                             const u32x4 a = sh[src] & mask;
-                            const u32x4 bb = u32x4{breg[h][0][e], breg[h][1][e], breg[h][2][e], breg[h][3][e]};
-                            acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), as_f16x8(bb), acc[j], 0, 0, 0);
+#pragma unroll
+                            for (int nb = 0; nb < NB; ++nb) {
+                                const u32x4 bb = u32x4{breg[nb][h][0][e], breg[nb][h][1][e], breg[nb][h][2][e], breg[nb][h][3][e]};
+                                acc[nb][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), as_f16x8(bb), acc[nb][j], 0, 0, 0);
+                            }
                         }
                     }
-                    part[t] = acc[0] * 1048576.f + acc[1] * 262144.f + acc[2] * 65536.f;
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb)
+                        part[nb][t] = acc[nb][0] * 1048576.f + acc[nb][1] * 262144.f + acc[nb][2] * 65536.f;
                 }
             }
         }
         // split-K: partial sums into this wave's set `parity`, one barrier, fixed-order sum.
         // The other set is still being read by waves that lag one item behind, never more:
         // they must pass this item's barrier before anybody writes that set again.
-        unsigned char* const red = my_lds + 4096 + parity * (T * 1024);
+        unsigned char* const red = my_lds + 4096 + parity * (T * NB * 1024);
 #pragma unroll
-        for (int t = 0; t < T; ++t) reinterpret_cast<f32x4*>(red + t * 1024)[lane] = part[t];
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int t = 0; t < T; ++t) reinterpret_cast<f32x4*>(red + (nb * T + t) * 1024)[lane] = part[nb][t];
         __builtin_amdgcn_s_waitcnt(0xF | (0x3 << 14) | (0x7 << 4));     // lgkmcnt(0): LDS only, loads stay in flight
         __builtin_amdgcn_s_barrier();
-        if (const int o = threadIdx.x; o < T * 64) {       // T <= waves: one output quad per thread
-            const int t = o >> 6;
+        if (const int o = threadIdx.x; o < T * NB * 64) {  // T NB <= waves: one output quad per thread
+            const int q = o >> 6;                           // nb * T + t
+            const int nb = q / T;
+            const int t = q - nb * T;
             const int l = o & 63;
+            const int row = 16 * nb + (l & 15);
             const int tile = first + t;
             f32x4 v[8];
 #pragma unroll
             for (int w = 0; w < 8; ++w)
-                v[w] = (w < NW) ? reinterpret_cast<const f32x4*>(lds_raw + w * kStride + 4096 + parity * (T * 1024) + t * 1024)[l]
+                v[w] = (w < NW) ? reinterpret_cast<const f32x4*>(lds_raw + w * kStride + 4096 + parity * (T * NB * 1024) + q * 1024)[l]
                                 : f32x4{0.f, 0.f, 0.f, 0.f};
             f32x4 s = ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
             // sums of the earlier passes over K: kept by the thread that owns this output quad
@@ -631,9 +668,9 @@ gemv_stream_kernel(GemvBatch b)
             if (!first_pass && tile < tile_end) s += *keep;
             if (!last_pass && tile < tile_end) *keep = s;
             const int n = tile * 16 + 4 * (l >> 4);
-            if (last_pass && tile < tile_end && (l & 15) < J.Mrem) {
+            if (last_pass && tile < tile_end && row < J.Mrem) {
                 typedef __attribute__((address_space(1))) __half* gh_ptr;
-                gh_ptr dst = (gh_ptr)(J.y + size_t(l & 15) * J.N + n);
+                gh_ptr dst = (gh_ptr)(J.y + size_t(row) * J.N + n);
                 const float gamma = J.gamma;
                 if (n + 3 < J.N && (J.N & 3) == 0) {       // four consecutive n: one 8-byte store
                     const f16x2 lo = {(_Float16)(gamma * s[0]), (_Float16)(gamma * s[1])};
@@ -685,15 +722,19 @@ template <bool MULTI, bool PASSES>
 KernelFn pick_stream_t(int T)
 {
     switch (T) {
-        case 1: return gemv_stream_kernel<1, MULTI, PASSES>;
-        case 2: return gemv_stream_kernel<2, MULTI, PASSES>;
-        case 3: return gemv_stream_kernel<3, MULTI, PASSES>;
-        default: return gemv_stream_kernel<4, MULTI, PASSES>;
+        case 1: return gemv_stream_kernel<1, MULTI, PASSES, 1>;
+        case 2: return gemv_stream_kernel<2, MULTI, PASSES, 1>;
+        case 3: return gemv_stream_kernel<3, MULTI, PASSES, 1>;
+        default: return gemv_stream_kernel<4, MULTI, PASSES, 1>;
     }
 }
 
-KernelFn pick_stream(int T, bool multi, bool passes)
+KernelFn pick_stream(int T, bool multi, bool passes, int nb)
 {
+    if (nb == 2) {                                         // two row blocks: T <= 2, one pass over K
+        if (T == 1) return multi ? gemv_stream_kernel<1, true, false, 2> : gemv_stream_kernel<1, false, false, 2>;
+        return multi ? gemv_stream_kernel<2, true, false, 2> : gemv_stream_kernel<2, false, false, 2>;
+    }
     if (passes) return multi ? pick_stream_t<true, true>(T) : pick_stream_t<false, true>(T);
     return multi ? pick_stream_t<true, false>(T) : pick_stream_t<false, false>(T);
 }
@@ -716,6 +757,7 @@ struct GemvPolicy {
     int t_grouped = 0;                  // 0: pick from the tile count
     int stream = 3;                     // bit 0: stream form for one job, bit 1: for several
     int stream_groups = 256;            // workgroups of the stream form (one per CU)
+    int two_blocks = 1;                 // jobs of more than 16 rows go in blocks of 32 (two row blocks per wave)
     int long_k_min_run = 3;             // K > 4096 streams if the call averages this many tile passes per workgroup
 };
 GemvPolicy g_policy;
@@ -728,7 +770,7 @@ constexpr int kStreamMaxRun = 32;       // tiles of a run whose sums fit the 32 
 // out to the jobs so that all finish together (see run_cost below); spare ones go to the job
 // with the costliest runs, one by one.  Returns hipErrorInvalidValue without launching if a multi-pass job's
 // runs would not fit the LDS (the caller then uses the general kernel).
-hipError_t launch_stream(GemvBatch& b, int max_slices, hipStream_t s)
+hipError_t launch_stream(GemvBatch& b, int max_slices, int nb, hipStream_t s)
 {
     const GemvPolicy pol = g_policy;
     const int NW = max_slices < kStreamWaves ? max_slices : kStreamWaves;
@@ -744,6 +786,11 @@ hipError_t launch_stream(GemvBatch& b, int max_slices, hipStream_t s)
     int T = int((total_cost + G - 1) / G);   // tiles per item: the whole run if it is short
     if (T > kTMax) T = kTMax;            // (8 tiles per item measured slower: 23.9 against 21.4 us)
     if (T > NW) T = NW;                  // the epilogue gives every thread at most one output quad
+    if (nb == 2) {                       // two row blocks per job: half the tiles per item (registers)
+        if (T > 2) T = 2;
+        if (2 * T > NW) T = NW / 2;
+        if (multi_pass || T < 1) return hipErrorInvalidValue;
+    }
     if (T < 1) T = 1;
     // Time of a workgroup of job j with w groups, in tile units: passes x (run + start-up), where
     // the start-up of a pass (a round trip for the activations) counts as 3 tiles for jobs of
@@ -796,26 +843,27 @@ hipError_t launch_stream(GemvBatch& b, int max_slices, hipStream_t s)
         grid += wg[j];
     }
     const int total_items = 0;
-    const size_t lds = size_t(NW) * stream_wave_lds(T) + (multi_pass ? size_t(kStreamMaxRun) * 1024 : 0);
+    const size_t lds = size_t(NW) * stream_wave_lds(T * nb) + (multi_pass ? size_t(kStreamMaxRun) * 1024 : 0);
     b.total_items = total_items;
     b.red_off = 0;
     b.pad = 0;
     const bool multi = b.count > 1;
-    KernelFn fn = pick_stream(T, multi, multi_pass);
-    static bool lds_raised[2][2][kTMax + 1];
-    if (!lds_raised[multi_pass][multi][T]) {
+    KernelFn fn = pick_stream(T, multi, multi_pass, nb);
+    static bool lds_raised[3][2][kTMax + 1];
+    const int variant = nb == 2 ? 2 : (multi_pass ? 1 : 0);
+    if (!lds_raised[variant][multi][T]) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
                                            hipFuncAttributeMaxDynamicSharedMemorySize,
                                            8 * stream_wave_lds(T) + kStreamMaxRun * 1024);
         if (e != hipSuccess) return e;
-        lds_raised[multi_pass][multi][T] = true;
+        lds_raised[variant][multi][T] = true;
     }
     hipLaunchKernelGGL(fn, dim3(grid), dim3(NW * 64), lds, s, b);
     return hipGetLastError();
 }
 
 // Launch one batch (<= kMaxJobs jobs, tiles / slices / M filled in): sets items and grid.
-hipError_t launch_batch(GemvBatch& b, bool grouped, bool stream_form, hipStream_t s)
+hipError_t launch_batch(GemvBatch& b, bool grouped, bool stream_form, int nb, hipStream_t s)
 {
     const GemvPolicy pol = g_policy;
     int64_t total_tiles = 0;
@@ -825,9 +873,10 @@ hipError_t launch_batch(GemvBatch& b, bool grouped, bool stream_form, hipStream_
         if (b.job[j].slices > max_slices) max_slices = b.job[j].slices;
     }
     if (stream_form && max_slices <= kStreamWaves * kStreamMaxPasses && (pol.stream & (b.count > 1 ? 2 : 1))) {
-        const hipError_t e = launch_stream(b, max_slices, s);
-        if (e != hipErrorInvalidValue) return e;           // else: runs too long for its LDS, general kernel
+        const hipError_t e = launch_stream(b, max_slices, nb, s);
+        if (e != hipErrorInvalidValue || nb != 1) return e;   // else: runs too long for its LDS, general kernel
     }
+    if (nb != 1) return hipErrorInvalidValue;              // jobs of two row blocks exist for the stream form only
     int NW = grouped ? pol.nw_grouped : pol.nw_single;
     if (NW > max_slices) NW = max_slices;
     int resident = grouped ? pol.grid_cap : (NW <= 4 ? 512 : 256);
@@ -879,6 +928,7 @@ extern "C" void tl_dev_stream(int stream, int groups, int long_k_min_run)
     g_policy.stream = stream; g_policy.stream_groups = groups;
     if (long_k_min_run > 0) g_policy.long_k_min_run = long_k_min_run;
 }
+extern "C" void tl_dev_two_blocks(int on) { g_policy.two_blocks = on; }
 #endif
 
 bool gemv_supports(int64_t M, int64_t N, int64_t K)
@@ -906,33 +956,41 @@ hipError_t launch_gemv_jobs(const GemmDesc* jobs, int count, hipStream_t s)
         call_cost += ((jobs[i].M + 15) / 16) * ((jobs[i].N + 15) / 16);      // tiles of the whole call
     }
     const bool long_k_streams = call_cost >= int64_t(g_policy.stream_groups) * g_policy.long_k_min_run;
-    GemvBatch bs, bg;
+    // bs: stream form; bs2: stream form with jobs of up to 32 rows (two blocks of 16 per wave);
+    // bg: general kernel
+    GemvBatch bs, bs2, bg;
     bs.count = 0;
+    bs2.count = 0;
     bg.count = 0;
     auto flush = [&](GemvBatch& b) -> hipError_t {
         if (b.count == 0) return hipSuccess;
-        hipError_t e = launch_batch(b, grouped, &b == &bs, s);
+        hipError_t e = launch_batch(b, grouped, &b != &bg, &b == &bs2 ? 2 : 1, s);
         b.count = 0;
         return e;
     };
+    const bool stream_on = (g_policy.stream & 3) == 3;
     for (int i = 0; i < count; ++i) {
         const GemmDesc& d = jobs[i];
-        for (int64_t m0 = 0; m0 < d.M; m0 += 16) {
+        const int slices = int((d.K + kSliceK - 1) / kSliceK);
+        // more than 16 rows and one pass over K: blocks of 32 rows, decoded once for both halves
+        const bool two_blocks = stream_on && g_policy.two_blocks && gemv_two_blocks(d.M, d.N, d.K);
+        const int64_t mstep = two_blocks ? 32 : 16;
+        for (int64_t m0 = 0; m0 < d.M; m0 += mstep) {
             GemvJob j;
             j.x = d.x + m0 * d.K;
             j.W = d.W;
             j.y = d.y + m0 * d.N;
             j.gamma = d.gamma;
-            j.Mrem = int(d.M - m0 < 16 ? d.M - m0 : 16);
+            j.Mrem = int(d.M - m0 < mstep ? d.M - m0 : mstep);
             j.N = int(d.N); j.K = int(d.K);
             j.tiles = int((d.N + 15) / 16);
             j.items = 0;
-            j.slices = int((d.K + kSliceK - 1) / kSliceK);
-            j.mr = pow2_at_least(j.Mrem);
+            j.slices = slices;
+            j.mr = pow2_at_least(j.Mrem < 16 ? j.Mrem : 16);
             j.pad[0] = j.pad[1] = 0;
             const bool streams = j.slices <= kStreamWaves ||
                                  (long_k_streams && j.slices <= kStreamWaves * kStreamMaxPasses);
-            GemvBatch& b = streams ? bs : bg;
+            GemvBatch& b = two_blocks ? bs2 : (streams ? bs : bg);
             b.job[b.count++] = j;
             if (b.count == kMaxJobs) {
                 hipError_t e = flush(b);
@@ -941,6 +999,8 @@ hipError_t launch_gemv_jobs(const GemmDesc* jobs, int count, hipStream_t s)
         }
     }
     hipError_t e = flush(bs);
+    if (e != hipSuccess) return e;
+    e = flush(bs2);
     if (e != hipSuccess) return e;
     return flush(bg);
 }

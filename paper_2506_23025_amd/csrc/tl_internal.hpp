@@ -42,6 +42,17 @@ struct GemmDesc {
 bool gemv_supports(int64_t M, int64_t N, int64_t K);
 hipError_t launch_gemv(const __half* x, const uint32_t* Wp, float gamma, __half* y,
                        int64_t M, int64_t N, int64_t K, hipStream_t s);
+// Whether the small-M kernel takes a GEMM in blocks of 32 activation rows (every decoded weight
+// operand feeds two MFMAs) rather than 16.  It halves the passes over W but shortens the items,
+// which pays when W is re-read from beyond the L2 cache or the blocks are many (measured:
+// 4096 -> 14336 from M = 64 on, 4096 -> 4096 from M = 384 on).
+inline bool gemv_two_blocks(int64_t M, int64_t N, int64_t K)
+{
+    const int64_t slices = (K + 511) / 512;
+    if (M <= 16 || slices < 2 || slices > 8) return false;
+    return (M >= 64 && N * K / 4 >= (int64_t(8) << 20)) || M >= 384;
+}
+
 // Several independent GEMMs (each passing gemv_supports) in as few launches as possible.
 hipError_t launch_gemv_jobs(const GemmDesc* jobs, int count, hipStream_t s);
 

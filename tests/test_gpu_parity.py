@@ -199,6 +199,24 @@ def test_config3_block_single_and_grouped(M):
         assert_close(y, y1.astype(np.float64), x, g, f"block {name} M={M}, grouped against single")
 
 
+@pytest.mark.parametrize("M,N,K", [(77, 8200, 4096), (390, 130, 1024), (64, 14336, 4096), (400, 33, 2048)])
+def test_small_m_kernel_blocks_of_32_rows(M, N, K):
+    # shapes the small-M kernel takes in blocks of 32 activation rows (two row blocks per wave):
+    # ragged last block (77 = 32 + 32 + 13, 390 = 12 x 32 + 6), ragged N, several launches (M = 400)
+    x, W, g = si.layer(8800 + M + N + K, M, N, K)
+    Wp = tl.tl_pack_2bit(W)
+    y = run_gemm(x, Wp, g, N, K, tl.TL_PATH_GEMV)
+    if N * K <= 4096 * 1024:
+        assert_close(y, oracle.gemm_packed2(x, Wp, g, K), x, g, f"blocks of 32 rows {M}x{N}x{K}")
+    else:
+        cols = np.sort(np.random.default_rng(M).choice(N, 300, replace=False))
+        cols[0], cols[-1] = 0, N - 1
+        assert_close(y[:, cols], oracle.gemm(x, np.ascontiguousarray(W[cols]), g), x, g,
+                     f"blocks of 32 rows {M}x{N}x{K} sampled")
+    # bit for bit the same on a second run
+    assert np.array_equal(y.view(np.uint16), run_gemm(x, Wp, g, N, K, tl.TL_PATH_GEMV).view(np.uint16))
+
+
 # ---------------------------------------------------------------- MFMA prefill kernel
 
 MFMA_SHAPES = [
