@@ -50,6 +50,14 @@ constexpr int vmcnt_imm3(int n)
 
 __device__ __forceinline__ f16x8 as_h8(u32x4 v) { return __builtin_bit_cast(f16x8, v); }
 
+// Barrier that waits for this wave's LDS traffic only; the weight loads and activation
+// transfers already requested stay in flight across it (__syncthreads would drain them).
+__device__ __forceinline__ void lds_barrier3()
+{
+    __builtin_amdgcn_s_waitcnt(0xF | (0x3 << 14) | (0x7 << 4));      // lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
+}
+
 template <int T>
 __global__ void __launch_bounds__(512)
 gemv3_kernel(Gemv3Params p)
@@ -153,7 +161,7 @@ gemv3_kernel(Gemv3Params p)
         }
         lut[b] = (c[0] << 4) | (c[1] << 6) | (c[2] << 8) | (c[3] << 20) | (c[4] << 22);
     }
-    __syncthreads();
+    lds_barrier3();
     if (wave < slices) __builtin_amdgcn_s_waitcnt(vmcnt_imm3(2 * T));   // LDS-DMA is not tracked by the compiler
 
     for (; slice < slices; slice += NW) {
@@ -230,11 +238,11 @@ gemv3_kernel(Gemv3Params p)
     }
 
     // ---- split-K reduction across the waves, epilogue ----
-    __syncthreads();
+    lds_barrier3();
     f32x4* red = reinterpret_cast<f32x4*>(lds_raw + kLutBytes);
 #pragma unroll
     for (int t = 0; t < T; ++t) red[(t * NW + wave) * 64 + lane] = part_acc[t];
-    __syncthreads();
+    lds_barrier3();
     for (int item = threadIdx.x; item < T * 64; item += blockDim.x) {
         const int t = item >> 6;
         const int l = item & 63;
