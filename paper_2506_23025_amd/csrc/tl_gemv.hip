@@ -527,17 +527,32 @@ gemv_stream_kernel(GemvBatch b)
         int mr = 1;
         while (mr < rows) mr *= 2;
         if (active && rows > 0) {
-            // activation rows by LDS-DMA, swizzled: lane l fetches piece l ^ (r & 7) of row r
-            for (int r = 0; r < mr; ++r) {
-                const int rr = 16 * nb + (r < rows ? r : rows - 1);
-                const int kx = slice * kSliceK + ((lane ^ (r & 7)) << 3);
-                if (kx < J.K) {
+            // activation rows by LDS-DMA, swizzled: lane l fetches piece l ^ (r & 7) of row r.
+            // Kept as short rolled loops: this is on the way to the first weight load, and at
+            // the start of a kernel every instruction line is a miss in the instruction cache.
+            if ((slice + 1) * kSliceK <= J.K) {            // the whole slice lies inside K
+                const unsigned char* const src0 = J.xb + size_t(16 * nb) * J.K * 2 + size_t(slice) * (kSliceK * 2);
+#pragma unroll 1
+                for (int r = 0; r < mr; ++r) {
+                    const int rr = r < rows ? r : rows - 1;
                     __builtin_amdgcn_global_load_lds(
-                        (const __attribute__((address_space(1))) void*)(J.xb + size_t(rr) * J.K * 2 + uint32_t(kx) * 2u),
+                        (const __attribute__((address_space(1))) void*)(src0 + size_t(rr) * J.K * 2 + (uint32_t(lane ^ (r & 7)) << 4)),
                         (__attribute__((address_space(3))) void*)(my_lds + r * 1024),
                         16, 0, 0);
-                } else {
-                    *reinterpret_cast<u32x4*>(my_lds + r * 1024 + (uint32_t(lane) << 4)) = u32x4{0u, 0u, 0u, 0u};
+                }
+            } else {
+#pragma unroll 1
+                for (int r = 0; r < mr; ++r) {
+                    const int rr = 16 * nb + (r < rows ? r : rows - 1);
+                    const int kx = slice * kSliceK + ((lane ^ (r & 7)) << 3);
+                    if (kx < J.K) {
+                        __builtin_amdgcn_global_load_lds(
+                            (const __attribute__((address_space(1))) void*)(J.xb + size_t(rr) * J.K * 2 + uint32_t(kx) * 2u),
+                            (__attribute__((address_space(3))) void*)(my_lds + r * 1024),
+                            16, 0, 0);
+                    } else {
+                        *reinterpret_cast<u32x4*>(my_lds + r * 1024 + (uint32_t(lane) << 4)) = u32x4{0u, 0u, 0u, 0u};
+                    }
                 }
             }
             if (nb == 0) {
