@@ -773,6 +773,8 @@ struct GemvPolicy {
     int stream = 3;                     // bit 0: stream form for one job, bit 1: for several
     int stream_groups = 256;            // workgroups of the stream form (one per CU)
     int two_blocks = 1;                 // jobs of more than 16 rows go in blocks of 32 (two row blocks per wave)
+    double start_up_per_row = 0.2;      // stream form: start-up of a pass in tiles per activation row
+    int t_stream = 0;                   // stream form: cap on tiles per item (0: none)
     int long_k_min_run = 3;             // K > 4096 streams if the call averages this many tile passes per workgroup
 };
 GemvPolicy g_policy;
@@ -790,33 +792,27 @@ hipError_t launch_stream(GemvBatch& b, int max_slices, int nb, hipStream_t s)
     const GemvPolicy pol = g_policy;
     const int NW = max_slices < kStreamWaves ? max_slices : kStreamWaves;
     auto passes = [&](int j) { return (b.job[j].slices + NW - 1) / NW; };
-    int64_t total_cost = 0, total_tiles = 0;
+    int64_t total_tiles = 0;
     bool multi_pass = false;
     for (int j = 0; j < b.count; ++j) {
-        total_cost += int64_t(b.job[j].tiles) * passes(j);
         total_tiles += b.job[j].tiles;
         multi_pass |= passes(j) > 1;
     }
     const int G = total_tiles < pol.stream_groups ? int(total_tiles) : pol.stream_groups;
-    int T = int((total_cost + G - 1) / G);   // tiles per item: the whole run if it is short
-    if (T > kTMax) T = kTMax;            // (8 tiles per item measured slower: 23.9 against 21.4 us)
-    if (T > NW) T = NW;                  // the epilogue gives every thread at most one output quad
-    if (nb == 2) {                       // two row blocks per job: half the tiles per item (registers)
-        if (T > 2) T = 2;
-        if (2 * T > NW) T = NW / 2;
-        if (multi_pass || T < 1) return hipErrorInvalidValue;
-    }
-    if (T < 1) T = 1;
-    // Time of a workgroup of job j with w groups, in tile units: passes x (run + start-up), where
-    // the start-up of a pass (a round trip for the activations) counts as 3 tiles for jobs of
-    // several passes.  Bisection on the common finishing time gives the group counts.
+    // Time of a workgroup of job j with w groups, in tile units: passes x (run + start-up).  The
+    // start-up of a pass is fetching the activation slice (1 KB per row and wave through the
+    // same address path as the weights) and building the operands: measured 0.2 tiles per
+    // activation row; a job of several passes waits for that round trip in every pass but the
+    // first, counted as 3 tiles more.  Bisection on the common finishing time gives the group counts.
+    auto start_up = [&](int j) {
+        const int rows = b.job[j].Mrem < 16 * nb ? b.job[j].Mrem : 16 * nb;
+        return pol.start_up_per_row * double(rows) + (passes(j) > 1 ? 3.0 : 0.0);
+    };
     auto run_cost = [&](int j, int w) {
-        const int p = passes(j);
-        return double(p) * (double((b.job[j].tiles + w - 1) / w) + (p > 1 ? 3.0 : 0.0));
+        return double(passes(j)) * (double((b.job[j].tiles + w - 1) / w) + start_up(j));
     };
     auto groups_for = [&](int j, double tau) {            // fewest groups that finish job j by tau
-        const int p = passes(j);
-        const double per = tau / double(p) - (p > 1 ? 3.0 : 0.0);
+        const double per = tau / double(passes(j)) - start_up(j);
         if (per < 1.0) return b.job[j].tiles;
         const int w = int((double(b.job[j].tiles) + per - 1.0) / per);
         return w < 1 ? 1 : (w > b.job[j].tiles ? b.job[j].tiles : w);
@@ -846,8 +842,25 @@ hipError_t launch_stream(GemvBatch& b, int max_slices, int nb, hipStream_t s)
         if (best < 0) break;
         --wg[best]; --used;
     }
-    for (int j = 0; j < b.count; ++j)
-        if (passes(j) > 1 && (b.job[j].tiles + wg[j] - 1) / wg[j] > kStreamMaxRun) return hipErrorInvalidValue;
+    int run = 1;                                           // longest run of tiles of a workgroup
+    for (int j = 0; j < b.count; ++j) {
+        const int r = (b.job[j].tiles + wg[j] - 1) / wg[j];
+        if (passes(j) > 1 && r > kStreamMaxRun) return hipErrorInvalidValue;
+        if (r > run) run = r;
+    }
+    // Tiles per item.  Measured: items of 3 tiles stream 3-4 % faster than items of 4 (6 KB
+    // against 8 KB requested per wave at a time; with more in flight the memory system slows
+    // down), a run of 4 goes best as 2 + 2 (the second pair loads while the first is decoded),
+    // and shorter runs are one item.
+    int T = run <= 3 ? run : (run == 4 ? 2 : 3);
+    if (T > NW) T = NW;                  // the epilogue gives every thread at most one output quad
+    if (pol.t_stream > 0 && T > pol.t_stream) T = pol.t_stream;
+    if (nb == 2) {                       // two row blocks per job: at most 2 tiles per item (registers)
+        if (T > 2) T = 2;
+        if (2 * T > NW) T = NW / 2;
+        if (multi_pass || T < 1) return hipErrorInvalidValue;
+    }
+    if (T < 1) T = 1;
     for (int j = 0; j < kMaxJobs; ++j) b.item0[j] = 0x7fffffff;
     int grid = 0;
     for (int j = 0; j < b.count; ++j) {
@@ -944,6 +957,8 @@ extern "C" void tl_dev_stream(int stream, int groups, int long_k_min_run)
     if (long_k_min_run > 0) g_policy.long_k_min_run = long_k_min_run;
 }
 extern "C" void tl_dev_two_blocks(int on) { g_policy.two_blocks = on; }
+extern "C" void tl_dev_stream_t(int t) { g_policy.t_stream = t; }
+extern "C" void tl_dev_start_up(double v) { g_policy.start_up_per_row = v; }
 #endif
 
 bool gemv_supports(int64_t M, int64_t N, int64_t K)
