@@ -530,29 +530,30 @@ gemv_stream_kernel(GemvBatch b)
             // activation rows by LDS-DMA, swizzled: lane l fetches piece l ^ (r & 7) of row r.
             // Kept as short rolled loops: this is on the way to the first weight load, and at
             // the start of a kernel every instruction line is a miss in the instruction cache.
+            // Staged rows past `rows` are never written: an MFMA column depends on its own column
+            // of B alone, and the outputs of those columns are not stored.
+            typedef const __attribute__((address_space(1))) unsigned char* gbytes;
+            const size_t row_stride = size_t(J.K) * 2;
+            gbytes src = (gbytes)(J.xb + size_t(16 * nb) * row_stride + size_t(slice) * (kSliceK * 2));
             if ((slice + 1) * kSliceK <= J.K) {            // the whole slice lies inside K
-                const unsigned char* const src0 = J.xb + size_t(16 * nb) * J.K * 2 + size_t(slice) * (kSliceK * 2);
+                const uint32_t lane16 = uint32_t(lane) << 4;
 #pragma unroll 1
-                for (int r = 0; r < mr; ++r) {
-                    const int rr = r < rows ? r : rows - 1;
-                    __builtin_amdgcn_global_load_lds(
-                        (const __attribute__((address_space(1))) void*)(src0 + size_t(rr) * J.K * 2 + (uint32_t(lane ^ (r & 7)) << 4)),
-                        (__attribute__((address_space(3))) void*)(my_lds + r * 1024),
-                        16, 0, 0);
+                for (int r = 0; r < rows; ++r) {
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + (lane16 ^ (uint32_t(r & 7) << 4))),
+                                                     (__attribute__((address_space(3))) void*)(my_lds + r * 1024), 16, 0, 0);
+                    src += row_stride;
                 }
             } else {
 #pragma unroll 1
-                for (int r = 0; r < mr; ++r) {
-                    const int rr = 16 * nb + (r < rows ? r : rows - 1);
-                    const int kx = slice * kSliceK + ((lane ^ (r & 7)) << 3);
-                    if (kx < J.K) {
-                        __builtin_amdgcn_global_load_lds(
-                            (const __attribute__((address_space(1))) void*)(J.xb + size_t(rr) * J.K * 2 + uint32_t(kx) * 2u),
-                            (__attribute__((address_space(3))) void*)(my_lds + r * 1024),
-                            16, 0, 0);
+                for (int r = 0; r < rows; ++r) {
+                    const int kk = (lane ^ (r & 7)) << 3;  // first of this lane's 8 activations within the slice
+                    if (slice * kSliceK + kk < J.K) {
+                        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + uint32_t(kk) * 2u),
+                                                         (__attribute__((address_space(3))) void*)(my_lds + r * 1024), 16, 0, 0);
                     } else {
                         *reinterpret_cast<u32x4*>(my_lds + r * 1024 + (uint32_t(lane) << 4)) = u32x4{0u, 0u, 0u, 0u};
                     }
+                    src += row_stride;
                 }
             }
             if (nb == 0) {
@@ -773,7 +774,7 @@ struct GemvPolicy {
     int stream = 3;                     // bit 0: stream form for one job, bit 1: for several
     int stream_groups = 256;            // workgroups of the stream form (one per CU)
     int two_blocks = 1;                 // jobs of more than 16 rows go in blocks of 32 (two row blocks per wave)
-    double start_up_per_row = 0.2;      // stream form: start-up of a pass in tiles per activation row
+    double start_up_per_row = 0.15;     // stream form: start-up of a pass in tiles per activation row
     int t_stream = 0;                   // stream form: cap on tiles per item (0: none)
     int long_k_min_run = 3;             // K > 4096 streams if the call averages this many tile passes per workgroup
 };
@@ -801,7 +802,7 @@ hipError_t launch_stream(GemvBatch& b, int max_slices, int nb, hipStream_t s)
     const int G = total_tiles < pol.stream_groups ? int(total_tiles) : pol.stream_groups;
     // Time of a workgroup of job j with w groups, in tile units: passes x (run + start-up).  The
     // start-up of a pass is fetching the activation slice (1 KB per row and wave through the
-    // same address path as the weights) and building the operands: measured 0.2 tiles per
+    // same address path as the weights) and building the operands: measured about 0.15 tiles per
     // activation row; a job of several passes waits for that round trip in every pass but the
     // first, counted as 3 tiles more.  Bisection on the common finishing time gives the group counts.
     auto start_up = [&](int j) {
