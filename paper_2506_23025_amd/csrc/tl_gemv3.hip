@@ -8,15 +8,20 @@
 // What differs is the slice geometry and the decode:
 //
 //  * A slice is 128 packed bytes = 640 weights per row; a lane's 16 bytes hold 80 weights.
-//  * Decode is a table look-up: a 256-entry table in LDS maps a byte to its five digits
-//    c = w + 1, already placed where the 2-bit kernel's masks put them: low half-word
-//    c0 << 4 | c1 << 6 | c2 << 8, high half-word c3 << 4 | c4 << 6.  Three ANDs per byte give
-//    the fp16 (subnormal) pairs (c0, c3) 2^-20, (c1, c4) 2^-18 and (c2, 0) 2^-16, which feed
-//    v_mfma_f32_16x16x32_f16 against the activation pairs (x[5b], x[5b+3]), (x[5b+1], x[5b+4])
-//    and (x[5b+2], 0).  Per 5 weights: 2 address operations, 1 LDS read, 3 ANDs.
+//  * Decode is a table look-up: a 256-entry table of 8-byte entries in LDS maps a byte to its
+//    five digits c = w + 1 as fp16 (subnormal) pairs: word 0 = c0 << 4 | c2 << 8 | c3 << 20,
+//    word 1 = c1 << 4 | c4 << 20.  The two words of two neighbouring bytes, with c2 masked out
+//    of the first word of each, are one A operand of v_mfma_f32_16x16x32_f16 as they stand:
+//    (c0, c3) 2^-20, (c1, c4) 2^-20 per byte, against the activation pairs (x[5b], x[5b+3]) and
+//    (x[5b+1], x[5b+4]); the c2 digits of four bytes, masked out the other way, are a third
+//    operand (c2, 0) 2^-16 against (x[5b+2], 0).  Per 5 weights: 1 address operation (a shift
+//    with a byte select), 1 LDS read, 2 ANDs; all sixteen look-ups of a half tile are issued
+//    before the first is used.
 //  * The paper expects the 1.6-bit form to cost more arithmetic per weight than the 2-bit
-//    form (Sec. 3.3 results, "Limitations"); here it is 1.0 against 0.7 VALU operations per
-//    weight, for 0.81 of the bytes.
+//    form (Sec. 3.3 results, "Limitations"); here it is 0.7 VALU operations and 0.2 LDS
+//    look-ups per weight against 0.7 VALU operations for the 2-bit form, for 0.81 of the
+//    bytes; the look-ups (random addresses: about half of their LDS cycles are bank
+//    conflicts) and the single item per workgroup keep it behind the 2-bit kernel.
 #include "tl_internal.hpp"
 
 namespace tl {
@@ -27,8 +32,8 @@ constexpr int kT3Max = 4;            // tiles per workgroup
 constexpr int kSlice3 = 640;         // weights per slice (128 packed bytes)
 constexpr int kXRow = 1296;          // bytes per staged activation row (1280 + 16: spreads LDS banks)
 constexpr int kWave3Lds = 16 * kXRow;   // 20736 bytes per wave
-constexpr int kLutBytes = 1024;
-constexpr int kNW3Max = 7;           // 7 * 20736 + 1024 bytes of LDS
+constexpr int kLutBytes = 2048;       // 256 entries of 8 bytes
+constexpr int kNW3Max = 7;           // 7 * 20736 + 2048 bytes of LDS
 
 struct Gemv3Params {
     const __half* x;
@@ -58,6 +63,20 @@ __device__ __forceinline__ void lds_barrier3()
     __builtin_amdgcn_s_barrier();
 }
 
+// 8 * (byte B of w): the offset of that byte's table entry, in one instruction (the shift
+// reads its operand through a byte select).
+template <int B>
+__device__ __forceinline__ uint32_t byte_times_8(uint32_t w)
+{
+    uint32_t r;
+    const uint32_t three = 3u;
+    if constexpr (B == 0) asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_0" : "=v"(r) : "v"(three), "v"(w));
+    if constexpr (B == 1) asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1" : "=v"(r) : "v"(three), "v"(w));
+    if constexpr (B == 2) asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_2" : "=v"(r) : "v"(three), "v"(w));
+    if constexpr (B == 3) asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_3" : "=v"(r) : "v"(three), "v"(w));
+    return r;
+}
+
 template <int T>
 __global__ void __launch_bounds__(512)
 gemv3_kernel(Gemv3Params p)
@@ -66,8 +85,10 @@ gemv3_kernel(Gemv3Params p)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int NW = blockDim.x >> 6;
-    uint32_t* const lut = reinterpret_cast<uint32_t*>(lds_raw);
+    u32x2* const lut = reinterpret_cast<u32x2*>(lds_raw);
     unsigned char* const my_lds = lds_raw + kLutBytes + wave * kWave3Lds;
+    // the table starts the LDS: a byte offset into it is an LDS address
+    auto lut_at = [](uint32_t off) { return *(const __attribute__((address_space(3))) u32x2*)(uintptr_t(off)); };
 
     const int m0 = blockIdx.y * 16;
     const int Mrem = (p.M - m0 < 16) ? (p.M - m0) : 16;
@@ -111,9 +132,10 @@ gemv3_kernel(Gemv3Params p)
     // Staged activation row r of the slice: 640 halves = 80 pieces of 16 bytes, by LDS-DMA
     // (two instructions: pieces 0..63, then 64..79).  Pieces past K are stored as zeros.
     auto issue_x = [&](int slice) {
-        for (int r = 0; r < MR; ++r) {
-            const int rr = r < Mrem ? r : Mrem - 1;
-            const unsigned char* src = xb + size_t(rr) * K * 2;
+        // rows past Mrem stay unwritten: an MFMA column depends on its own column of B alone,
+        // and the outputs of those columns are not stored
+        for (int r = 0; r < Mrem; ++r) {
+            const unsigned char* src = xb + size_t(r) * K * 2;
             unsigned char* dst = my_lds + r * kXRow;
 #pragma unroll
             for (int part = 0; part < 2; ++part) {
@@ -159,7 +181,7 @@ gemv3_kernel(Gemv3Params p)
 #pragma unroll
             for (int i = 0; i < 5; ++i) { c[i] = v % 3u; v /= 3u; }
         }
-        lut[b] = (c[0] << 4) | (c[1] << 6) | (c[2] << 8) | (c[3] << 20) | (c[4] << 22);
+        lut[b] = u32x2{(c[0] << 4) | (c[2] << 8) | (c[3] << 20), (c[1] << 4) | (c[4] << 20)};
     }
     lds_barrier3();
     if (wave < slices) __builtin_amdgcn_s_waitcnt(vmcnt_imm3(2 * T));   // LDS-DMA is not tracked by the compiler
@@ -170,20 +192,32 @@ gemv3_kernel(Gemv3Params p)
         // cls 0 -> (x[k], x[k+3]), 1 -> (x[k+1], x[k+4]), 2 -> (x[k+2], 0), k = 5 * byte index
         uint32_t breg[2][4][3][4];
         {
+            // The lane's 16 bytes of half h cover 80 consecutive weights, i.e. 160 consecutive
+            // bytes of the staged row: ten 16-byte reads, then one byte permute per pair.
             const unsigned char* row = my_lds + xrow * kXRow;
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
+            for (int h = 0; h < 2; ++h) {
+                u32x4 xv[10];
+#pragma unroll
+                for (int i = 0; i < 10; ++i)
+                    xv[i] = *reinterpret_cast<const u32x4*>(row + (4 * h + mg) * 160 + 16 * i);
+                auto pair = [&](int a, int b) {            // (x[a], x[b]) of the 80; b < 0: (x[a], 0)
+                    const uint32_t lo = xv[a >> 3][(a >> 1) & 3];
+                    const uint32_t hi = b < 0 ? 0u : xv[b >> 3][(b >> 1) & 3];
+                    const uint32_t s0 = (a & 1) ? 0x0302u : 0x0100u;
+                    const uint32_t s1 = b < 0 ? 0x0c0cu : ((b & 1) ? 0x0706u : 0x0504u);
+                    return __builtin_amdgcn_perm(hi, lo, (s1 << 16) | s0);
+                };
 #pragma unroll
                 for (int d = 0; d < 4; ++d)
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        const int kl = ((4 * h + mg) * 16 + 4 * d + j) * 5;      // first weight of the byte
-                        const uint16_t* px = reinterpret_cast<const uint16_t*>(row + kl * 2);
-                        const uint32_t x0 = px[0], x1 = px[1], x2 = px[2], x3 = px[3], x4 = px[4];
-                        breg[h][d][0][j] = x0 | (x3 << 16);
-                        breg[h][d][1][j] = x1 | (x4 << 16);
-                        breg[h][d][2][j] = x2;
+                        const int k0 = 5 * (4 * d + j);     // first weight of the byte
+                        breg[h][d][0][j] = pair(k0, k0 + 3);
+                        breg[h][d][1][j] = pair(k0 + 1, k0 + 4);
+                        breg[h][d][2][j] = pair(k0 + 2, -1);
                     }
+            }
         }
         // nsx = -2^-20 sum_k x over the slice, in accumulator layout (constant 16-row operand)
         f32x4 nsx = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -193,12 +227,16 @@ gemv3_kernel(Gemv3Params p)
 #pragma unroll
             for (int h = 0; h < 2; ++h)
 #pragma unroll
-                for (int d = 0; d < 4; ++d)
-#pragma unroll
-                    for (int cls = 0; cls < 3; ++cls) {
-                        const u32x4 bb = u32x4{breg[h][d][cls][0], breg[h][d][cls][1], breg[h][d][cls][2], breg[h][d][cls][3]};
-                        nsx = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(a), as_h8(bb), nsx, 0, 0, 0);
-                    }
+                for (int d = 0; d < 4; ++d) {
+                    // the same groups of four as the tile loop uses, so that each group can live
+                    // in consecutive registers
+                    const u32x4 b01 = u32x4{breg[h][d][0][0], breg[h][d][1][0], breg[h][d][0][1], breg[h][d][1][1]};
+                    const u32x4 b23 = u32x4{breg[h][d][0][2], breg[h][d][1][2], breg[h][d][0][3], breg[h][d][1][3]};
+                    const u32x4 b2 = u32x4{breg[h][d][2][0], breg[h][d][2][1], breg[h][d][2][2], breg[h][d][2][3]};
+                    nsx = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(a), as_h8(b01), nsx, 0, 0, 0);
+                    nsx = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(a), as_h8(b23), nsx, 0, 0, 0);
+                    nsx = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(a), as_h8(b2), nsx, 0, 0, 0);
+                }
         }
 #pragma unroll
         for (int t = 0; t < T; ++t) {
@@ -211,24 +249,32 @@ gemv3_kernel(Gemv3Params p)
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
                     const u32x4 wv = *reinterpret_cast<const u32x4*>(reg_t + (h ? wr_off1 : wr_off0));
+                    // all sixteen look-ups of the half first, so that their latency runs under
+                    // the arithmetic of the ones before
+                    u32x2 e[4][4];
 #pragma unroll
                     for (int d = 0; d < 4; ++d) {
-                        const uint32_t w = wv[d];
-                        uint32_t e[4];
-                        e[0] = lut[w & 0xFFu];
-                        e[1] = lut[(w >> 8) & 0xFFu];
-                        e[2] = lut[(w >> 16) & 0xFFu];
-                        e[3] = lut[w >> 24];
+                        e[d][0] = lut_at(byte_times_8<0>(wv[d]));
+                        e[d][1] = lut_at(byte_times_8<1>(wv[d]));
+                        e[d][2] = lut_at(byte_times_8<2>(wv[d]));
+                        e[d][3] = lut_at(byte_times_8<3>(wv[d]));
+                    }
 #pragma unroll
-                        for (int cls = 0; cls < 3; ++cls) {
-                            const uint32_t mask = (cls == 0) ? 0x00300030u : (cls == 1) ? 0x00C000C0u : 0x00000300u;
-                            const u32x4 a = u32x4{e[0] & mask, e[1] & mask, e[2] & mask, e[3] & mask};
-                            const u32x4 bb = u32x4{breg[h][d][cls][0], breg[h][d][cls][1], breg[h][d][cls][2], breg[h][d][cls][3]};
-                            acc[cls] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(a), as_h8(bb), acc[cls], 0, 0, 0);
-                        }
+                    for (int d = 0; d < 4; ++d) {
+                        // bytes 0,1 and 2,3 of the dword: the two table words of a byte pair are an
+                        // operand as they stand once c2 is masked out of the first word of each
+                        const u32x4 a2 = u32x4{e[d][0][0] & 0x300u, e[d][1][0] & 0x300u, e[d][2][0] & 0x300u, e[d][3][0] & 0x300u};
+                        const u32x4 a01 = u32x4{e[d][0][0] & 0x00300030u, e[d][0][1], e[d][1][0] & 0x00300030u, e[d][1][1]};
+                        const u32x4 a23 = u32x4{e[d][2][0] & 0x00300030u, e[d][2][1], e[d][3][0] & 0x00300030u, e[d][3][1]};
+                        const u32x4 b01 = u32x4{breg[h][d][0][0], breg[h][d][1][0], breg[h][d][0][1], breg[h][d][1][1]};
+                        const u32x4 b23 = u32x4{breg[h][d][0][2], breg[h][d][1][2], breg[h][d][0][3], breg[h][d][1][3]};
+                        const u32x4 b2 = u32x4{breg[h][d][2][0], breg[h][d][2][1], breg[h][d][2][2], breg[h][d][2][3]};
+                        acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(a01), as_h8(b01), acc[0], 0, 0, 0);
+                        acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(a23), as_h8(b23), acc[1], 0, 0, 0);
+                        acc[2] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(a2), as_h8(b2), acc[2], 0, 0, 0);
                     }
                 }
-                part_acc[t] += acc[0] * 1048576.f + acc[1] * 262144.f + acc[2] * 65536.f;
+                part_acc[t] += (acc[0] + acc[1]) * 1048576.f + acc[2] * 65536.f;
             }
         }
         if (more) {
