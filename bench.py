@@ -276,10 +276,31 @@ def main():
         for line in open(tpath):
             if line.startswith("grouped_sweep_bytes_per_launch"):
                 traffic = float(line.split("=")[1])
-    roofline = dict(bound="hbm", kernel="gemv_stream_kernel<4, true>, grouped launch of the ten GEMMs of a step",
+    # the same number of bytes read by a kernel that does nothing else (one launch per step,
+    # from the largest weight ring, a different stretch each time): what the memory system
+    # gives a single launch of this size
+    big = max(layers.values(), key=lambda l: l["ring"].numel())["ring"].view(-1)
+    probe_bytes = (step_bytes + 15) // 16 * 16
+    slots = max(1, big.numel() * 4 // probe_bytes)
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    pc = [0]
+
+    def probe_step():
+        off = (pc[0] % slots) * probe_bytes
+        pc[0] += 1
+        st = L.tl_probe_read(big.data_ptr() + off, probe_bytes, sink.data_ptr(), stream)
+        if st != tl.TL_OK:
+            raise tl.TlError(st, "tl_probe_read")
+
+    us_probe = timed(probe_step, args.steps) * 1e3 / args.steps
+    roofline = dict(bound="hbm", kernel="gemv_stream_kernel<3, true, false, 1>, grouped launch of the ten GEMMs of a step",
                     achieved=round(step_bytes / us_launch / 1e3, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(step_bytes / us_launch / 1e3 / HBM_PEAK_GBS, 4),
-                    bytes_per_launch=step_bytes, us_per_launch=round(us_launch, 3), traffic=traffic)
+                    bytes_per_launch=step_bytes, us_per_launch=round(us_launch, 3), traffic=traffic,
+                    read_only_probe=dict(kernel="probe_read_kernel: the same bytes, loads only, one launch",
+                                         us_per_launch=round(us_probe, 3), GBps=round(probe_bytes / us_probe / 1e3, 1),
+                                         frac_of_peak=round(probe_bytes / us_probe / 1e3 / HBM_PEAK_GBS, 4),
+                                         kernel_vs_probe=round(us_probe / us_launch, 4)))
 
     # ---------------- CPU oracle on the same sweep (reported baseline, not a target) -------
     cpu = None

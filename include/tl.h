@@ -195,6 +195,17 @@ tl_status tl_ternary_gemm_1p6_fx(const void* x, const void* Wpacked, uint16_t ga
  */
 tl_status tl_probe_copy(void* dst, const void* src, size_t bytes, void* stream);
 
+/*
+ * Bandwidth ceiling: a streaming read of `bytes` bytes (multiple of 16, `src` a device
+ * pointer, 16-byte aligned) that does nothing with them -- one launch, as many workgroups as
+ * the buffer has 16 KB pieces.  No kernel that streams a weight matrix of that size once per
+ * launch (Sec. 3.3: the memory-bound regime) can finish sooner; the benchmark times it beside
+ * the GEMM kernels.  `sink` is a device pointer to 4 writable bytes, 4-byte aligned, written
+ * only if the fold of all words read equals one particular value (it keeps the loads alive).
+ * Not part of the method.
+ */
+tl_status tl_probe_read(const void* src, size_t bytes, void* sink, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

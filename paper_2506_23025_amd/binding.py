@@ -23,6 +23,7 @@ EXPORTS = (
     "tl_pack_1p6bit_fx", "tl_unpack_1p6bit_fx", "tl_unpack", "tl_unpack_dev", "tl_ternary_gemm",
     "tl_ternary_gemm_path", "tl_ternary_gemm_grouped", "tl_ternary_gemm_1p6", "tl_ternary_gemm_1p6_fx",
     "tl_probe_copy",
+    "tl_probe_read",
 )
 
 
@@ -81,6 +82,8 @@ def _load():
     L.tl_ternary_gemm_1p6_fx.restype = ci
     L.tl_probe_copy.argtypes = [vp, vp, sz, vp]
     L.tl_probe_copy.restype = ci
+    L.tl_probe_read.argtypes = [vp, sz, vp, vp]
+    L.tl_probe_read.restype = ci
     return L
 
 
@@ -233,3 +236,7 @@ def tl_ternary_gemm_1p6_fx(x, Wpacked, gamma_fp16_bits, y, M, N, K, stream=None)
 
 def tl_probe_copy(dst, src, nbytes, stream=None):
     _check(_lib.tl_probe_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)), "tl_probe_copy")
+
+
+def tl_probe_read(src, nbytes, sink, stream=None):
+    _check(_lib.tl_probe_read(_ptr(src), nbytes, _ptr(sink), _stream(stream)), "tl_probe_read")

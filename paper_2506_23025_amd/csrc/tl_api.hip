@@ -189,4 +189,12 @@ tl_status tl_probe_copy(void* dst, const void* src, size_t bytes, void* stream)
     return tl::from_hip(tl::launch_probe_copy(dst, src, bytes, static_cast<hipStream_t>(stream)));
 }
 
+tl_status tl_probe_read(const void* src, size_t bytes, void* sink, void* stream)
+{
+    if (!src || !sink) return TL_ERR_NULL;
+    if (bytes % 16 != 0) return TL_ERR_SHAPE;
+    if (!tl::aligned16(src) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return TL_ERR_ALIGN;
+    return tl::from_hip(tl::launch_probe_read(src, bytes, sink, static_cast<hipStream_t>(stream)));
+}
+
 }  // extern "C"

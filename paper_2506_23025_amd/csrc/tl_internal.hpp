@@ -22,6 +22,7 @@ hipError_t launch_unpack2(const uint32_t* packed, int64_t N, int64_t K, int8_t* 
 hipError_t launch_unpack3(const uint8_t* packed, int64_t N, int64_t K, int64_t stride, int8_t* out,
                           bool fx, hipStream_t s);
 hipError_t launch_probe_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
+hipError_t launch_probe_read(const void* src, size_t bytes, void* sink, hipStream_t s);
 
 // Plain VALU kernel: any M, N, K.
 hipError_t launch_gemm_generic(const __half* x, const uint32_t* Wp, float gamma, __half* y,

@@ -167,6 +167,9 @@ def test_error_codes():
     assert L.tl_ternary_gemm_grouped(tl.make_jobs([(16, 16, 0, 16, 0, 1, 16)]), 1, None) == tl.TL_ERR_SHAPE
     assert L.tl_unpack_dev(tl.TL_FMT_2BIT, None, 1, 16, None, None) == tl.TL_ERR_NULL
     assert L.tl_probe_copy(16, 16, 24, None) == tl.TL_ERR_SHAPE
+    assert L.tl_probe_read(16, 24, 16, None) == tl.TL_ERR_SHAPE
+    assert L.tl_probe_read(16, 32, None, None) == tl.TL_ERR_NULL
+    assert L.tl_probe_read(16, 32, 18, None) == tl.TL_ERR_ALIGN
     for s in range(8):
         assert tl.tl_status_str(s)
 
