@@ -189,6 +189,22 @@ tl_status tl_ternary_gemm_1p6_fx(const void* x, const void* Wpacked, uint16_t ga
                                  void* y, int64_t M, int64_t N, int64_t K, void* stream);
 
 /*
+ * The same product with one fp16 scale per group of `group` consecutive weights along K and
+ * per output row, in place of the single gamma:
+ *     y[m][n] = sum_g scales[g][n] * ( sum_{k in group g} x[m][k] * w[n][k] )
+ * (paper Sec. 3.3, CPU inference: the 2-bit block format keeps one fp16 scale per block of
+ * 256 weights; GPU kernel appendix: the dequantised fragments are scaled by quantisation
+ * scales held in a separate buffer).  `scales` is a device pointer to fp16
+ * [ceil(K / group)][N], 16-byte aligned; the last group may be short.  x, Wpacked (2-bit
+ * format), y, stream, accumulation and rounding as for tl_ternary_gemm.  `group` must be a
+ * multiple of 16 (TL_ERR_SHAPE otherwise).  group % 256 == 0, K % 64 == 0 and N % 4 == 0 run
+ * in the weight-streaming small-M kernel (M in blocks of 16 rows); everything else in a plain
+ * kernel without tiling.  Nothing is allocated; the call is asynchronous on `stream`.
+ */
+tl_status tl_ternary_gemm_gs(const void* x, const void* Wpacked, const void* scales, int64_t group,
+                             void* y, int64_t M, int64_t N, int64_t K, void* stream);
+
+/*
  * Bandwidth calibration: a plain streaming copy dst[i] = src[i] of `bytes` bytes
  * (multiple of 16, both device pointers 16-byte aligned).  Not part of the
  * method; it gives the HBM counters and timers a kernel of known traffic.

@@ -267,6 +267,31 @@ def gemm_packed3le(x, Wp, gamma, K):
     return y
 
 
+def gemm_group_scales(x, W, scales, group):
+    """y[m][n] = sum_g scales[g][n] * sum_{k in group g} x[m][k] W[n][k], fp64, unrounded.
+    One scale per block of `group` consecutive weights along K and per output row (Sec. 3.3,
+    CPU inference: a block of the 2-bit format carries its own fp16 scale, and a block is
+    reconstructed as scale times its ternary values; the GPU kernel reads its scales from a
+    separate buffer).  scales: fp16 [ceil(K / group)][N]; the last group may be short.
+    The definition written out: one fp64 matrix product per group (each exact), scaled, summed."""
+    x64 = np.asarray(x, dtype=np.float16).astype(np.float64)
+    W64 = _w(W).astype(np.float64)
+    s64 = np.asarray(scales, dtype=np.float16).astype(np.float64)
+    M, K = x64.shape
+    N = W64.shape[0]
+    G = (K + group - 1) // group
+    assert W64.shape[1] == K and s64.shape == (G, N)
+    y = np.zeros((M, N), dtype=np.float64)
+    for g in range(G):
+        k0, k1 = g * group, min(K, (g + 1) * group)
+        y += (x64[:, k0:k1] @ W64[:, k0:k1].T) * s64[g][None, :]
+    return y
+
+
+def gemm_packed2_group_scales(x, Wp, scales, group, K):
+    return gemm_group_scales(x, unpack2(Wp, K), scales, group)
+
+
 def gemm_fixed(x, W):
     """Exact integer S * 2^24, S[m][n] = sum_k x[m][k] W[n][k]."""
     xb = _xbits(x)

@@ -181,6 +181,26 @@ tl_status tl_ternary_gemm_1p6_fx(const void* x, const void* Wpacked, uint16_t ga
     return gemm_1p6(x, Wpacked, gamma_fp16_bits, y, M, N, K, stream, true);
 }
 
+tl_status tl_ternary_gemm_gs(const void* x, const void* Wpacked, const void* scales, int64_t group,
+                             void* y, int64_t M, int64_t N, int64_t K, void* stream)
+{
+    if (!x || !Wpacked || !scales || !y) return TL_ERR_NULL;
+    if (!tl::dims_ok(M, N, K)) return TL_ERR_SHAPE;
+    if (group < 16 || group % 16 != 0) return TL_ERR_SHAPE;
+    if (!tl::aligned16(x) || !tl::aligned16(Wpacked) || !tl::aligned16(scales) || !tl::aligned16(y)) return TL_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const __half* xh = static_cast<const __half*>(x);
+    const uint32_t* wp = static_cast<const uint32_t*>(Wpacked);
+    const __half* sh = static_cast<const __half*>(scales);
+    __half* yh = static_cast<__half*>(y);
+    if (tl::gemv_gs_supports(M, N, K, group)) {
+        const hipError_t e = tl::launch_gemv_gs(xh, wp, sh, group, yh, M, N, K, s);
+        if (e != hipErrorInvalidValue) return tl::from_hip(e);
+        (void)hipGetLastError();                 // nothing was launched: the plain kernel takes it
+    }
+    return tl::from_hip(tl::launch_gemm_generic_gs(xh, wp, sh, group, yh, M, N, K, s));
+}
+
 tl_status tl_probe_copy(void* dst, const void* src, size_t bytes, void* stream)
 {
     if (!dst || !src) return TL_ERR_NULL;

@@ -136,6 +136,45 @@ gemm_generic_kernel(const __half* __restrict__ x, const uint32_t* __restrict__ W
     }
 }
 
+// The same with one fp16 scale per `group` weights along K and output row, s[K / group][N]
+// (group % 16 == 0, so a packed word lies inside one group): every word's sum is weighted by
+// its group's scale.
+__global__ void __launch_bounds__(256)
+gemm_generic_gs_kernel(const __half* __restrict__ x, const uint32_t* __restrict__ Wp,
+                       const __half* __restrict__ scales, int64_t group, __half* __restrict__ y,
+                       int64_t M, int64_t N, int64_t K, int64_t words)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t n = blockIdx.x * int64_t(4) + (threadIdx.x >> 6);
+    const int64_t m0 = blockIdx.y * int64_t(MB);
+    if (n >= N) return;                               // whole wave leaves together
+    float acc[MB];
+    for (int r = 0; r < MB; ++r) acc[r] = 0.f;
+    const uint32_t* row = Wp + n * words;
+    for (int64_t i = lane; i < words; i += 64) {
+        uint32_t word = row[i];
+        const int64_t base = 16 * i;
+        const int len = (K - base < 16) ? int(K - base) : 16;
+        const float sc = __half2float(scales[(base / group) * N + n]);
+        float part[MB];
+        for (int r = 0; r < MB; ++r) part[r] = 0.f;
+        for (int j = 0; j < len; ++j, word >>= 2) {
+            const int w = int(word & 3u) - 1;
+            for (int r = 0; r < MB; ++r) {
+                if (m0 + r < M) {
+                    const float xv = __half2float(x[(m0 + r) * K + base + j]);
+                    part[r] += (w > 0) ? xv : ((w < 0) ? -xv : 0.f);
+                }
+            }
+        }
+        for (int r = 0; r < MB; ++r) acc[r] += sc * part[r];
+    }
+    for (int r = 0; r < MB; ++r) {
+        const float s = wave_sum(acc[r]);
+        if (lane == 0 && m0 + r < M) y[(m0 + r) * N + n] = __float2half_rn(s);
+    }
+}
+
 __global__ void __launch_bounds__(256)
 gemm3_generic_kernel(const __half* __restrict__ x, const uint8_t* __restrict__ Wp, int64_t stride,
                      float gamma, __half* __restrict__ y, int64_t M, int64_t N, int64_t K, bool fx)
@@ -220,6 +259,16 @@ hipError_t launch_gemm_generic(const __half* x, const uint32_t* Wp, float gamma,
     const int64_t words = (K + 15) / 16;
     dim3 grid(blocks_for(N, 4), blocks_for(M, MB));
     hipLaunchKernelGGL(gemm_generic_kernel, grid, dim3(256), 0, s, x, Wp, gamma, y, M, N, K, words);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_generic_gs(const __half* x, const uint32_t* Wp, const __half* scales,
+                                  int64_t group, __half* y, int64_t M, int64_t N, int64_t K,
+                                  hipStream_t s)
+{
+    const int64_t words = (K + 15) / 16;
+    dim3 grid(blocks_for(N, 4), blocks_for(M, MB));
+    hipLaunchKernelGGL(gemm_generic_gs_kernel, grid, dim3(256), 0, s, x, Wp, scales, group, y, M, N, K, words);
     return hipGetLastError();
 }
 

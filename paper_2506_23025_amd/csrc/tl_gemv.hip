@@ -47,13 +47,13 @@ struct GemvJob {                  // 64 bytes, lives in the kernel argument segm
     const __half* x;              // first activation row of this 16-row block
     const uint32_t* W;
     __half* y;                    // first output row of this block
-    float gamma;
+    float gamma;                  // per-group scales: bits of the int "256-weight halves per group"
     int Mrem;                     // 1..16 activation rows
     int N, K;
     int tiles;                    // ceil(N / 16)
-    int items;                    // work items of this job: ceil(tiles / T)
+    int items;                    // work items of this job: ceil(tiles / T); per-group scales: low word of the scales pointer
     int slices;                   // ceil(K / 512)
-    int mr;                       // staged rows: power of two >= Mrem (surplus rows repeat)
+    int mr;                       // staged rows: power of two >= Mrem; per-group scales: high word of the scales pointer
     int pad[2];
 };
 
@@ -90,6 +90,8 @@ struct ItemCtx {
     int chunks;                   // 64-weight (16-byte) chunks per row
     int tiles, items, idx;        // tile t of the item is idx + t * items
     int slices;
+    const unsigned char* sc;      // per-group scales [K / group][N] fp16, and 256-weight halves per group
+    int hpg;
 };
 
 // The job table of a launch, one job per lane (lane & 15), read from the kernel argument
@@ -138,6 +140,8 @@ __device__ __forceinline__ ItemCtx load_item(const JobTable& tb, int g)
     c.tiles = int(f[10]); c.items = int(f[11]); c.idx = g - item0;
     c.slices = int(f[12]);
     c.MR = int(f[13]);
+    c.sc = reinterpret_cast<const unsigned char*>(uintptr_t(f[11]) | (uintptr_t(f[13]) << 32));
+    c.hpg = int(f[6]);
     return c;
 }
 
@@ -432,7 +436,11 @@ constexpr int stream_wave_lds(int T)
 // NB: blocks of 16 activation rows a job may have (1 or 2).  With two, every decoded weight
 // operand feeds two MFMAs, one per block: the decode, which is what limits the kernel, is paid
 // once for 32 rows (not combined with PASSES).
-template <int T, bool MULTI, bool PASSES, int NB>
+// GS: per-group scales (Sec. 3.3, CPU inference: one fp16 scale per block along K; App. on the
+// GPU kernel: scales kept in a separate buffer) instead of one gamma: the two 256-weight halves
+// of a slice are accumulated apart, each multiplied by the scale of its group and output row.
+// Groups are multiples of 256 weights; the scales lie as [K / group][N].
+template <int T, bool MULTI, bool PASSES, int NB, bool GS = false>
 __global__ void __launch_bounds__(512)
 gemv_stream_kernel(GemvBatch b)
 {
@@ -443,6 +451,8 @@ gemv_stream_kernel(GemvBatch b)
     // LDS of a wave: activation rows (16 KB) while the operands are built; afterwards two tile
     // regions at 0 and 2 KB, and from 4 KB two sets of T NB partial-sum tiles (1 KB each).
     static_assert(NB == 1 || !PASSES, "two row blocks are not combined with passes over K");
+    static_assert(!GS || (NB == 1 && MULTI), "per-group scales: one row block, job table");
+    constexpr int H = GS ? 2 : 1;             // accumulator sets per tile: one per 256-weight half
     constexpr int kStride = stream_wave_lds(T * NB);
     unsigned char* const my_lds = lds_raw + wave * kStride;
 
@@ -492,6 +502,8 @@ gemv_stream_kernel(GemvBatch b)
     typedef const __attribute__((address_space(1))) u32x4* gptr;
 
     u32x4 wreg[T][2];
+    f16x4 sreg[T][H];                          // GS: the scales of the lane's four output rows, per half
+    uint32_t sc_off[2] = {0u, 0u};             // GS: byte offset of the halves' groups in the scales
     auto issue_w = [&](int first, int t) {
         int tile = first + t;
         if (tile >= tile_end) tile = tile_end - 1;         // past the run: its last tile again, never stored
@@ -502,12 +514,21 @@ gemv_stream_kernel(GemvBatch b)
         const uint32_t off1 = uint32_t(lr + 8 < last ? lr + 8 : last) * J.row_bytes + col_off;
         wreg[t][0] = __builtin_nontemporal_load((gptr)(tb + off0));
         wreg[t][1] = __builtin_nontemporal_load((gptr)(tb + off1));
+        if constexpr (GS) {
+            int n0 = tile * 16 + 4 * mg;                   // the lane's rows of the result: n0 .. n0 + 3
+            if (n0 > J.N - 4) n0 = J.N - 4;                // rows past N (N % 4 == 0): any scale will do
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh)
+                sreg[t][hh] = *(const __attribute__((address_space(1))) f16x4*)(J.sc + sc_off[hh] + uint32_t(n0) * 2u);
+        }
     };
 
     uint32_t breg[NB][2][4][8];                // this wave's activations as MFMA B operands, per row block
-    f32x4 nsx[NB];                             // -2^-20 sum_k x[m][k] over the slice, as an accumulator
+    f32x4 nsx[NB][H];                          // -2^-20 sum_k x[m][k] over the slice (GS: each half), as an accumulator
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) nsx[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int hh = 0; hh < H; ++hh) nsx[nb][hh] = f32x4{0.f, 0.f, 0.f, 0.f};
     // Start of a pass: fetch this wave's activation slice and the first item's weights together,
     // then turn the activations into operand registers.
     auto begin_pass = [&](int pass) {
@@ -519,7 +540,19 @@ gemv_stream_kernel(GemvBatch b)
         col_off = uint32_t(chunk) * 16u;
     }
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) nsx[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int hh = 0; hh < H; ++hh) nsx[nb][hh] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if constexpr (GS) {
+        // groups of this wave's two halves; a half past K (its activations are zeros) takes the last group
+        const int last_group = (J.K - 1) / (256 * J.hpg);
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+            int g = (2 * slice + hh) / J.hpg;
+            if (g > last_group) g = last_group;
+            sc_off[hh] = uint32_t(g) * uint32_t(J.N) * 2u;
+        }
+    }
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
         // rows of this block: block 0 takes the first 16 (or fewer), block 1 what is left
@@ -560,7 +593,7 @@ gemv_stream_kernel(GemvBatch b)
 #pragma unroll
                 for (int t = 0; t < T; ++t) issue_w(tile0, t);
                 // the compiler does not track LDS-DMA: wait until only the 2T weight loads are outstanding
-                __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * T));
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm((GS ? 4 : 2) * T));
             } else {
                 __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // requested after the weights: wait for all
             }
@@ -589,7 +622,7 @@ gemv_stream_kernel(GemvBatch b)
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const u32x4 bb = u32x4{breg[nb][h][0][e], breg[nb][h][1][e], breg[nb][h][2][e], breg[nb][h][3][e]};
-                    nsx[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), as_f16x8(bb), nsx[nb], 0, 0, 0);
+                    nsx[nb][GS ? h : 0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), as_f16x8(bb), nsx[nb][GS ? h : 0], 0, 0, 0);
                 }
             if (NB > 1 && nb == 0) __builtin_amdgcn_s_waitcnt(0xF | (0x3 << 14) | (0x7 << 4));   // staging read before it is refilled
         } else {
@@ -621,15 +654,20 @@ gemv_stream_kernel(GemvBatch b)
                 unsigned char* const reg_t = my_lds + (t & 1) * 2048;
                 *reinterpret_cast<u32x4*>(reg_t + ww_off) = wreg[t][0];
                 *reinterpret_cast<u32x4*>(reg_t + 1024 + ww_off) = wreg[t][1];
+                f16x4 sc_cur[H];                           // this tile's scales, before the refill replaces them
+#pragma unroll
+                for (int hh = 0; hh < H; ++hh) sc_cur[hh] = sreg[t][hh];
                 if constexpr (REFILL) issue_w(first + T, t);
                 if (REFILL || first + t < tile_end) {      // the last item may be short
-                    f32x4 acc[NB][3];
+                    f32x4 acc[NB][H][3];
 #pragma unroll
-                    for (int nb = 0; nb < NB; ++nb) {
-                        acc[nb][0] = nsx[nb];
-                        acc[nb][1] = f32x4{0.f, 0.f, 0.f, 0.f};
-                        acc[nb][2] = f32x4{0.f, 0.f, 0.f, 0.f};
-                    }
+                    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                        for (int hh = 0; hh < H; ++hh) {
+                            acc[nb][hh][0] = nsx[nb][hh];
+                            acc[nb][hh][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+                            acc[nb][hh][2] = f32x4{0.f, 0.f, 0.f, 0.f};
+                        }
 #pragma unroll
                     for (int h = 0; h < 2; ++h) {
                         const u32x4 wv = *reinterpret_cast<const u32x4*>(reg_t + (h ? wr_off1 : wr_off0));
@@ -646,13 +684,25 @@ gemv_stream_kernel(GemvBatch b)
 #pragma unroll
                             for (int nb = 0; nb < NB; ++nb) {
                                 const u32x4 bb = u32x4{breg[nb][h][0][e], breg[nb][h][1][e], breg[nb][h][2][e], breg[nb][h][3][e]};
-                                acc[nb][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), as_f16x8(bb), acc[nb][j], 0, 0, 0);
+                                acc[nb][GS ? h : 0][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), as_f16x8(bb), acc[nb][GS ? h : 0][j], 0, 0, 0);
                             }
                         }
                     }
 #pragma unroll
-                    for (int nb = 0; nb < NB; ++nb)
-                        part[nb][t] = acc[nb][0] * 1048576.f + acc[nb][1] * 262144.f + acc[nb][2] * 65536.f;
+                    for (int nb = 0; nb < NB; ++nb) {
+                        if constexpr (GS) {
+                            // register r of the accumulator is output row 4 (lane / 16) + r of the tile
+                            f32x4 sum = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                            for (int hh = 0; hh < 2; ++hh) {
+                                const f32x4 sc = f32x4{float(sc_cur[hh][0]), float(sc_cur[hh][1]), float(sc_cur[hh][2]), float(sc_cur[hh][3])};
+                                sum += sc * (acc[nb][hh][0] * 1048576.f + acc[nb][hh][1] * 262144.f + acc[nb][hh][2] * 65536.f);
+                            }
+                            part[nb][t] = sum;
+                        } else {
+                            part[nb][t] = acc[nb][0][0] * 1048576.f + acc[nb][0][1] * 262144.f + acc[nb][0][2] * 65536.f;
+                        }
+                    }
                 }
             }
         }
@@ -687,7 +737,7 @@ gemv_stream_kernel(GemvBatch b)
             if (last_pass && tile < tile_end && row < J.Mrem) {
                 typedef __attribute__((address_space(1))) __half* gh_ptr;
                 gh_ptr dst = (gh_ptr)(J.y + size_t(row) * J.N + n);
-                const float gamma = J.gamma;
+                const float gamma = GS ? 1.f : J.gamma;
                 if (n + 3 < J.N && (J.N & 3) == 0) {       // four consecutive n: one 8-byte store
                     const f16x2 lo = {(_Float16)(gamma * s[0]), (_Float16)(gamma * s[1])};
                     const f16x2 hi = {(_Float16)(gamma * s[2]), (_Float16)(gamma * s[3])};
@@ -745,6 +795,15 @@ KernelFn pick_stream_t(int T)
     }
 }
 
+KernelFn pick_stream_gs(int T, bool passes)
+{
+    switch (T) {
+        case 1: return passes ? gemv_stream_kernel<1, true, true, 1, true> : gemv_stream_kernel<1, true, false, 1, true>;
+        case 2: return passes ? gemv_stream_kernel<2, true, true, 1, true> : gemv_stream_kernel<2, true, false, 1, true>;
+        default: return passes ? gemv_stream_kernel<3, true, true, 1, true> : gemv_stream_kernel<3, true, false, 1, true>;
+    }
+}
+
 KernelFn pick_stream(int T, bool multi, bool passes, int nb)
 {
     if (nb == 2) {                                         // two row blocks: T <= 2, one pass over K
@@ -788,7 +847,7 @@ constexpr int kStreamMaxRun = 32;       // tiles of a run whose sums fit the 32 
 // out to the jobs so that all finish together (see run_cost below); spare ones go to the job
 // with the costliest runs, one by one.  Returns hipErrorInvalidValue without launching if a multi-pass job's
 // runs would not fit the LDS (the caller then uses the general kernel).
-hipError_t launch_stream(GemvBatch& b, int max_slices, int nb, hipStream_t s)
+hipError_t launch_stream(GemvBatch& b, int max_slices, int nb, hipStream_t s, bool gs = false)
 {
     const GemvPolicy pol = g_policy;
     const int NW = max_slices < kStreamWaves ? max_slices : kStreamWaves;
@@ -866,7 +925,7 @@ hipError_t launch_stream(GemvBatch& b, int max_slices, int nb, hipStream_t s)
     int grid = 0;
     for (int j = 0; j < b.count; ++j) {
         b.item0[j] = grid;
-        b.job[j].items = 0;
+        if (!gs) b.job[j].items = 0;                       // (the scaled form keeps half of a pointer there)
         b.job[j].pad[0] = b.job[j].tiles / wg[j];
         b.job[j].pad[1] = b.job[j].tiles % wg[j];
         grid += wg[j];
@@ -876,10 +935,10 @@ hipError_t launch_stream(GemvBatch& b, int max_slices, int nb, hipStream_t s)
     b.total_items = total_items;
     b.red_off = 0;
     b.pad = 0;
-    const bool multi = b.count > 1;
-    KernelFn fn = pick_stream(T, multi, multi_pass, nb);
-    static bool lds_raised[3][2][kTMax + 1];
-    const int variant = nb == 2 ? 2 : (multi_pass ? 1 : 0);
+    const bool multi = gs || b.count > 1;              // the scaled form always reads the job table
+    KernelFn fn = gs ? pick_stream_gs(T, multi_pass) : pick_stream(T, multi, multi_pass, nb);
+    static bool lds_raised[5][2][kTMax + 1];
+    const int variant = gs ? (multi_pass ? 4 : 3) : (nb == 2 ? 2 : (multi_pass ? 1 : 0));
     if (!lds_raised[variant][multi][T]) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
                                            hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -1034,6 +1093,46 @@ hipError_t launch_gemv_jobs(const GemmDesc* jobs, int count, hipStream_t s)
     e = flush(bs2);
     if (e != hipSuccess) return e;
     return flush(bg);
+}
+
+bool gemv_gs_supports(int64_t M, int64_t N, int64_t K, int64_t group)
+{
+    const int64_t slices = (K + kSliceK - 1) / kSliceK;
+    return gemv_supports(M, N, K) && group >= 256 && group % 256 == 0 && N >= 4 && N % 4 == 0 &&
+           slices <= kStreamWaves * kStreamMaxPasses &&
+           (slices <= kStreamWaves || (N + 15) / 16 <= int64_t(256) * kStreamMaxRun);
+}
+
+hipError_t launch_gemv_gs(const __half* x, const uint32_t* Wp, const __half* scales, int64_t group,
+                          __half* y, int64_t M, int64_t N, int64_t K, hipStream_t s)
+{
+    if (!gemv_gs_supports(M, N, K, group)) return hipErrorInvalidValue;
+    const int slices = int((K + kSliceK - 1) / kSliceK);
+    const uintptr_t sp = reinterpret_cast<uintptr_t>(scales);
+    const int hpg = int(group / 256);
+    GemvBatch b;
+    b.count = 0;
+    for (int64_t m0 = 0; m0 < M; m0 += 16) {
+        GemvJob j;
+        j.x = x + m0 * K;
+        j.W = Wp;
+        j.y = y + m0 * N;
+        j.gamma = __builtin_bit_cast(float, hpg);
+        j.Mrem = int(M - m0 < 16 ? M - m0 : 16);
+        j.N = int(N); j.K = int(K);
+        j.tiles = int((N + 15) / 16);
+        j.items = int(uint32_t(sp));
+        j.slices = slices;
+        j.mr = int(uint32_t(sp >> 32));
+        j.pad[0] = j.pad[1] = 0;
+        b.job[b.count++] = j;
+        if (b.count == kMaxJobs || m0 + 16 >= M) {
+            const hipError_t e = launch_stream(b, slices, 1, s, true);
+            if (e != hipSuccess) return e;
+            b.count = 0;
+        }
+    }
+    return hipSuccess;
 }
 
 hipError_t launch_gemv(const __half* x, const uint32_t* Wp, float gamma, __half* y,

@@ -15,6 +15,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 
 // Launchers return hipGetLastError() of their launch.  All pointers are device pointers.
 hipError_t launch_unpack2(const uint32_t* packed, int64_t N, int64_t K, int8_t* out, hipStream_t s);
@@ -56,6 +57,16 @@ inline bool gemv_two_blocks(int64_t M, int64_t N, int64_t K)
 
 // Several independent GEMMs (each passing gemv_supports) in as few launches as possible.
 hipError_t launch_gemv_jobs(const GemmDesc* jobs, int count, hipStream_t s);
+
+// Per-group scales s[K / group][N] in place of gamma (stream form of the small-M kernel; M in
+// blocks of 16).  Needs what gemv_supports needs and group % 256 == 0, N % 4 == 0.
+bool gemv_gs_supports(int64_t M, int64_t N, int64_t K, int64_t group);
+hipError_t launch_gemv_gs(const __half* x, const uint32_t* Wp, const __half* scales, int64_t group,
+                          __half* y, int64_t M, int64_t N, int64_t K, hipStream_t s);
+// Plain VALU kernel with per-group scales: any M, N, K; group % 16 == 0.
+hipError_t launch_gemm_generic_gs(const __half* x, const uint32_t* Wp, const __half* scales,
+                                  int64_t group, __half* y, int64_t M, int64_t N, int64_t K,
+                                  hipStream_t s);
 
 // Weight-streaming small-M kernel for the 1.6-bit format.  Needs K % 8 == 0.
 bool gemv3_supports(int64_t M, int64_t N, int64_t K);

@@ -52,6 +52,12 @@ def gamma_uniform(rng, lo=0.01, hi=0.05):
     return np.float16(rng.uniform(lo, hi))
 
 
+def group_scales(rng, groups, N, lo=0.01, hi=0.05):
+    """fp16 [groups][N]: one scale per group of weights along K and output row, drawn in fp64
+    and rounded to fp16 before anyone uses it."""
+    return rng.uniform(lo, hi, size=(groups, N)).astype(np.float16)
+
+
 def gamma_bits(g):
     return int(np.array(g, dtype=np.float16).view(np.uint16))
 

@@ -458,3 +458,50 @@ def test_gemv_1p6_full_size_agrees_with_2bit_path(M):
     assert_close(y3, y2.astype(np.float64), x, g, "1.6-bit vs 2-bit")
     # deterministic
     assert np.array_equal(run_gemm3(x, tl.tl_pack_1p6bit(W), g, N, K).view(np.uint16), y3.view(np.uint16))
+
+
+# --- per-group scales --------------------------------------------------------------------
+
+def run_gemm_gs(x, Wp, sc, group, N, K):
+    import torch
+    M = x.shape[0]
+    xd, wd = to_dev(x.view(np.uint16).view(np.int16)), dev_u32(Wp)
+    sd = to_dev(sc.view(np.uint16).view(np.int16))
+    yd = torch.full((M, N), -21555, dtype=torch.int16, device="cuda")
+    tl.tl_ternary_gemm_gs(xd, wd, sd, group, yd, M, N, K)
+    torch.cuda.synchronize()
+    return yd.cpu().numpy().view(np.float16)
+
+
+GS_SHAPES = [
+    # small-M stream kernel: group % 256 == 0, K % 64 == 0, N % 4 == 0
+    (1, 64, 512, 256), (3, 100, 1024, 256), (16, 4096, 4096, 256), (5, 272, 4096, 512), (16, 144, 4096, 1024),
+    (7, 48, 4096, 4096), (1, 4100, 4096, 256), (33, 128, 2048, 256), (4, 40, 11008, 256), (2, 64, 8192, 768),
+    (300, 64, 1024, 256), (2, 1152, 1344, 256), (1, 14336, 4096, 256),
+    # plain kernel: any other group (multiple of 16), N or K
+    (3, 7, 100, 16), (2, 33, 4096, 64), (5, 6, 4096, 256), (4, 12, 1000, 256),
+]
+
+
+@pytest.mark.parametrize("M,N,K,group", GS_SHAPES)
+def test_gemm_group_scales_matches_oracle(M, N, K, group):
+    rng = np.random.default_rng(7700 + M + N + K + group)
+    x, W, _ = si.layer(7600 + M + N + K, M, N, K)
+    sc = si.group_scales(rng, (K + group - 1) // group, N)
+    Wp = tl.tl_pack_2bit(W)
+    y = run_gemm_gs(x, Wp, sc, group, N, K)
+    ref = oracle.gemm_packed2_group_scales(x, Wp, sc, group, K)
+    assert_close(y, ref, x, float(sc.max()), f"group scales {M}x{N}x{K} / {group}")
+
+
+def test_gemm_group_scales_equal_scales_reproduce_the_single_gamma_kernel_bits():
+    # every scale equal to gamma: the two halves of a slice are scaled apart and added, which is
+    # the single-gamma result up to the rounding of that one addition
+    M, N, K = 4, 512, 4096
+    x, W, g = si.layer(7801, M, N, K)
+    Wp = tl.tl_pack_2bit(W)
+    sc = np.full((K // 256, N), g, dtype=np.float16)
+    y = run_gemm_gs(x, Wp, sc, 256, N, K)
+    y1 = run_gemm(x, Wp, g, N, K, tl.TL_PATH_GEMV)
+    assert_close(y, y1.astype(np.float64), x, g, "equal scales against the single-gamma kernel")
+    assert_close(y, oracle.gemm_packed2(x, Wp, g, K), x, g, "equal scales against the oracle")

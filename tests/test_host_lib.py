@@ -166,6 +166,10 @@ def test_error_codes():
     assert L.tl_ternary_gemm_grouped(None, 2, None) == tl.TL_ERR_NULL
     assert L.tl_ternary_gemm_grouped(tl.make_jobs([(16, 16, 0, 16, 0, 1, 16)]), 1, None) == tl.TL_ERR_SHAPE
     assert L.tl_unpack_dev(tl.TL_FMT_2BIT, None, 1, 16, None, None) == tl.TL_ERR_NULL
+    assert L.tl_ternary_gemm_gs(16, 16, None, 256, 16, 1, 1, 16, None) == tl.TL_ERR_NULL
+    assert L.tl_ternary_gemm_gs(16, 16, 16, 24, 16, 1, 1, 16, None) == tl.TL_ERR_SHAPE
+    assert L.tl_ternary_gemm_gs(16, 16, 16, 0, 16, 1, 1, 16, None) == tl.TL_ERR_SHAPE
+    assert L.tl_ternary_gemm_gs(16, 16, 8, 256, 16, 1, 1, 16, None) == tl.TL_ERR_ALIGN
     assert L.tl_probe_copy(16, 16, 24, None) == tl.TL_ERR_SHAPE
     assert L.tl_probe_read(16, 24, 16, None) == tl.TL_ERR_SHAPE
     assert L.tl_probe_read(16, 32, None, None) == tl.TL_ERR_NULL

@@ -118,3 +118,57 @@ def test_gamma_is_the_fp16_value():
     y1 = oracle.gemm(x, W, np.float16(1))
     assert np.array_equal(y, 0.0200042724609375 * y1)
     assert np.array_equal(oracle.gemm(x, W, si.gamma_bits(g)), y)
+
+
+# --- per-group scales ------------------------------------------------------------------
+
+@pytest.mark.parametrize("M,N,K,group", [(1, 1, 4, 2), (2, 3, 10, 4), (3, 2, 33, 16), (2, 2, 16, 16), (1, 3, 7, 64)])
+def test_group_scales_brute_force_exact_rationals(M, N, K, group):
+    # the definition, element by element, in exact rational arithmetic (the last group is short
+    # in three of the cases); the fp64 result may differ from it by the rounding of the sum
+    # over groups only
+    rng = np.random.default_rng(900 + K)
+    x, W, _ = _tiny(40 + K, M, N, K)
+    G = (K + group - 1) // group
+    sc = si.group_scales(rng, G, N)
+    y = oracle.gemm_group_scales(x, W, sc, group)
+    for m in range(M):
+        for n in range(N):
+            exact = Fraction(0)
+            for g in range(G):
+                part = sum(Fraction(float(x[m, k])) * int(W[n, k]) for k in range(g * group, min(K, (g + 1) * group)))
+                exact += Fraction(float(sc[g, n])) * part
+            assert abs(Fraction(y[m, n]) - exact) <= abs(exact) * Fraction(1, 2 ** 48) + Fraction(1, 2 ** 60)
+
+
+def test_group_scales_all_equal_is_the_single_gamma_product():
+    x, W, g = si.layer(31, 3, 9, 1000)
+    sc = np.full((4, 9), g, dtype=np.float16)          # groups of 256, the last one short
+    y = oracle.gemm_group_scales(x, W, sc, 256)
+    assert np.allclose(y, oracle.gemm(x, W, g), rtol=1e-13, atol=1e-15)
+
+
+def test_group_scales_one_group_switched_on_is_that_slice_of_k():
+    x, W, g = si.layer(32, 2, 5, 700)
+    for grp in range(3):                                # groups of 256: [0,256) [256,512) [512,700)
+        sc = np.zeros((3, 5), dtype=np.float16)
+        sc[grp, :] = g
+        k0, k1 = grp * 256, min(700, grp * 256 + 256)
+        ref = oracle.gemm(np.ascontiguousarray(x[:, k0:k1]), np.ascontiguousarray(W[:, k0:k1]), g)
+        assert np.array_equal(oracle.gemm_group_scales(x, W, sc, 256), ref)
+
+
+def test_group_scales_single_group_is_one_scale_per_output_row_and_linear_in_the_scales():
+    rng = np.random.default_rng(33)
+    x, W, _ = si.layer(33, 2, 6, 300)
+    sc = si.group_scales(rng, 1, 6)
+    S = x.astype(np.float64) @ W.astype(np.float64).T
+    assert np.array_equal(oracle.gemm_group_scales(x, W, sc, 512), S * sc.astype(np.float64))   # per column n
+    a = si.group_scales(rng, 3, 6)
+    b = np.zeros_like(a)
+    b[1, 2] = a[1, 2]                                   # split one entry off: y(a) = y(a - b) + y(b)
+    c = a.copy()
+    c[1, 2] = 0
+    ya, yb, yc = (oracle.gemm_group_scales(x, W, s, 128) for s in (a, b, c))
+    assert np.allclose(ya, yb + yc, rtol=1e-13, atol=1e-15)
+    assert np.count_nonzero(yb[:, [0, 1, 3, 4, 5]]) == 0   # the entry belongs to output row 2 alone
