@@ -268,6 +268,53 @@ def main():
                               GBps=round(bb / us / 1e3, 1), hbm_frac=round(bb / us / 1e3 / HBM_PEAK_GBS, 4)))
         del blay
 
+    # the 1.6-bit format and per-group scales beside the 2-bit, single-gamma kernel (one call each)
+    formats = []
+    if not args.no_per_call:
+        frng = np.random.default_rng(si.SEEDS["c5"])
+        for name in si.DECODE_SWEEP_SHAPES:
+            lay = layers[name]
+            N = lay["N"]
+            W3 = tl.tl_pack_1p6bit(lay["W"])
+            copies3 = max(2, min(24, (512 << 20) // W3.nbytes))
+            ring3 = torch.empty((copies3,) + W3.shape, dtype=torch.uint8, device=dev)
+            ring3[0].copy_(torch.from_numpy(W3))
+            for i in range(1, copies3):
+                ring3[i].copy_(ring3[0])
+            group = 256
+            sc = torch.from_numpy(si.group_scales(frng, K // group, N).view(np.int16)).to(dev)
+            for M in (1, 4, 16):
+                cur = [0]
+                fy = torch.empty((M, N), dtype=torch.int16, device=dev)    # the sweep's outputs stay as they are
+
+                def call3():
+                    i = cur[0]
+                    cur[0] = (i + 1) % copies3
+                    st = L.tl_ternary_gemm_1p6(xd[M].data_ptr(), ring3[i].data_ptr(), lay["gbits"],
+                                               fy.data_ptr(), M, N, K, stream)
+                    if st != tl.TL_OK:
+                        raise tl.TlError(st, "tl_ternary_gemm_1p6")
+
+                def call_gs():
+                    i = cursor[name]
+                    cursor[name] = (i + 1) % lay["copies"]
+                    st = L.tl_ternary_gemm_gs(xd[M].data_ptr(), lay["ring"][i].data_ptr(), sc.data_ptr(), group,
+                                              fy.data_ptr(), M, N, K, stream)
+                    if st != tl.TL_OK:
+                        raise tl.TlError(st, "tl_ternary_gemm_gs")
+
+                reps = max(1, min(args.steps, 200))
+                us2 = timed(lambda: launch(name, M), reps) * 1e3 / reps
+                us3 = timed(call3, reps) * 1e3 / reps
+                usg = timed(call_gs, reps) * 1e3 / reps
+                b2 = algorithmic_bytes(M, N, K)
+                b3 = N * W3.shape[1] + 2 * M * K + 2 * M * N
+                formats.append(dict(layer=name, M=M, N=N, K=K,
+                                    two_bit=dict(us=round(us2, 3), GBps=round(b2 / us2 / 1e3, 1)),
+                                    one_point_six_bit=dict(us=round(us3, 3), GBps=round(b3 / us3 / 1e3, 1)),
+                                    two_bit_group_scales_256=dict(us=round(usg, 3), GBps=round((b2 + 2 * (K // group) * N) / usg / 1e3, 1))))
+            del ring3
+
     # dominant kernel: the small-M kernel in its grouped launch; one launch = one step
     us_launch = ms_per_step * 1e3
     traffic = None
@@ -335,7 +382,7 @@ def main():
                    "gemms_per_step": len(calls), "launches_per_step": 1, "weight_ring_copies": {n: layers[n]["copies"] for n in layers},
                    "algorithmic_bytes_per_step": step_bytes},
         "hbm_frac_of_peak": round(value / HBM_PEAK_GBS, 4),
-        "roofline": roofline, "cpu_baseline": cpu, "single_calls": single, "per_call": per_call, "prefill": prefill, "mid_batch": mid_batch, "block": block,
+        "roofline": roofline, "cpu_baseline": cpu, "single_calls": single, "per_call": per_call, "prefill": prefill, "mid_batch": mid_batch, "block": block, "formats": formats,
         "launch_mode": "eager" if args.eager else "hip_graph_replay",
         "host_wall_ms_timed_region_incl_capture": round(wall_ms, 2), "context": PAPER_CONTEXT,
     }
