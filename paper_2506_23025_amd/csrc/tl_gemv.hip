@@ -1039,13 +1039,9 @@ hipError_t launch_gemv_jobs(const GemmDesc* jobs, int count, hipStream_t s)
     // a round trip to memory for the activations; that pays once the call holds enough work to
     // give every workgroup a run of a few tiles (e.g. the linears of a whole block), otherwise
     // the general kernel takes those jobs.
-    int64_t call_cost = 0;
-    for (int i = 0; i < count; ++i) {
-        const int64_t slices = (jobs[i].K + kSliceK - 1) / kSliceK;
-        (void)slices;
-        call_cost += ((jobs[i].M + 15) / 16) * ((jobs[i].N + 15) / 16);      // tiles of the whole call
-    }
-    const bool long_k_streams = call_cost >= int64_t(g_policy.stream_groups) * g_policy.long_k_min_run;
+    int64_t call_tiles = 0;                                   // tiles of the whole call
+    for (int i = 0; i < count; ++i) call_tiles += ((jobs[i].M + 15) / 16) * ((jobs[i].N + 15) / 16);
+    const bool long_k_streams = call_tiles >= int64_t(g_policy.stream_groups) * g_policy.long_k_min_run;
     // bs: stream form; bs2: stream form with jobs of up to 32 rows (two blocks of 16 per wave);
     // bg: general kernel
     GemvBatch bs, bs2, bg;
