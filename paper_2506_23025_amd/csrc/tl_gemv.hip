@@ -600,7 +600,13 @@ gemv_stream_kernel(GemvBatch b)
             const int xrow = mi & (mr - 1);
             const uint32_t xr_off = uint32_t(xrow) * 1024u + uint32_t(mg) * 128u;
             const uint32_t sw = uint32_t(xrow & 7);
-            // breg[nb][h][wd][e]: (x[k], x[k + 8]) with k = slice0 + 64 (4h + g) + 16 wd + e
+            // breg[nb][h][wd][e]: (x[k], x[k + 8]) with k = slice0 + 64 (4h + g) + 16 wd + e.
+            // Columns that stand for no activation row get zeros (byte selector 0x0c), not the
+            // unwritten staging rows: nothing is stored from them, and multiplying zeros costs
+            // the matrix pipes less power than multiplying copies of real rows.
+            const bool live = mi < rows;
+            const uint32_t sel_lo = live ? 0x05040100u : 0x0c0c0c0cu;
+            const uint32_t sel_hi = live ? 0x07060302u : 0x0c0c0c0cu;
 #pragma unroll
             for (int h = 0; h < 2; ++h)
 #pragma unroll
@@ -611,8 +617,8 @@ gemv_stream_kernel(GemvBatch b)
                         my_lds + xr_off + h * 512 + ((uint32_t(2 * wd + 1) ^ sw) << 4));
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        breg[nb][h][wd][2 * r] = __builtin_amdgcn_perm(hi[r], lo[r], 0x05040100u);
-                        breg[nb][h][wd][2 * r + 1] = __builtin_amdgcn_perm(hi[r], lo[r], 0x07060302u);
+                        breg[nb][h][wd][2 * r] = __builtin_amdgcn_perm(hi[r], lo[r], sel_lo);
+                        breg[nb][h][wd][2 * r + 1] = __builtin_amdgcn_perm(hi[r], lo[r], sel_hi);
                     }
                 }
             const uint32_t c = 0x80108010u;               // fp16 pair of -2^-20
