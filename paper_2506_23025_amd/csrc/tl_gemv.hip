@@ -108,13 +108,20 @@ __device__ __forceinline__ JobTable load_table(int lane)
     kptr ka = (kptr)__builtin_amdgcn_kernarg_segment_ptr();     // GemvBatch is the only argument
     const int k = lane & 15;
     JobTable r;
-    r.item0 = *(const __attribute__((address_space(4))) int*)(ka + offsetof(GemvBatch, item0) + 4 * k);
-    const __attribute__((address_space(4))) u32x4* jp =
-        (const __attribute__((address_space(4))) u32x4*)(ka + offsetof(GemvBatch, job) + sizeof(GemvJob) * k);
+    r.item0 = 0x7fffffff;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const u32x4 q = jp[i];
-        r.d[4 * i] = q[0]; r.d[4 * i + 1] = q[1]; r.d[4 * i + 2] = q[2]; r.d[4 * i + 3] = q[3];
+    for (int i = 0; i < 16; ++i) r.d[i] = 0u;
+    // only lanes 0..15 load (the entries are read with v_readlane from those lanes): a quarter
+    // of the addresses for the CU's address path, which all eight waves go through at once
+    if (lane < 16) {
+        r.item0 = *(const __attribute__((address_space(4))) int*)(ka + offsetof(GemvBatch, item0) + 4 * k);
+        const __attribute__((address_space(4))) u32x4* jp =
+            (const __attribute__((address_space(4))) u32x4*)(ka + offsetof(GemvBatch, job) + sizeof(GemvJob) * k);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const u32x4 q = jp[i];
+            r.d[4 * i] = q[0]; r.d[4 * i + 1] = q[1]; r.d[4 * i + 2] = q[2]; r.d[4 * i + 3] = q[3];
+        }
     }
     return r;
 }
