@@ -185,3 +185,22 @@ def test_padding_bits_and_bytes():
     P3 = tl.tl_pack_1p6bit(W)
     assert P3[0, :4].tolist() == [242, 242, 242, 2 + 6 + 18 + 54 + 81]
     assert not P3[0, 4:].any()
+
+
+def test_header_is_plain_c_and_the_library_links_from_c(tmp_path):
+    # include/tl.h under a strict C99 compiler, a C program linked against libtl.so
+    import os
+    import shutil
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    cc = shutil.which("gcc") or shutil.which("cc")
+    assert cc, "no C compiler"
+    libdir = os.path.dirname(tl.LIB_PATH)
+    exe = str(tmp_path / "abi_host")
+    cmd = [cc, "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(root, "include"),
+           os.path.join(root, "tests", "c", "abi_host.c"), "-o", exe, "-L", libdir, "-ltl",
+           "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib", "-Wl,--allow-shlib-undefined"]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([exe], capture_output=True, text=True)
+    assert r.returncode == 0 and r.stdout.strip() == "ok", (r.returncode, r.stdout, r.stderr)
