@@ -505,3 +505,47 @@ def test_gemm_group_scales_equal_scales_reproduce_the_single_gamma_kernel_bits()
     y1 = run_gemm(x, Wp, g, N, K, tl.TL_PATH_GEMV)
     assert_close(y, y1.astype(np.float64), x, g, "equal scales against the single-gamma kernel")
     assert_close(y, oracle.gemm_packed2(x, Wp, g, K), x, g, "equal scales against the oracle")
+
+
+# --- seeded random shapes through every dispatch rule --------------------------------------
+
+def _random_shape(rng):
+    M = int(rng.choice([1, 2, 3, 5, 8, 16, 17, 31, 32, 33, 64, 70, 130, 300]))
+    N = int(rng.choice([1, 3, 4, 15, 16, 17, 100, 256, 272, 513, 1000, 2049]))
+    K = int(rng.choice([16, 17, 64, 100, 128, 448, 512, 576, 1024, 2048, 3136, 4096, 4160, 6144, 11008]))
+    return M, N, K
+
+
+def test_random_shapes_single_calls():
+    rng = np.random.default_rng(20250623)
+    for case in range(36):
+        M, N, K = _random_shape(rng)
+        x, W, g = si.layer(880000 + case, M, N, K)
+        Wp = tl.tl_pack_2bit(W)
+        print(f"case {case}: {M}x{N}x{K}", flush=True)
+        y = run_gemm(x, Wp, g, N, K)
+        assert_close(y, oracle.gemm_packed2(x, Wp, g, K), x, g, f"random shape {M}x{N}x{K}")
+
+
+def test_random_grouped_calls():
+    import torch
+    rng = np.random.default_rng(20250624)
+    for call in range(6):
+        count = int(rng.integers(2, 21))
+        host, dev, jobs, specs = [], [], [], []
+        for i in range(count):
+            M, N, K = _random_shape(rng)
+            x, W, g = si.layer(890000 + 100 * call + i, M, N, K)
+            Wp = tl.tl_pack_2bit(W)
+            xd, wd = to_dev(x.view(np.int16)), dev_u32(Wp)
+            yd = torch.full((M, N), -21555, dtype=torch.int16, device="cuda")
+            host.append((x, Wp, g))
+            dev.append(yd)
+            specs.append((M, N, K))
+            jobs.append((xd, wd, si.gamma_bits(g), yd, M, N, K))
+        print(f"call {call}: {specs}", flush=True)
+        tl.tl_ternary_gemm_grouped(jobs)
+        torch.cuda.synchronize()
+        for (M, N, K), (x, Wp, g), yd in zip(specs, host, dev):
+            y = yd.cpu().numpy().view(np.float16)
+            assert_close(y, oracle.gemm_packed2(x, Wp, g, K), x, g, f"random grouped call {call}: {M}x{N}x{K}")
