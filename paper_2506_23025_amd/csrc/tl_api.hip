@@ -33,22 +33,42 @@ inline tl_status from_hip(hipError_t e) { return e == hipSuccess ? TL_OK : TL_ER
 // M at and below which the 1.6-bit weight-streaming kernel is used.
 constexpr int64_t kGemvMaxM = 128;
 
-// Small-M kernel (blocks of 16 activation rows that each stream W) or LDS-tiled MFMA kernel,
-// when both can run the shape: whichever the measured cost models below make cheaper.  The
-// small-M kernel streams W once per block of 16 rows at about 5.6 TB/s (0.9 us at least; blocks
-// of 32 rows cost 1.35 times as much, plus 4 us for their shorter items); the
-// MFMA kernel walks K in steps of 64 at 0.72 us per step while its 128 x 128 tiles number at
-// most one per CU, else at 0.95 us per step and 256 tiles of 128 x 256.
+// Small-M kernel (blocks of 16 or 32 activation rows that each stream W) or LDS-tiled MFMA
+// kernel, when both can run the shape: whichever the cost models below make cheaper.  They are
+// fits to measurements (us; W in MB of packed weights):
+//  * small-M, blocks of 32 rows: 4 + blocks x (0.45 + 0.205 W)      (4096 -> 14336: 3.46 us per block)
+//  * small-M, blocks of 16 rows: 3.8 + blocks x W x (0.17 while W stays in the L2 caches, 0.21
+//    beyond, 0.264 when K needs several passes), at least 0.5 per block
+//  * MFMA, 128 x 128 tiles (at most one per CU): 3 + K/64 x (0.60 + 0.08 tiles/256)
+//  * MFMA, 128 x 256 tiles: (5 + K/64 x 0.86) x f(tiles/256), f(r) = 1 up to one tile per CU, then
+//    max(r, 0.82 ceil(r)): a round that is not full costs most of a full one
+//    (4096 -> 14336: 336 tiles 98 us, 448 tiles 107 us, 896 tiles 219 us).
 inline bool prefer_small_m(int64_t M, int64_t N, int64_t K)
 {
     if (M <= 16) return true;
-    const double w_bytes = double(N) * double(K) / 4.0;
-    const double per_block = w_bytes / 5.6e6 > 0.9 ? w_bytes / 5.6e6 : 0.9;
-    const double t_small = tl::gemv_two_blocks(M, N, K) ? 4.0 + double((M + 31) / 32) * 1.35 * per_block
-                                                        : double((M + 15) / 16) * per_block;
-    const double wide = double((M + 127) / 128) * double((N + 255) / 256);
-    const double per_step = wide <= 128.0 ? 0.72 : 0.95 * (wide > 256.0 ? wide / 256.0 : 1.0);
-    const double t_mfma = double(K / 64) * per_step;
+    const double w_mb = double(N) * double(K) / 4.0e6;
+    const int64_t slices = (K + 511) / 512;
+    double t_small;
+    if (tl::gemv_two_blocks(M, N, K)) {
+        t_small = 4.0 + double((M + 31) / 32) * (0.45 + 0.205 * w_mb);
+    } else {
+        const double per_mb = slices > 8 ? 0.264 : (w_mb < 8.4 ? 0.17 : 0.21);
+        const double per_block = per_mb * w_mb > 0.5 ? per_mb * w_mb : 0.5;
+        t_small = 3.8 + double((M + 15) / 16) * per_block;
+    }
+    const double steps = double(K / 64);
+    const double row_blocks = double((M + 127) / 128);
+    const double wide = row_blocks * double((N + 255) / 256);
+    double t_mfma;
+    if (wide <= 128.0) {                                   // 128 x 128 tiles, at most one per CU
+        const double tiles = row_blocks * double((N + 127) / 128);
+        t_mfma = 3.0 + steps * (0.60 + 0.08 * tiles / 256.0);
+    } else {                                               // 128 x 256 tiles, in rounds of 256
+        const double r = wide / 256.0;
+        const double rounds = double(int64_t(r) + (r > double(int64_t(r)) ? 1 : 0));
+        const double f = r <= 1.0 ? 1.0 : (r > 0.82 * rounds ? r : 0.82 * rounds);
+        t_mfma = (5.0 + steps * 0.86) * f;
+    }
     return t_small < t_mfma;
 }
 

@@ -1054,7 +1054,10 @@ hipError_t launch_gemv_jobs(const GemmDesc* jobs, int count, hipStream_t s)
     // the general kernel takes those jobs.
     int64_t call_tiles = 0;                                   // tiles of the whole call
     for (int i = 0; i < count; ++i) call_tiles += ((jobs[i].M + 15) / 16) * ((jobs[i].N + 15) / 16);
-    const bool long_k_streams = call_tiles >= int64_t(g_policy.stream_groups) * g_policy.long_k_min_run;
+    // (measured: one job of 512 tiles is better off in the general kernel, 11008 -> 8192 at M = 1
+    // 9.7 against 10.9 us; two jobs of 256 tiles stream better, 11008 -> 4096 at M = 32 16.1 against 20.3 us)
+    const bool long_k_streams = call_tiles >= int64_t(g_policy.stream_groups) * g_policy.long_k_min_run ||
+                                (blocks_total >= 2 && call_tiles >= int64_t(g_policy.stream_groups) * 2);
     // bs: stream form; bs2: stream form with jobs of up to 32 rows (two blocks of 16 per wave);
     // bg: general kernel
     GemvBatch bs, bs2, bg;
