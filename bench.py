@@ -224,8 +224,13 @@ def main():
         reps = max(1, min(args.steps, 40))
         us = timed(lambda: launch_prefill(M), reps) * 1e3 / reps
         fl = 2.0 * M * pre_N * K
+        which = {tl.TL_PATH_GEMV: "small-M kernel", tl.TL_PATH_MFMA: "mfma_kernel",
+                 tl.TL_PATH_GENERIC: "generic kernel"}[tl.tl_ternary_gemm_which(M, pre_N, K)]
+        us_auto = us if which == "mfma_kernel" else timed(lambda: launch_prefill(M, tl.TL_PATH_AUTO), reps) * 1e3 / reps
         prefill.append(dict(layer=pre_name, M=M, N=pre_N, K=K, kernel="mfma_kernel", us=round(us, 2),
-                            TFLOPs=round(fl / us / 1e6, 1), mfma_frac=round(fl / us / 1e6 / MFMA_PEAK_TFLOPS, 4)))
+                            TFLOPs=round(fl / us / 1e6, 1), mfma_frac=round(fl / us / 1e6 / MFMA_PEAK_TFLOPS, 4),
+                            tl_ternary_gemm=dict(kernel=which, us=round(us_auto, 2), TFLOPs=round(fl / us_auto / 1e6, 1),
+                                                 mfma_frac=round(fl / us_auto / 1e6 / MFMA_PEAK_TFLOPS, 4))))
     for M in ([] if args.no_per_call else (32, 64, 128, 256, 512)):
         reps = max(1, min(args.steps, 40))
         us = timed(lambda: launch_prefill(M, tl.TL_PATH_AUTO), reps) * 1e3 / reps

@@ -151,6 +151,14 @@ tl_status tl_unpack_dev(tl_format fmt, const void* packed, int64_t N, int64_t K,
 tl_status tl_ternary_gemm(const void* x, const void* Wpacked, uint16_t gamma_fp16_bits,
                           void* y, int64_t M, int64_t N, int64_t K, void* stream);
 
+/*
+ * The kernel tl_ternary_gemm (TL_PATH_AUTO) runs for a shape: TL_PATH_GEMV, TL_PATH_MFMA or
+ * TL_PATH_GENERIC; TL_PATH_AUTO (0) if M, N or K is not a valid size.  A pure function of the
+ * three numbers (host side, touches no GPU): the library's cost models of its two fast
+ * kernels decide between them where both can run the shape.
+ */
+tl_path tl_ternary_gemm_which(int64_t M, int64_t N, int64_t K);
+
 /* Same, with the kernel forced.  TL_ERR_UNSUPPORTED if `path` cannot run the shape. */
 tl_status tl_ternary_gemm_path(const void* x, const void* Wpacked, uint16_t gamma_fp16_bits,
                                void* y, int64_t M, int64_t N, int64_t K, void* stream,

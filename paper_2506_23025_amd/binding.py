@@ -23,6 +23,7 @@ EXPORTS = (
     "tl_pack_1p6bit_fx", "tl_unpack_1p6bit_fx", "tl_unpack", "tl_unpack_dev", "tl_ternary_gemm",
     "tl_ternary_gemm_path", "tl_ternary_gemm_grouped", "tl_ternary_gemm_1p6", "tl_ternary_gemm_1p6_fx",
     "tl_ternary_gemm_gs",
+    "tl_ternary_gemm_which",
     "tl_probe_copy",
     "tl_probe_read",
 )
@@ -83,6 +84,8 @@ def _load():
     L.tl_ternary_gemm_1p6_fx.restype = ci
     L.tl_ternary_gemm_gs.argtypes = [vp, vp, vp, i64, vp, i64, i64, i64, vp]
     L.tl_ternary_gemm_gs.restype = ci
+    L.tl_ternary_gemm_which.argtypes = [i64, i64, i64]
+    L.tl_ternary_gemm_which.restype = ci
     L.tl_probe_copy.argtypes = [vp, vp, sz, vp]
     L.tl_probe_copy.restype = ci
     L.tl_probe_read.argtypes = [vp, sz, vp, vp]
@@ -235,6 +238,10 @@ def tl_ternary_gemm_1p6(x, Wpacked, gamma_fp16_bits, y, M, N, K, stream=None):
 def tl_ternary_gemm_1p6_fx(x, Wpacked, gamma_fp16_bits, y, M, N, K, stream=None):
     _check(_lib.tl_ternary_gemm_1p6_fx(_ptr(x), _ptr(Wpacked), gamma_fp16_bits, _ptr(y), M, N, K,
                                        _stream(stream)), "tl_ternary_gemm_1p6_fx")
+
+
+def tl_ternary_gemm_which(M, N, K):
+    return int(_lib.tl_ternary_gemm_which(M, N, K))
 
 
 def tl_ternary_gemm_gs(x, Wpacked, scales, group, y, M, N, K, stream=None):

@@ -92,6 +92,14 @@ tl_status tl_unpack_dev(tl_format fmt, const void* packed, int64_t N, int64_t K,
     return TL_ERR_UNSUPPORTED;
 }
 
+tl_path tl_ternary_gemm_which(int64_t M, int64_t N, int64_t K)
+{
+    if (!tl::dims_ok(M, N, K)) return TL_PATH_AUTO;
+    if (tl::gemv_supports(M, N, K) && (tl::prefer_small_m(M, N, K) || !tl::mfma_supports(M, N, K))) return TL_PATH_GEMV;
+    if (tl::mfma_supports(M, N, K)) return TL_PATH_MFMA;
+    return TL_PATH_GENERIC;
+}
+
 tl_status tl_ternary_gemm_path(const void* x, const void* Wpacked, uint16_t gamma_fp16_bits, void* y,
                                int64_t M, int64_t N, int64_t K, void* stream, tl_path path)
 {
@@ -104,12 +112,7 @@ tl_status tl_ternary_gemm_path(const void* x, const void* Wpacked, uint16_t gamm
     const uint32_t* wp = static_cast<const uint32_t*>(Wpacked);
     __half* yh = static_cast<__half*>(y);
 
-    if (path == TL_PATH_AUTO) {
-        if (tl::gemv_supports(M, N, K) && (tl::prefer_small_m(M, N, K) || !tl::mfma_supports(M, N, K))) path = TL_PATH_GEMV;
-        else if (tl::mfma_supports(M, N, K)) path = TL_PATH_MFMA;
-        else if (tl::gemv_supports(M, N, K)) path = TL_PATH_GEMV;
-        else path = TL_PATH_GENERIC;
-    }
+    if (path == TL_PATH_AUTO) path = tl_ternary_gemm_which(M, N, K);
     switch (path) {
         case TL_PATH_GENERIC:
             return tl::from_hip(tl::launch_gemm_generic(xh, wp, gamma, yh, M, N, K, s));
@@ -153,7 +156,7 @@ tl_status tl_ternary_gemm_grouped(const tl_gemm_job* jobs, int64_t count, void* 
     };
     for (int64_t i = 0; i < count; ++i) {
         const tl_gemm_job& j = jobs[i];
-        if (tl::gemv_supports(j.M, j.N, j.K) && (tl::prefer_small_m(j.M, j.N, j.K) || !tl::mfma_supports(j.M, j.N, j.K))) {
+        if (tl_ternary_gemm_which(j.M, j.N, j.K) == TL_PATH_GEMV) {
             fused[nf++] = tl::GemmDesc{static_cast<const __half*>(j.x), static_cast<const uint32_t*>(j.Wpacked),
                                        static_cast<__half*>(j.y), tl::half_bits_to_float(j.gamma_fp16_bits),
                                        j.M, j.N, j.K};

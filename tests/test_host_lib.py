@@ -204,3 +204,19 @@ def test_header_is_plain_c_and_the_library_links_from_c(tmp_path):
     assert r.returncode == 0, r.stderr
     r = subprocess.run([exe], capture_output=True, text=True)
     assert r.returncode == 0 and r.stdout.strip() == "ok", (r.returncode, r.stdout, r.stderr)
+
+
+def test_kernel_choice_is_a_pure_function_of_the_shape():
+    # decode batch sizes stream the weights; the prefill sizes of the workloads use the tiled MFMA
+    # kernel; shapes neither fast kernel takes fall back; invalid sizes give no path
+    for M in (1, 2, 4, 8, 16):
+        for N, K in ((2048, 2048), (4096, 4096), (14336, 4096), (4096, 11008)):
+            assert tl.tl_ternary_gemm_which(M, N, K) == tl.TL_PATH_GEMV
+    for M in (1024, 2048):
+        assert tl.tl_ternary_gemm_which(M, 14336, 4096) == tl.TL_PATH_MFMA
+    assert tl.tl_ternary_gemm_which(3, 70, 100) == tl.TL_PATH_GENERIC      # K not a multiple of 64
+    assert tl.tl_ternary_gemm_which(0, 16, 64) == tl.TL_PATH_AUTO
+    assert tl.tl_ternary_gemm_which(1, 16, -64) == tl.TL_PATH_AUTO
+    # the model follows the measured crossovers (small-M kernel up to M = 768 at 4096 -> 14336)
+    assert tl.tl_ternary_gemm_which(512, 14336, 4096) == tl.TL_PATH_GEMV
+    assert tl.tl_ternary_gemm_which(768, 4096, 11008) == tl.TL_PATH_MFMA
