@@ -183,7 +183,8 @@ gemv3_kernel(Gemv3Params p)
         }
         lut[b] = u32x2{(c[0] << 4) | (c[2] << 8) | (c[3] << 20), (c[1] << 4) | (c[4] << 20)};
     }
-    lds_barrier3();
+    // (the barrier that makes the table visible comes after the operands are built: they need
+    // the wave's own activation transfers only)
     if (wave < slices) __builtin_amdgcn_s_waitcnt(vmcnt_imm3(2 * T));   // LDS-DMA is not tracked by the compiler
 
     for (; slice < slices; slice += NW) {
@@ -238,6 +239,7 @@ gemv3_kernel(Gemv3Params p)
                     nsx = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(a), as_h8(b2), nsx, 0, 0, 0);
                 }
         }
+        if (slice == wave) lds_barrier3();                 // first pass (every wave runs it): the table is complete
 #pragma unroll
         for (int t = 0; t < T; ++t) {
             unsigned char* const reg_t = my_lds + t * 2048;
