@@ -14,21 +14,25 @@
 //    (i, g) to hold row i.  The 2 KB tile slice is turned through wave-private LDS
 //    (ds_write_b128 / ds_read_b128, XOR-swizzled, no barrier: a wave only reads what it
 //    wrote itself).
-//  * Decode costs 11 VALU operations per 16 weights.  `word & (3 << 2j | 3 << (2j+16))`
+//  * Decode costs 10 VALU operations per 16 weights.  `word & (3 << 2j | 3 << (2j+16))`
 //    leaves two codes in the mantissa fields of an fp16 pair, i.e. the subnormal numbers
 //    c * 4^j * 2^-24 (gfx950 MFMA does not flush fp16 subnormals).  The matrix core aligns
 //    products by their exponent FIELDS, so a code low in the mantissa loses accuracy
-//    (measured: ~2^-17 relative at j = 0, none at j >= 3).  Three shifted copies of the
-//    word (<< 4, >> 2, >> 8) therefore bring every code to j in {2, 3, 4}.  Products of
+//    (measured: ~2^-17 relative at j = 0, none at j >= 3).  The word as loaded and two shifted
+//    copies (<< 4, >> 6) therefore bring every code to j in {2, 3, 4}.  Products of
 //    different j carry different power-of-two factors, so they go to three accumulators
 //    that are combined once per tile: sum_j 2^(24-2j) acc_j = sum_k x_k c_k.  With
 //    c = w + 1 the result is sum_k x_k c_k - sum_k x_k; the second sum comes from one more
 //    group of MFMAs per wave whose 16-row operand is a constant, and seeds the accumulator.
 //  * Split-K partial tiles of the NW waves are added in a fixed order through LDS, scaled
 //    by gamma, rounded to fp16 (RNE) and stored.  No atomics: results are deterministic.
-//  * One launch can carry up to 16 independent jobs (a job = one matrix and at most 16
-//    activation rows); a workgroup finds its job from its index.  Grouped launches use
-//    4-wave groups, two per CU, so that one group's wait for HBM overlaps the other's MFMAs.
+//  * One launch can carry up to 16 independent jobs (a job = one matrix and at most 16, in
+//    one variant 32, activation rows); a workgroup finds its job from its index.
+//  * Two forms.  The stream form (gemv_stream_kernel: K up to 8 slices per pass, the usual
+//    case) gives a wave one slice for the whole kernel and a workgroup a run of consecutive
+//    tiles of one job, so activations are staged once and only weights move afterwards.  The
+//    general form (gemv_kernel) loops a wave over slices and a workgroup over items of any
+//    job; it takes lone calls with long K.
 #include "tl_internal.hpp"
 
 #include <cstddef>
