@@ -253,7 +253,7 @@ def main():
             for i in range(1, copies):
                 ring[i].copy_(ring[0])
             blay.append(dict(name=name, K=k, N=N, ring=ring, copies=copies, gbits=si.gamma_bits(si.gamma_uniform(brng))))
-        for M in (1, 16):
+        for M in si.BLOCK_M:
             bx = {k: torch.from_numpy(si.activations(brng, M, k).view(np.int16)).to(dev) for k in {l["K"] for l in blay}}
             by = [torch.empty((M, l["N"]), dtype=torch.int16, device=dev) for l in blay]
             bcur = [0]
