@@ -549,3 +549,34 @@ def test_random_grouped_calls():
         for (M, N, K), (x, Wp, g), yd in zip(specs, host, dev):
             y = yd.cpu().numpy().view(np.float16)
             assert_close(y, oracle.gemm_packed2(x, Wp, g, K), x, g, f"random grouped call {call}: {M}x{N}x{K}")
+
+
+def test_random_shapes_other_formats_and_group_scales():
+    rng = np.random.default_rng(20250625)
+    for case in range(16):
+        M, N, K = _random_shape(rng)
+        x, W, g = si.layer(895000 + case, M, N, K)
+        print(f"case {case}: {M}x{N}x{K}", flush=True)
+        # 1.6-bit, plain base 3
+        y3 = run_gemm3(x, tl.tl_pack_1p6bit(W), g, N, K)
+        assert_close(y3, oracle.gemm(x, W, g), x, g, f"random 1.6-bit {M}x{N}x{K}")
+        # per-group scales, group sizes on both sides of the fast kernel's conditions
+        group = int(rng.choice([16, 64, 256, 512, 1024]))
+        sc = si.group_scales(rng, (K + group - 1) // group, N)
+        Wp = tl.tl_pack_2bit(W)
+        ys = run_gemm_gs(x, Wp, sc, group, N, K)
+        assert_close(ys, oracle.gemm_packed2_group_scales(x, Wp, sc, group, K), x, float(sc.max()),
+                     f"random group scales {M}x{N}x{K} / {group}")
+
+
+def test_probe_kernels_run_and_leave_memory_alone():
+    import torch
+    n = (1 << 20) + 16
+    src = torch.arange(n, dtype=torch.int32, device="cuda")
+    dst = torch.zeros(n, dtype=torch.int32, device="cuda")
+    sink = torch.full((4,), 7, dtype=torch.int32, device="cuda")
+    tl.tl_probe_read(src, n * 4, sink)
+    tl.tl_probe_copy(dst, src, n * 4)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
+    assert sink.tolist() == [7, 7, 7, 7]          # the fold of 0..n-1 is not the value that triggers the store
