@@ -36,7 +36,8 @@ constexpr int64_t kGemvMaxM = 128;
 // Small-M kernel (blocks of 16 or 32 activation rows that each stream W) or LDS-tiled MFMA
 // kernel, when both can run the shape: whichever the cost models below make cheaper.  They are
 // fits to measurements (us; W in MB of packed weights):
-//  * small-M, blocks of 32 rows: 4 + blocks x (0.45 + 0.205 W)      (4096 -> 14336: 3.46 us per block)
+//  * small-M, blocks of 32 rows: 4 + blocks x (0.45 + 0.205 W)      (4096 -> 14336: 3.46 us per block);
+//    0.33 W when K needs several passes (11008 -> 4096: 4.1 us per block)
 //  * small-M, blocks of 16 rows: 3.8 + blocks x W x (0.17 while W stays in the L2 caches, 0.21
 //    beyond, 0.264 when K needs several passes), at least 0.5 per block
 //  * MFMA, 128 x 128 tiles (at most one per CU): 3 + K/64 x (0.60 + 0.08 tiles/256)
@@ -50,7 +51,7 @@ inline bool prefer_small_m(int64_t M, int64_t N, int64_t K)
     const int64_t slices = (K + 511) / 512;
     double t_small;
     if (tl::gemv_two_blocks(M, N, K)) {
-        t_small = 4.0 + double((M + 31) / 32) * (0.45 + 0.205 * w_mb);
+        t_small = 4.0 + double((M + 31) / 32) * (0.45 + (slices > 8 ? 0.33 : 0.205) * w_mb);
     } else {
         const double per_mb = slices > 8 ? 0.264 : (w_mb < 8.4 ? 0.17 : 0.21);
         const double per_block = per_mb * w_mb > 0.5 ? per_mb * w_mb : 0.5;

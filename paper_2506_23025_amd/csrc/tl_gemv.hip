@@ -461,7 +461,6 @@ gemv_stream_kernel(GemvBatch b)
     const int NW = blockDim.x >> 6;
     // LDS of a wave: activation rows (16 KB) while the operands are built; afterwards two tile
     // regions at 0 and 2 KB, and from 4 KB two sets of T NB partial-sum tiles (1 KB each).
-    static_assert(NB == 1 || !PASSES, "two row blocks are not combined with passes over K");
     static_assert(!GS || (NB == 1 && MULTI), "per-group scales: one row block, job table");
     constexpr int H = GS ? 2 : 1;             // accumulator sets per tile: one per 256-weight half
     constexpr int kStride = stream_wave_lds(T * NB);
@@ -747,7 +746,7 @@ gemv_stream_kernel(GemvBatch b)
                                 : f32x4{0.f, 0.f, 0.f, 0.f};
             f32x4 s = ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
             // sums of the earlier passes over K: kept by the thread that owns this output quad
-            f32x4* const keep = reinterpret_cast<f32x4*>(ysum + (tile - tile0) * 1024) + l;
+            f32x4* const keep = reinterpret_cast<f32x4*>(ysum + ((tile - tile0) * NB + nb) * 1024) + l;
             if (!first_pass && tile < tile_end) s += *keep;
             if (!last_pass && tile < tile_end) *keep = s;
             const int n = tile * 16 + 4 * (l >> 4);
@@ -823,7 +822,8 @@ KernelFn pick_stream_gs(int T, bool passes)
 
 KernelFn pick_stream(int T, bool multi, bool passes, int nb)
 {
-    if (nb == 2) {                                         // two row blocks: T <= 2, one pass over K
+    if (nb == 2) {                                         // two row blocks: T <= 2
+        if (passes) return T == 1 ? gemv_stream_kernel<1, true, true, 2> : gemv_stream_kernel<2, true, true, 2>;
         if (T == 1) return multi ? gemv_stream_kernel<1, true, false, 2> : gemv_stream_kernel<1, false, false, 2>;
         return multi ? gemv_stream_kernel<2, true, false, 2> : gemv_stream_kernel<2, false, false, 2>;
     }
@@ -922,7 +922,7 @@ hipError_t launch_stream(GemvBatch& b, int max_slices, int nb, hipStream_t s, bo
     int run = 1;                                           // longest run of tiles of a workgroup
     for (int j = 0; j < b.count; ++j) {
         const int r = (b.job[j].tiles + wg[j] - 1) / wg[j];
-        if (passes(j) > 1 && r > kStreamMaxRun) return hipErrorInvalidValue;
+        if (passes(j) > 1 && r > kStreamMaxRun / nb) return hipErrorInvalidValue;   // 1 KB of kept sums per tile and row block
         if (r > run) run = r;
     }
     // Tiles per item.  Measured: items of 3 tiles stream 3-4 % faster than items of 4 (6 KB
@@ -935,7 +935,7 @@ hipError_t launch_stream(GemvBatch& b, int max_slices, int nb, hipStream_t s, bo
     if (nb == 2) {                       // two row blocks per job: at most 2 tiles per item (registers)
         if (T > 2) T = 2;
         if (2 * T > NW) T = NW / 2;
-        if (multi_pass || T < 1) return hipErrorInvalidValue;
+        if (T < 1) return hipErrorInvalidValue;
     }
     if (T < 1) T = 1;
     for (int j = 0; j < kMaxJobs; ++j) b.item0[j] = 0x7fffffff;
@@ -954,8 +954,8 @@ hipError_t launch_stream(GemvBatch& b, int max_slices, int nb, hipStream_t s, bo
     b.pad = 0;
     const bool multi = gs || b.count > 1;              // the scaled form always reads the job table
     KernelFn fn = gs ? pick_stream_gs(T, multi_pass) : pick_stream(T, multi, multi_pass, nb);
-    static bool lds_raised[5][2][kTMax + 1];
-    const int variant = gs ? (multi_pass ? 4 : 3) : (nb == 2 ? 2 : (multi_pass ? 1 : 0));
+    static bool lds_raised[6][2][kTMax + 1];
+    const int variant = gs ? (multi_pass ? 4 : 3) : (nb == 2 ? (multi_pass ? 5 : 2) : (multi_pass ? 1 : 0));
     if (!lds_raised[variant][multi][T]) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
                                            hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -979,9 +979,31 @@ hipError_t launch_batch(GemvBatch& b, bool grouped, bool stream_form, int nb, hi
     }
     if (stream_form && max_slices <= kStreamWaves * kStreamMaxPasses && (pol.stream & (b.count > 1 ? 2 : 1))) {
         const hipError_t e = launch_stream(b, max_slices, nb, s);
-        if (e != hipErrorInvalidValue || nb != 1) return e;   // else: runs too long for its LDS, general kernel
+        if (e != hipErrorInvalidValue) return e;           // else: runs too long for its LDS, general kernel
     }
-    if (nb != 1) return hipErrorInvalidValue;              // jobs of two row blocks exist for the stream form only
+    if (nb != 1) {
+        // jobs of two row blocks exist for the stream form only: each goes on as two jobs of 16 rows
+        GemvBatch h;
+        h.count = 0;
+        for (int j = 0; j < b.count; ++j) {
+            for (int part = 0; part < 2; ++part) {
+                const int rows = b.job[j].Mrem - 16 * part;
+                if (rows <= 0) break;
+                GemvJob q = b.job[j];
+                q.x = b.job[j].x + size_t(16 * part) * size_t(q.K);
+                q.y = b.job[j].y + size_t(16 * part) * size_t(q.N);
+                q.Mrem = rows < 16 ? rows : 16;
+                q.mr = pow2_at_least(q.Mrem);
+                h.job[h.count++] = q;
+                if (h.count == kMaxJobs) {
+                    const hipError_t e = launch_batch(h, true, false, 1, s);
+                    if (e != hipSuccess) return e;
+                    h.count = 0;
+                }
+            }
+        }
+        return h.count ? launch_batch(h, true, false, 1, s) : hipSuccess;
+    }
     int NW = grouped ? pol.nw_grouped : pol.nw_single;
     if (NW > max_slices) NW = max_slices;
     int resident = grouped ? pol.grid_cap : (NW <= 4 ? 512 : 256);
@@ -1097,6 +1119,16 @@ hipError_t launch_gemv_jobs(const GemmDesc* jobs, int count, hipStream_t s)
             const bool streams = j.slices <= kStreamWaves ||
                                  (long_k_streams && j.slices <= kStreamWaves * kStreamMaxPasses);
             GemvBatch& b = two_blocks ? bs2 : (streams ? bs : bg);
+            if (two_blocks && j.slices > kStreamWaves) {
+                // several passes: the kept sums allow runs of kStreamMaxRun / 2 tiles, so a launch holds
+                // at most that many tiles per workgroup
+                int64_t held = j.tiles;
+                for (int q = 0; q < b.count; ++q) held += b.job[q].tiles;
+                if (b.count > 0 && held > int64_t(g_policy.stream_groups) * (kStreamMaxRun / 2)) {
+                    hipError_t e = flush(b);
+                    if (e != hipSuccess) return e;
+                }
+            }
             b.job[b.count++] = j;
             if (b.count == kMaxJobs) {
                 hipError_t e = flush(b);

@@ -47,11 +47,14 @@ hipError_t launch_gemv(const __half* x, const uint32_t* Wp, float gamma, __half*
 // Whether the small-M kernel takes a GEMM in blocks of 32 activation rows (every decoded weight
 // operand feeds two MFMAs) rather than 16.  It halves the passes over W but shortens the items,
 // which pays when W is re-read from beyond the L2 cache or the blocks are many (measured:
-// 4096 -> 14336 from M = 64 on, 4096 -> 4096 from M = 384 on).
+// 4096 -> 14336 from M = 64 on, 4096 -> 4096 from M = 384 on).  K up to 64 slices (32768).
 inline bool gemv_two_blocks(int64_t M, int64_t N, int64_t K)
 {
     const int64_t slices = (K + 511) / 512;
-    if (M <= 16 || slices < 2 || slices > 8) return false;
+    if (M <= 16 || slices < 2 || slices > 64) return false;
+    // several passes over K: the run of a workgroup must fit its LDS, and the gain starts at M = 128
+    // (11008 -> 4096: M = 64 24.0 against 21.5 us, M = 128 28.6 against 29.3 us, M = 512 65 against 95 us)
+    if (slices > 8 && ((N + 15) / 16 > 256 * 16 || M < 128)) return false;
     return (M >= 64 && N * K / 4 >= (int64_t(8) << 20)) || M >= 384;
 }
 

@@ -199,10 +199,15 @@ def test_config3_block_single_and_grouped(M):
         assert_close(y, y1.astype(np.float64), x, g, f"block {name} M={M}, grouped against single")
 
 
-@pytest.mark.parametrize("M,N,K", [(77, 8200, 4096), (390, 130, 1024), (64, 14336, 4096), (400, 33, 2048)])
+@pytest.mark.parametrize("M,N,K", [(77, 8200, 4096), (390, 130, 1024), (64, 14336, 4096), (400, 33, 2048),
+                                   (64, 4096, 11008), (390, 520, 8704), (80, 8192, 6144), (45, 65552, 4608),
+                                   (600, 4099, 16384)])
 def test_small_m_kernel_blocks_of_32_rows(M, N, K):
     # shapes the small-M kernel takes in blocks of 32 activation rows (two row blocks per wave):
-    # ragged last block (77 = 32 + 32 + 13, 390 = 12 x 32 + 6), ragged N, several launches (M = 400)
+    # ragged last block (77 = 32 + 32 + 13, 390 = 12 x 32 + 6), ragged N, several launches (M = 400);
+    # K beyond one pass (sums of both row blocks kept in LDS between passes), a K that ends inside a
+    # slice (8704 = 17 x 512), launches cut short so that the runs fit (600 rows of 257 tiles), and
+    # a matrix too tall for that form (65552 rows: back to blocks of 16)
     x, W, g = si.layer(8800 + M + N + K, M, N, K)
     Wp = tl.tl_pack_2bit(W)
     y = run_gemm(x, Wp, g, N, K, tl.TL_PATH_GEMV)

@@ -219,4 +219,4 @@ def test_kernel_choice_is_a_pure_function_of_the_shape():
     assert tl.tl_ternary_gemm_which(1, 16, -64) == tl.TL_PATH_AUTO
     # the model follows the measured crossovers (small-M kernel up to M = 768 at 4096 -> 14336)
     assert tl.tl_ternary_gemm_which(512, 14336, 4096) == tl.TL_PATH_GEMV
-    assert tl.tl_ternary_gemm_which(768, 4096, 11008) == tl.TL_PATH_MFMA
+    assert tl.tl_ternary_gemm_which(1024, 4096, 11008) == tl.TL_PATH_MFMA
