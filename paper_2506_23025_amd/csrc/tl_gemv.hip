@@ -446,7 +446,7 @@ constexpr int stream_wave_lds(int T)
 // PASSES: some job of the launch has K longer than the waves' slices together.
 // NB: blocks of 16 activation rows a job may have (1 or 2).  With two, every decoded weight
 // operand feeds two MFMAs, one per block: the decode, which is what limits the kernel, is paid
-// once for 32 rows (not combined with PASSES).
+// once for 32 rows.  With PASSES the kept sums take 1 KB per tile and row block.
 // GS: per-group scales (Sec. 3.3, CPU inference: one fp16 scale per block along K; App. on the
 // GPU kernel: scales kept in a separate buffer) instead of one gamma: the two 256-weight halves
 // of a slice are accumulated apart, each multiplied by the scale of its group and output row.
