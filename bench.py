@@ -62,6 +62,7 @@ def main():
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
     L = tl.raw()
+    tl.tl_init()                                        # every kernel prepared before anything is captured
     stream = torch.cuda.current_stream().cuda_stream
 
     if args.mode == "copy":

@@ -152,6 +152,15 @@ tl_status tl_ternary_gemm(const void* x, const void* Wpacked, uint16_t gamma_fp1
                           void* y, int64_t M, int64_t N, int64_t K, void* stream);
 
 /*
+ * Optional.  Prepares every kernel of the library on the current HIP device (their limits for
+ * dynamically sized LDS) so that no later call has to: without it each kernel instance does
+ * this the first time it is launched.  Call it once per device, e.g. before capturing the
+ * library's calls into a HIP graph.  Idempotent; allocates nothing; TL_ERR_HIP if the runtime
+ * refuses.
+ */
+tl_status tl_init(void);
+
+/*
  * The kernel tl_ternary_gemm (TL_PATH_AUTO) runs for a shape: TL_PATH_GEMV, TL_PATH_MFMA or
  * TL_PATH_GENERIC; TL_PATH_AUTO (0) if M, N or K is not a valid size.  A pure function of the
  * three numbers (host side, touches no GPU): the library's cost models of its two fast

@@ -24,6 +24,7 @@ EXPORTS = (
     "tl_ternary_gemm_path", "tl_ternary_gemm_grouped", "tl_ternary_gemm_1p6", "tl_ternary_gemm_1p6_fx",
     "tl_ternary_gemm_gs",
     "tl_ternary_gemm_which",
+    "tl_init",
     "tl_probe_copy",
     "tl_probe_read",
 )
@@ -86,6 +87,8 @@ def _load():
     L.tl_ternary_gemm_gs.restype = ci
     L.tl_ternary_gemm_which.argtypes = [i64, i64, i64]
     L.tl_ternary_gemm_which.restype = ci
+    L.tl_init.argtypes = []
+    L.tl_init.restype = ci
     L.tl_probe_copy.argtypes = [vp, vp, sz, vp]
     L.tl_probe_copy.restype = ci
     L.tl_probe_read.argtypes = [vp, sz, vp, vp]
@@ -238,6 +241,10 @@ def tl_ternary_gemm_1p6(x, Wpacked, gamma_fp16_bits, y, M, N, K, stream=None):
 def tl_ternary_gemm_1p6_fx(x, Wpacked, gamma_fp16_bits, y, M, N, K, stream=None):
     _check(_lib.tl_ternary_gemm_1p6_fx(_ptr(x), _ptr(Wpacked), gamma_fp16_bits, _ptr(y), M, N, K,
                                        _stream(stream)), "tl_ternary_gemm_1p6_fx")
+
+
+def tl_init():
+    _check(_lib.tl_init(), "tl_init")
 
 
 def tl_ternary_gemm_which(M, N, K):

@@ -225,6 +225,13 @@ tl_status tl_ternary_gemm_gs(const void* x, const void* Wpacked, const void* sca
     return tl::from_hip(tl::launch_gemm_generic_gs(xh, wp, sh, group, yh, M, N, K, s));
 }
 
+tl_status tl_init(void)
+{
+    hipError_t e = tl::gemv_init();
+    if (e == hipSuccess) e = tl::gemv3_init();
+    return tl::from_hip(e);
+}
+
 tl_status tl_probe_copy(void* dst, const void* src, size_t bytes, void* stream)
 {
     if (!dst || !src) return TL_ERR_NULL;

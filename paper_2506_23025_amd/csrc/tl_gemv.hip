@@ -1060,6 +1060,27 @@ extern "C" void tl_dev_stream_t(int t) { g_policy.t_stream = t; }
 extern "C" void tl_dev_start_up(double v) { g_policy.start_up_per_row = v; }
 #endif
 
+// Raises the dynamic-LDS limit of every kernel instance of this file on the current device (the
+// launchers do it on first use otherwise).
+hipError_t gemv_init()
+{
+    const int stream_lds = 8 * kWaveLds + kStreamMaxRun * 1024;
+    auto raise = [](KernelFn fn, int bytes) {
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    };
+    for (int T = 1; T <= kTMax; ++T)
+        for (int multi = 0; multi < 2; ++multi) {
+            hipError_t e = raise(pick_kernel(T, multi != 0), kMaxLds);
+            for (int passes = 0; passes < 2 && e == hipSuccess; ++passes) {
+                e = raise(pick_stream(T, multi != 0, passes != 0, 1), stream_lds);
+                if (e == hipSuccess && T <= 2) e = raise(pick_stream(T, multi != 0, passes != 0, 2), stream_lds);
+                if (e == hipSuccess && T <= 3) e = raise(pick_stream_gs(T, passes != 0), stream_lds);
+            }
+            if (e != hipSuccess) return e;
+        }
+    return hipSuccess;
+}
+
 bool gemv_supports(int64_t M, int64_t N, int64_t K)
 {
     return M >= 1 && N >= 1 && K >= 64 && (K % 64) == 0 && K <= (int64_t(1) << 24) &&

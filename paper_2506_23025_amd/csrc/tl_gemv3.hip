@@ -325,6 +325,17 @@ Kernel3Fn pick3(int T)
 
 }  // namespace
 
+hipError_t gemv3_init()
+{
+    for (int T = 1; T <= kT3Max; ++T) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(pick3(T)),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                 kNW3Max * kWave3Lds + kLutBytes);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
 bool gemv3_supports(int64_t M, int64_t N, int64_t K)
 {
     return M >= 1 && N >= 1 && K >= 8 && (K % 8) == 0 && K <= (int64_t(1) << 24) &&

@@ -81,6 +81,10 @@ bool mfma_supports(int64_t M, int64_t N, int64_t K);
 hipError_t launch_mfma(const __half* x, const uint32_t* Wp, float gamma, __half* y,
                        int64_t M, int64_t N, int64_t K, hipStream_t s);
 
+// Prepare every kernel instance on the current device (dynamic-LDS limits); idempotent.
+hipError_t gemv_init();
+hipError_t gemv3_init();
+
 // fp16 bits -> float on the host (exact).
 float half_bits_to_float(uint16_t h);
 

@@ -585,3 +585,11 @@ def test_probe_kernels_run_and_leave_memory_alone():
     torch.cuda.synchronize()
     assert torch.equal(dst, src)
     assert sink.tolist() == [7, 7, 7, 7]          # the fold of 0..n-1 is not the value that triggers the store
+
+
+def test_init_is_idempotent_and_calls_work_after_it():
+    tl.tl_init()
+    tl.tl_init()
+    x, W, g = si.layer(31337, 3, 272, 4096)
+    Wp = tl.tl_pack_2bit(W)
+    assert_close(run_gemm(x, Wp, g, 272, 4096), oracle.gemm_packed2(x, Wp, g, 4096), x, g, "after tl_init")
