@@ -142,6 +142,9 @@ tl_status tl_unpack_dev(tl_format fmt, const void* packed, int64_t N, int64_t K,
  *   Wpacked device, TL_FMT_2BIT layout, 16-byte aligned
  *   gamma_fp16_bits  the per-matrix scale as raw IEEE binary16 bits
  *   y       device, fp16 [M][N] row-major, 16-byte aligned; fully overwritten
+ * Activations are expected to be finite.  A NaN in row m of x makes row m of y NaN (no other
+ * row); an infinity in row m makes that row NaN where the exact result would be +-infinity,
+ * because the fast kernels compute sum (w + 1) x - sum x (Sec. 3.1 stores w + 1).
  * Any M, N, K >= 1 is accepted; the library picks the kernel from the shape
  * (small M: weight-streaming kernel; large M: LDS-tiled MFMA kernel; shapes the
  * fast kernels cannot take: the generic kernel).  Results are deterministic:

@@ -593,3 +593,20 @@ def test_init_is_idempotent_and_calls_work_after_it():
     x, W, g = si.layer(31337, 3, 272, 4096)
     Wp = tl.tl_pack_2bit(W)
     assert_close(run_gemm(x, Wp, g, 272, 4096), oracle.gemm_packed2(x, Wp, g, 4096), x, g, "after tl_init")
+
+
+def test_non_finite_activations_stay_in_their_row():
+    # a NaN and an infinity in two rows of x: those rows of y are non-finite, every other row is
+    # exactly what it is without them
+    M, N, K = 5, 272, 4096
+    x, W, g = si.layer(4242, M, N, K)
+    Wp = tl.tl_pack_2bit(W)
+    clean = run_gemm(x, Wp, g, N, K)
+    bad = x.copy()
+    bad[1, 100] = np.float16(np.nan)
+    bad[3, 2000] = np.float16(np.inf)
+    y = run_gemm(bad, Wp, g, N, K)
+    for m in (0, 2, 4):
+        assert np.array_equal(y[m].view(np.uint16), clean[m].view(np.uint16))
+    assert not np.isfinite(y[1].astype(np.float32)).any()
+    assert not np.isfinite(y[3].astype(np.float32)).any()
