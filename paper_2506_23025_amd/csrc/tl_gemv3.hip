@@ -24,6 +24,8 @@
 //    conflicts) and the single item per workgroup keep it behind the 2-bit kernel.
 #include "tl_internal.hpp"
 
+#include <type_traits>
+
 namespace tl {
 
 namespace {
@@ -75,6 +77,107 @@ __device__ __forceinline__ uint32_t byte_times_8(uint32_t w)
     if constexpr (B == 2) asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_2" : "=v"(r) : "v"(three), "v"(w));
     if constexpr (B == 3) asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_3" : "=v"(r) : "v"(three), "v"(w));
     return r;
+}
+
+// byte -> digits table.  Plain form: base-3 digits, least significant first (bytes 243..255
+// never occur; they decode like byte - 243).  Fixed-point form: App. F, Alg. 1, run here once
+// per byte value -- multiply by 3, the digit is what spills over the byte, most significant
+// digit first; all 256 bytes decode.
+__device__ __forceinline__ void fill_table(u32x2* lut, bool fx)
+{
+    for (unsigned b = threadIdx.x; b < 256; b += blockDim.x) {
+        unsigned c[5];
+        if (fx) {
+            unsigned v = b;
+#pragma unroll
+            for (int i = 0; i < 5; ++i) { const unsigned t = v * 3u; c[i] = t >> 8; v = t & 0xFFu; }
+        } else {
+            unsigned v = b >= 243 ? b - 243 : b;
+#pragma unroll
+            for (int i = 0; i < 5; ++i) { c[i] = v % 3u; v /= 3u; }
+        }
+        lut[b] = u32x2{(c[0] << 4) | (c[2] << 8) | (c[3] << 20), (c[1] << 4) | (c[4] << 20)};
+    }
+}
+
+// The activations as MFMA B operands, grouped as the tile arithmetic uses them.  With
+// p(a, b) = (x[a], x[b]) and k = 5 (4d + j) the first weight of byte 4d + j of the lane's 16 bytes of
+// half h:  bop[h][d][0] = p(k0, k0+3), p(k0+1, k0+4) for bytes j = 0, 1;  bop[h][d][1] the same for
+// j = 2, 3;  bop[h][d][2] = (x[k+2], 0) for j = 0..3.  The lane's 16 bytes of half h cover 80
+// consecutive weights, i.e. 160 consecutive bytes of the staged row: ten 16-byte reads, then one
+// byte permute per pair.
+__device__ __forceinline__ void build_operands(const unsigned char* row, int mg, u32x4 (&bop)[2][4][3])
+{
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        u32x4 xv[10];
+#pragma unroll
+        for (int i = 0; i < 10; ++i)
+            xv[i] = *reinterpret_cast<const u32x4*>(row + (4 * h + mg) * 160 + 16 * i);
+        auto pair = [&](int a, int b) {                    // (x[a], x[b]) of the 80; b < 0: (x[a], 0)
+            const uint32_t lo = xv[a >> 3][(a >> 1) & 3];
+            const uint32_t hi = b < 0 ? 0u : xv[b >> 3][(b >> 1) & 3];
+            const uint32_t s0 = (a & 1) ? 0x0302u : 0x0100u;
+            const uint32_t s1 = b < 0 ? 0x0c0cu : ((b & 1) ? 0x0706u : 0x0504u);
+            return __builtin_amdgcn_perm(hi, lo, (s1 << 16) | s0);
+        };
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const int k = 20 * d;                           // first weight of byte 4d
+            bop[h][d][0] = u32x4{pair(k, k + 3), pair(k + 1, k + 4), pair(k + 5, k + 8), pair(k + 6, k + 9)};
+            bop[h][d][1] = u32x4{pair(k + 10, k + 13), pair(k + 11, k + 14), pair(k + 15, k + 18), pair(k + 16, k + 19)};
+            bop[h][d][2] = u32x4{pair(k + 2, -1), pair(k + 7, -1), pair(k + 12, -1), pair(k + 17, -1)};
+        }
+    }
+}
+
+// -2^-20 sum_k x over the slice, in accumulator layout (constant 16-row operand)
+__device__ __forceinline__ f32x4 seed_from(const u32x4 (&bop)[2][4][3])
+{
+    f32x4 nsx = f32x4{0.f, 0.f, 0.f, 0.f};
+    const uint32_t c = 0x80108010u;
+    const u32x4 a = u32x4{c, c, c, c};
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int d = 0; d < 4; ++d)
+#pragma unroll
+            for (int q = 0; q < 3; ++q)
+                nsx = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(a), as_h8(bop[h][d][q]), nsx, 0, 0, 0);
+    return nsx;
+}
+
+// sum_k x_k w_k of one tile slice that lies in MFMA order at reg_t: all sixteen look-ups of a
+// half first, so that their latency runs under the arithmetic of the ones before
+template <class LutAt>
+__device__ __forceinline__ f32x4 tile_sum(const unsigned char* reg_t, uint32_t wr_off0, uint32_t wr_off1,
+                                          const u32x4 (&bop)[2][4][3], f32x4 nsx, LutAt lut_at)
+{
+    f32x4 acc[3] = {nsx, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const u32x4 wv = *reinterpret_cast<const u32x4*>(reg_t + (h ? wr_off1 : wr_off0));
+        u32x2 e[4][4];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            e[d][0] = lut_at(byte_times_8<0>(wv[d]));
+            e[d][1] = lut_at(byte_times_8<1>(wv[d]));
+            e[d][2] = lut_at(byte_times_8<2>(wv[d]));
+            e[d][3] = lut_at(byte_times_8<3>(wv[d]));
+        }
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            // bytes 0,1 and 2,3 of the dword: the two table words of a byte pair are an operand
+            // as they stand once c2 is masked out of the first word of each
+            const u32x4 a2 = u32x4{e[d][0][0] & 0x300u, e[d][1][0] & 0x300u, e[d][2][0] & 0x300u, e[d][3][0] & 0x300u};
+            const u32x4 a01 = u32x4{e[d][0][0] & 0x00300030u, e[d][0][1], e[d][1][0] & 0x00300030u, e[d][1][1]};
+            const u32x4 a23 = u32x4{e[d][2][0] & 0x00300030u, e[d][2][1], e[d][3][0] & 0x00300030u, e[d][3][1]};
+            acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(a01), as_h8(bop[h][d][0]), acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(a23), as_h8(bop[h][d][1]), acc[1], 0, 0, 0);
+            acc[2] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(a2), as_h8(bop[h][d][2]), acc[2], 0, 0, 0);
+        }
+    }
+    return (acc[0] + acc[1]) * 1048576.f + acc[2] * 65536.f;
 }
 
 template <int T>
@@ -166,79 +269,16 @@ gemv3_kernel(Gemv3Params p)
         for (int t = 0; t < T; ++t) issue_w(t, slice);
     }
 
-    // byte -> digits table.  Plain form: base-3 digits, least significant first (bytes
-    // 243..255 never occur; they decode like byte - 243).  Fixed-point form: App. F, Alg. 1,
-    // run here once per byte value -- multiply by 3, the digit is what spills over the byte,
-    // most significant digit first; all 256 bytes decode.
-    for (unsigned b = threadIdx.x; b < 256; b += blockDim.x) {
-        unsigned c[5];
-        if (p.fx) {
-            unsigned v = b;
-#pragma unroll
-            for (int i = 0; i < 5; ++i) { const unsigned t = v * 3u; c[i] = t >> 8; v = t & 0xFFu; }
-        } else {
-            unsigned v = b >= 243 ? b - 243 : b;
-#pragma unroll
-            for (int i = 0; i < 5; ++i) { c[i] = v % 3u; v /= 3u; }
-        }
-        lut[b] = u32x2{(c[0] << 4) | (c[2] << 8) | (c[3] << 20), (c[1] << 4) | (c[4] << 20)};
-    }
+    fill_table(lut, p.fx != 0);
     // (the barrier that makes the table visible comes after the operands are built: they need
     // the wave's own activation transfers only)
     if (wave < slices) __builtin_amdgcn_s_waitcnt(vmcnt_imm3(2 * T));   // LDS-DMA is not tracked by the compiler
 
     for (; slice < slices; slice += NW) {
         const bool more = (slice + NW) < slices;
-        // breg[h][d][cls][j]: activation pair for byte 4d + j of the lane's 16 bytes (half h):
-        // cls 0 -> (x[k], x[k+3]), 1 -> (x[k+1], x[k+4]), 2 -> (x[k+2], 0), k = 5 * byte index
-        uint32_t breg[2][4][3][4];
-        {
-            // The lane's 16 bytes of half h cover 80 consecutive weights, i.e. 160 consecutive
-            // bytes of the staged row: ten 16-byte reads, then one byte permute per pair.
-            const unsigned char* row = my_lds + xrow * kXRow;
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                u32x4 xv[10];
-#pragma unroll
-                for (int i = 0; i < 10; ++i)
-                    xv[i] = *reinterpret_cast<const u32x4*>(row + (4 * h + mg) * 160 + 16 * i);
-                auto pair = [&](int a, int b) {            // (x[a], x[b]) of the 80; b < 0: (x[a], 0)
-                    const uint32_t lo = xv[a >> 3][(a >> 1) & 3];
-                    const uint32_t hi = b < 0 ? 0u : xv[b >> 3][(b >> 1) & 3];
-                    const uint32_t s0 = (a & 1) ? 0x0302u : 0x0100u;
-                    const uint32_t s1 = b < 0 ? 0x0c0cu : ((b & 1) ? 0x0706u : 0x0504u);
-                    return __builtin_amdgcn_perm(hi, lo, (s1 << 16) | s0);
-                };
-#pragma unroll
-                for (int d = 0; d < 4; ++d)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const int k0 = 5 * (4 * d + j);     // first weight of the byte
-                        breg[h][d][0][j] = pair(k0, k0 + 3);
-                        breg[h][d][1][j] = pair(k0 + 1, k0 + 4);
-                        breg[h][d][2][j] = pair(k0 + 2, -1);
-                    }
-            }
-        }
-        // nsx = -2^-20 sum_k x over the slice, in accumulator layout (constant 16-row operand)
-        f32x4 nsx = f32x4{0.f, 0.f, 0.f, 0.f};
-        {
-            const uint32_t c = 0x80108010u;
-            const u32x4 a = u32x4{c, c, c, c};
-#pragma unroll
-            for (int h = 0; h < 2; ++h)
-#pragma unroll
-                for (int d = 0; d < 4; ++d) {
-                    // the same groups of four as the tile loop uses, so that each group can live
-                    // in consecutive registers
-                    const u32x4 b01 = u32x4{breg[h][d][0][0], breg[h][d][1][0], breg[h][d][0][1], breg[h][d][1][1]};
-                    const u32x4 b23 = u32x4{breg[h][d][0][2], breg[h][d][1][2], breg[h][d][0][3], breg[h][d][1][3]};
-                    const u32x4 b2 = u32x4{breg[h][d][2][0], breg[h][d][2][1], breg[h][d][2][2], breg[h][d][2][3]};
-                    nsx = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(a), as_h8(b01), nsx, 0, 0, 0);
-                    nsx = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(a), as_h8(b23), nsx, 0, 0, 0);
-                    nsx = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(a), as_h8(b2), nsx, 0, 0, 0);
-                }
-        }
+        u32x4 bop[2][4][3];
+        build_operands(my_lds + xrow * kXRow, mg, bop);
+        const f32x4 nsx = seed_from(bop);
         if (slice == wave) lds_barrier3();                 // first pass (every wave runs it): the table is complete
 #pragma unroll
         for (int t = 0; t < T; ++t) {
@@ -246,38 +286,7 @@ gemv3_kernel(Gemv3Params p)
             *reinterpret_cast<u32x4*>(reg_t + ww_off) = wreg[t][0];
             *reinterpret_cast<u32x4*>(reg_t + 1024 + ww_off) = wreg[t][1];
             if (more) issue_w(t, slice + NW);
-            if (grp + t * groups < tiles) {
-                f32x4 acc[3] = {nsx, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const u32x4 wv = *reinterpret_cast<const u32x4*>(reg_t + (h ? wr_off1 : wr_off0));
-                    // all sixteen look-ups of the half first, so that their latency runs under
-                    // the arithmetic of the ones before
-                    u32x2 e[4][4];
-#pragma unroll
-                    for (int d = 0; d < 4; ++d) {
-                        e[d][0] = lut_at(byte_times_8<0>(wv[d]));
-                        e[d][1] = lut_at(byte_times_8<1>(wv[d]));
-                        e[d][2] = lut_at(byte_times_8<2>(wv[d]));
-                        e[d][3] = lut_at(byte_times_8<3>(wv[d]));
-                    }
-#pragma unroll
-                    for (int d = 0; d < 4; ++d) {
-                        // bytes 0,1 and 2,3 of the dword: the two table words of a byte pair are an
-                        // operand as they stand once c2 is masked out of the first word of each
-                        const u32x4 a2 = u32x4{e[d][0][0] & 0x300u, e[d][1][0] & 0x300u, e[d][2][0] & 0x300u, e[d][3][0] & 0x300u};
-                        const u32x4 a01 = u32x4{e[d][0][0] & 0x00300030u, e[d][0][1], e[d][1][0] & 0x00300030u, e[d][1][1]};
-                        const u32x4 a23 = u32x4{e[d][2][0] & 0x00300030u, e[d][2][1], e[d][3][0] & 0x00300030u, e[d][3][1]};
-                        const u32x4 b01 = u32x4{breg[h][d][0][0], breg[h][d][1][0], breg[h][d][0][1], breg[h][d][1][1]};
-                        const u32x4 b23 = u32x4{breg[h][d][0][2], breg[h][d][1][2], breg[h][d][0][3], breg[h][d][1][3]};
-                        const u32x4 b2 = u32x4{breg[h][d][2][0], breg[h][d][2][1], breg[h][d][2][2], breg[h][d][2][3]};
-                        acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(a01), as_h8(b01), acc[0], 0, 0, 0);
-                        acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(a23), as_h8(b23), acc[1], 0, 0, 0);
-                        acc[2] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(a2), as_h8(b2), acc[2], 0, 0, 0);
-                    }
-                }
-                part_acc[t] += (acc[0] + acc[1]) * 1048576.f + acc[2] * 65536.f;
-            }
+            if (grp + t * groups < tiles) part_acc[t] += tile_sum(reg_t, wr_off0, wr_off1, bop, nsx, lut_at);
         }
         if (more) {
             issue_x(slice + NW);
@@ -311,6 +320,158 @@ gemv3_kernel(Gemv3Params p)
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Stream form, for K of at most 7 slices (K <= 4480): wave w owns slice w for the whole kernel,
+// so activations are staged and turned into operands once; a workgroup walks a run of
+// consecutive tiles, T at a time ("item"), with the next item's weights requested as soon as
+// a tile's registers are free, two alternating sets of partial sums and one LDS-only barrier
+// per item -- the organisation of the 2-bit stream kernel (tl_gemv.hip) with this file's
+// decode.  Params::groups workgroups; workgroup g takes tiles [g per + min(g, extra), ...).
+template <int T>
+__global__ void __launch_bounds__(512)
+gemv3_stream_kernel(Gemv3Params p)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int NW = blockDim.x >> 6;
+    u32x2* const lut = reinterpret_cast<u32x2*>(lds_raw);
+    unsigned char* const my_lds = lds_raw + kLutBytes + wave * kWave3Lds;
+    auto lut_at = [](uint32_t off) { return *(const __attribute__((address_space(3))) u32x2*)(uintptr_t(off)); };
+
+    const int m0 = blockIdx.y * 16;
+    const int Mrem = (p.M - m0 < 16) ? (p.M - m0) : 16;
+    int MR = 1;
+    while (MR < Mrem) MR *= 2;
+    const int K = p.K, N = p.N;
+    const uint32_t stride = uint32_t(p.stride);
+    const int chunks = p.stride >> 4;
+    const int tiles = p.tiles;
+    const int per = tiles / p.groups, extra = tiles % p.groups;
+    const int g = blockIdx.x;
+    const int tile0 = g * per + (g < extra ? g : extra);
+    const int tile_end = tile0 + per + (g < extra ? 1 : 0);
+    const int n_items = (tile_end - tile0 + T - 1) / T;
+
+    const int lr = lane >> 3, lc = lane & 7;
+    const int mi = lane & 15, mg = lane >> 4;
+    const int xrow = mi & (MR - 1);
+    const uint32_t ww_off = uint32_t(lr) * 128u + (uint32_t(lc ^ lr) << 4);
+    const uint32_t wr_off0 = uint32_t(mi) * 128u + (uint32_t((mg) ^ (mi & 7)) << 4);
+    const uint32_t wr_off1 = uint32_t(mi) * 128u + (uint32_t((4 + mg) ^ (mi & 7)) << 4);
+
+    const unsigned char* const Wb = p.W;
+    const unsigned char* const xb = reinterpret_cast<const unsigned char*>(p.x + size_t(m0) * K);
+    const bool active = wave < p.slices;
+    uint32_t col_off;
+    {
+        int chunk = wave * 8 + lc;
+        if (chunk >= chunks) chunk = 0;                    // past the row: meets zero activations
+        col_off = uint32_t(chunk) * 16u;
+    }
+    const bool ragged_n = (N & 15) != 0;
+    typedef const __attribute__((address_space(1))) u32x4* gptr;
+
+    u32x4 wreg[T][2];
+    auto issue_w = [&](int first, int t) {
+        int tile = first + t;
+        if (tile >= tile_end) tile = tile_end - 1;         // past the run: its last tile again, never stored
+        const unsigned char* tb = Wb + size_t(tile) * 16u * stride;
+        const int last = (ragged_n && tile == tiles - 1) ? N - 1 - tile * 16 : 15;
+        const uint32_t off0 = uint32_t(lr < last ? lr : last) * stride + col_off;
+        const uint32_t off1 = uint32_t(lr + 8 < last ? lr + 8 : last) * stride + col_off;
+        wreg[t][0] = __builtin_nontemporal_load((gptr)(tb + off0));
+        wreg[t][1] = __builtin_nontemporal_load((gptr)(tb + off1));
+    };
+
+    if (active) {
+        // activation rows of this wave's slice by LDS-DMA: 640 halves = 80 pieces of 16 bytes per
+        // row (pieces 0..63, then 64..79); pieces past K are stored as zeros; rows past Mrem stay
+        // unwritten (an MFMA column depends on its own column of B alone)
+        for (int r = 0; r < Mrem; ++r) {
+            const unsigned char* src = xb + size_t(r) * K * 2;
+            unsigned char* dst = my_lds + r * kXRow;
+#pragma unroll
+            for (int part = 0; part < 2; ++part) {
+                const int piece = part * 64 + lane;
+                const int kx = wave * kSlice3 + piece * 8;
+                if (piece < 80) {
+                    if (kx < K) {
+                        __builtin_amdgcn_global_load_lds(
+                            (const __attribute__((address_space(1))) void*)(src + uint32_t(kx) * 2u),
+                            (__attribute__((address_space(3))) void*)(dst + part * 1024), 16, 0, 0);
+                    } else {
+                        *reinterpret_cast<u32x4*>(dst + piece * 16) = u32x4{0u, 0u, 0u, 0u};
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < T; ++t) issue_w(tile0, t);
+    }
+    fill_table(lut, p.fx != 0);
+    if (active) __builtin_amdgcn_s_waitcnt(vmcnt_imm3(2 * T));   // the activations are in; the weights stay in flight
+
+    u32x4 bop[2][4][3];
+    f32x4 nsx = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (active) {
+        build_operands(my_lds + xrow * kXRow, mg, bop);
+        nsx = seed_from(bop);
+    }
+    lds_barrier3();                                        // the table is complete
+
+    auto item = [&](auto refill_tag, int first, int parity) {
+        constexpr bool REFILL = decltype(refill_tag)::value;
+        f32x4 part[T];
+#pragma unroll
+        for (int t = 0; t < T; ++t) part[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (active) {
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                unsigned char* const reg_t = my_lds + (t & 1) * 2048;
+                *reinterpret_cast<u32x4*>(reg_t + ww_off) = wreg[t][0];
+                *reinterpret_cast<u32x4*>(reg_t + 1024 + ww_off) = wreg[t][1];
+                if constexpr (REFILL) issue_w(first + T, t);
+                if (REFILL || first + t < tile_end)
+                    part[t] = tile_sum(reg_t, wr_off0, wr_off1, bop, nsx, lut_at);
+            }
+        }
+        unsigned char* const red = my_lds + 4096 + parity * (T * 1024);
+#pragma unroll
+        for (int t = 0; t < T; ++t) reinterpret_cast<f32x4*>(red + t * 1024)[lane] = part[t];
+        lds_barrier3();
+        if (const int o = threadIdx.x; o < T * 64) {       // T <= waves: one output quad per thread
+            const int t = o >> 6, l = o & 63;
+            const int tile = first + t;
+            f32x4 v[8];
+#pragma unroll
+            for (int w = 0; w < 8; ++w)
+                v[w] = (w < NW) ? reinterpret_cast<const f32x4*>(lds_raw + kLutBytes + w * kWave3Lds + 4096 + parity * (T * 1024) + t * 1024)[l]
+                                : f32x4{0.f, 0.f, 0.f, 0.f};
+            const f32x4 s = ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
+            const int n = tile * 16 + 4 * (l >> 4);
+            if (tile < tile_end && (l & 15) < Mrem) {
+                typedef __attribute__((address_space(1))) __half* gh_ptr;
+                gh_ptr dst = (gh_ptr)(p.y + size_t(m0 + (l & 15)) * N + n);
+                const float gamma = p.gamma;
+                if (n + 3 < N && (N & 3) == 0) {           // four consecutive n: one 8-byte store
+                    const f16x2 lo = {(_Float16)(gamma * s[0]), (_Float16)(gamma * s[1])};
+                    const f16x2 hi = {(_Float16)(gamma * s[2]), (_Float16)(gamma * s[3])};
+                    *(__attribute__((address_space(1))) u32x2*)dst =
+                        u32x2{__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        if (n + r < N) *(__attribute__((address_space(1))) _Float16*)(dst + r) = (_Float16)(gamma * s[r]);
+                }
+            }
+        }
+    };
+    int i = 0;
+    for (; i + 1 < n_items; ++i) item(std::true_type{}, tile0 + i * T, i & 1);
+    item(std::false_type{}, tile0 + i * T, i & 1);
+}
+
 using Kernel3Fn = void (*)(Gemv3Params);
 
 Kernel3Fn pick3(int T)
@@ -323,14 +484,26 @@ Kernel3Fn pick3(int T)
     }
 }
 
+Kernel3Fn pick3_stream(int T)
+{
+    switch (T) {
+        case 1: return gemv3_stream_kernel<1>;
+        case 2: return gemv3_stream_kernel<2>;
+        default: return gemv3_stream_kernel<3>;
+    }
+}
+
 }  // namespace
 
 hipError_t gemv3_init()
 {
     for (int T = 1; T <= kT3Max; ++T) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(pick3(T)),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                 kNW3Max * kWave3Lds + kLutBytes);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(pick3(T)),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           kNW3Max * kWave3Lds + kLutBytes);
+        if (e == hipSuccess && T <= 3)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(pick3_stream(T)),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kNW3Max * kWave3Lds + kLutBytes);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
@@ -354,19 +527,36 @@ hipError_t launch_gemv3(const __half* x, const uint8_t* Wp, int64_t stride, floa
     p.slices = int((stride + 127) / 128);
     const int NW = p.slices < kNW3Max ? p.slices : kNW3Max;
     int groups = p.tiles < 256 ? p.tiles : 256;
+    static bool lds_raised[2][kT3Max + 1];
+    auto raise = [&](Kernel3Fn fn, int form, int T) -> hipError_t {
+        if (lds_raised[form][T]) return hipSuccess;
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                 kNW3Max * kWave3Lds + kLutBytes);
+        if (e == hipSuccess) lds_raised[form][T] = true;
+        return e;
+    };
+    dim3 grid(groups, unsigned((M + 15) / 16));
+    if (p.slices <= kNW3Max) {
+        // K in one pass: the stream form.  Tiles per item as for the 2-bit stream kernel: runs
+        // of up to 3 tiles are one item, a run of 4 goes as 2 + 2, longer runs in items of 3.
+        const int run = (p.tiles + groups - 1) / groups;
+        int T = run <= 3 ? run : (run == 4 ? 2 : 3);
+        if (T > NW) T = NW;                                // the epilogue gives every thread at most one output quad
+        p.groups = groups;
+        Kernel3Fn fn = pick3_stream(T);
+        const hipError_t e = raise(fn, 1, T);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(fn, grid, dim3(NW * 64), size_t(NW) * kWave3Lds + kLutBytes, s, p);
+        return hipGetLastError();
+    }
     int T = (p.tiles + groups - 1) / groups;
     if (T > kT3Max) { T = kT3Max; groups = (p.tiles + T - 1) / T; }
     p.groups = groups;
+    grid.x = unsigned(groups);
     Kernel3Fn fn = pick3(T);
-    static bool lds_raised[kT3Max + 1];
-    if (!lds_raised[T]) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           kNW3Max * kWave3Lds + kLutBytes);
-        if (e != hipSuccess) return e;
-        lds_raised[T] = true;
-    }
-    dim3 grid(groups, unsigned((M + 15) / 16));
+    const hipError_t e = raise(fn, 0, T);
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(fn, grid, dim3(NW * 64), size_t(NW) * kWave3Lds + kLutBytes, s, p);
     return hipGetLastError();
 }
