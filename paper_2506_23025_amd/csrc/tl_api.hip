@@ -31,7 +31,7 @@ inline bool dims_ok(int64_t M, int64_t N, int64_t K)
 inline tl_status from_hip(hipError_t e) { return e == hipSuccess ? TL_OK : TL_ERR_HIP; }
 
 // M at and below which the 1.6-bit weight-streaming kernel is used.
-constexpr int64_t kGemvMaxM = 128;
+constexpr int64_t kGemvMaxM = 4096;
 
 // Small-M kernel (blocks of 16 or 32 activation rows that each stream W) or LDS-tiled MFMA
 // kernel, when both can run the shape: whichever the cost models below make cheaper.  They are

@@ -20,8 +20,11 @@
 //  * The paper expects the 1.6-bit form to cost more arithmetic per weight than the 2-bit
 //    form (Sec. 3.3 results, "Limitations"); here it is 0.7 VALU operations and 0.2 LDS
 //    look-ups per weight against 0.7 VALU operations for the 2-bit form, for 0.81 of the
-//    bytes; the look-ups (random addresses: about half of their LDS cycles are bank
-//    conflicts) and the single item per workgroup keep it behind the 2-bit kernel.
+//    bytes, and 24 MFMAs per 640 x 16 weights against 16 per 512 x 16: per weight the SIMD time
+//    is the same, per byte of packed weights it is 1.25 times the 2-bit kernel's.
+//  * Two forms.  gemv3_stream_kernel (K in one pass of at most 7 slices, K <= 4480): a wave
+//    keeps its slice, a workgroup walks a run of tiles in items with the next item's weights in
+//    flight.  gemv3_kernel (longer K): waves loop over slices, one item per workgroup.
 #include "tl_internal.hpp"
 
 #include <type_traits>
@@ -538,6 +541,13 @@ hipError_t launch_gemv3(const __half* x, const uint8_t* Wp, int64_t stride, floa
     };
     dim3 grid(groups, unsigned((M + 15) / 16));
     if (p.slices <= kNW3Max) {
+        // every block of 16 activation rows is a set of workgroups of its own (blockIdx.y); they
+        // share the CUs, 256 workgroups in all, so that the launch is one round with longer runs
+        const int mblocks = int((M + 15) / 16);
+        int share = 256 / mblocks;
+        if (share < 1) share = 1;
+        if (groups > share) groups = share;
+        grid.x = unsigned(groups);
         // K in one pass: the stream form.  Tiles per item as for the 2-bit stream kernel: runs
         // of up to 3 tiles are one item, a run of 4 goes as 2 + 2, longer runs in items of 3.
         const int run = (p.tiles + groups - 1) / groups;

@@ -394,7 +394,8 @@ def test_grouped_empty_and_errors():
 # ---------------------------------------------------------------- 1.6-bit small-M kernel
 
 GEMV3_SHAPES = [(1, 16, 8), (1, 1, 640), (4, 272, 640), (3, 17, 1280), (16, 100, 648), (7, 33, 4096),
-                (16, 4099, 4096), (3, 40, 11008), (33, 130, 2048), (2, 512, 8192), (64, 48, 4096)]
+                (16, 4099, 4096), (3, 40, 11008), (33, 130, 2048), (2, 512, 8192), (64, 48, 4096),
+                (300, 272, 4096), (1000, 64, 1280), (5000, 16, 640), (130, 4100, 4480), (70, 100, 4488)]
 
 
 @pytest.mark.parametrize("M,N,K", GEMV3_SHAPES)
@@ -433,7 +434,7 @@ FX_SHAPES = [(1, 16, 8), (4, 272, 640), (3, 17, 1280), (16, 100, 648), (7, 33, 4
 
 @pytest.mark.parametrize("M,N,K", FX_SHAPES)
 def test_gemm_1p6_fx_matches_oracle(M, N, K):
-    # small-M kernel (table filled by Alg. 1) where K % 8 == 0 and M <= 128, generic kernel otherwise
+    # small-M kernel (table filled by Alg. 1) where K % 8 == 0 and M <= 4096, generic kernel otherwise
     import torch
     x, W, g = si.layer(9500 + M + N + K, M, N, K)
     Wp = tl.tl_pack_1p6bit_fx(W)
