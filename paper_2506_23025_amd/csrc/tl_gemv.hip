@@ -875,7 +875,10 @@ hipError_t launch_stream(GemvBatch& b, int max_slices, int nb, hipStream_t s, bo
         total_tiles += b.job[j].tiles;
         multi_pass |= passes(j) > 1;
     }
-    const int G = total_tiles < pol.stream_groups ? int(total_tiles) : pol.stream_groups;
+    // One workgroup of 8 waves per CU; with shorter K (fewer waves per workgroup) as many more
+    // workgroups, so that a CU still runs 8 waves (K = 1024: 1024 workgroups of 2 waves).
+    const int64_t g_max = int64_t(pol.stream_groups) * (kStreamWaves / NW);
+    const int G = total_tiles < g_max ? int(total_tiles) : int(g_max);
     // Time of a workgroup of job j with w groups, in tile units: passes x (run + start-up).  The
     // start-up of a pass is fetching the activation slice (1 KB per row and wave through the
     // same address path as the weights) and building the operands: measured about 0.15 tiles per

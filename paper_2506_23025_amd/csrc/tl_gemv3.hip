@@ -543,10 +543,11 @@ hipError_t launch_gemv3(const __half* x, const uint8_t* Wp, int64_t stride, floa
     if (p.slices <= kNW3Max) {
         // every block of 16 activation rows is a set of workgroups of its own (blockIdx.y); they
         // share the CUs, 256 workgroups in all, so that the launch is one round with longer runs
+        // (with shorter K, fewer waves per workgroup and as many more workgroups)
         const int mblocks = int((M + 15) / 16);
-        int share = 256 / mblocks;
+        int share = 256 * (kNW3Max / NW) / mblocks;
         if (share < 1) share = 1;
-        if (groups > share) groups = share;
+        groups = p.tiles < share ? p.tiles : share;
         grid.x = unsigned(groups);
         // K in one pass: the stream form.  Tiles per item as for the 2-bit stream kernel: runs
         // of up to 3 tiles are one item, a run of 4 goes as 2 + 2, longer runs in items of 3.
