@@ -26,7 +26,7 @@
 //    group of MFMAs per wave whose 16-row operand is a constant, and seeds the accumulator.
 //  * Split-K partial tiles of the NW waves are added in a fixed order through LDS, scaled
 //    by gamma, rounded to fp16 (RNE) and stored.  No atomics: results are deterministic.
-//  * One launch can carry up to 16 independent jobs (a job = one matrix and at most 16, in
+//  * One launch can carry up to 32 independent jobs (a job = one matrix and at most 16, in
 //    one variant 32, activation rows); a workgroup finds its job from its index.
 //  * Two forms.  The stream form (gemv_stream_kernel: K up to 8 slices per pass, the usual
 //    case) gives a wave one slice for the whole kernel and a workgroup a run of consecutive
@@ -45,7 +45,7 @@ namespace {
 constexpr int kTMax = 4;          // tiles per work item
 constexpr int kSliceK = 512;      // K elements a wave owns per pass
 constexpr int kWaveLds = 16384;   // bytes of LDS per wave: 16 activation rows x 1 KB
-constexpr int kMaxJobs = 16;      // jobs per launch
+constexpr int kMaxJobs = 32;      // jobs per launch (the table is 2.2 KB of kernel arguments)
 
 struct GemvJob {                  // 64 bytes, lives in the kernel argument segment
     const __half* x;              // first activation row of this 16-row block
@@ -98,7 +98,7 @@ struct ItemCtx {
     int hpg;
 };
 
-// The job table of a launch, one job per lane (lane & 15), read from the kernel argument
+// The job table of a launch, one job per lane (lanes 0 .. kMaxJobs - 1), read from the kernel argument
 // segment with vector loads: every workgroup needs one entry chosen by its index, and a
 // scalar look-up would be two dependent trips to memory before the first weight is requested.
 struct JobTable {
@@ -110,14 +110,14 @@ __device__ __forceinline__ JobTable load_table(int lane)
 {
     typedef const __attribute__((address_space(4))) unsigned char* kptr;
     kptr ka = (kptr)__builtin_amdgcn_kernarg_segment_ptr();     // GemvBatch is the only argument
-    const int k = lane & 15;
+    const int k = lane & (kMaxJobs - 1);
     JobTable r;
     r.item0 = 0x7fffffff;
 #pragma unroll
     for (int i = 0; i < 16; ++i) r.d[i] = 0u;
-    // only lanes 0..15 load (the entries are read with v_readlane from those lanes): a quarter
+    // only lanes 0 .. kMaxJobs - 1 load (the entries are read with v_readlane from those lanes): half
     // of the addresses for the CU's address path, which all eight waves go through at once
-    if (lane < 16) {
+    if (lane < kMaxJobs) {
         r.item0 = *(const __attribute__((address_space(4))) int*)(ka + offsetof(GemvBatch, item0) + 4 * k);
         const __attribute__((address_space(4))) u32x4* jp =
             (const __attribute__((address_space(4))) u32x4*)(ka + offsetof(GemvBatch, job) + sizeof(GemvJob) * k);
@@ -133,7 +133,7 @@ __device__ __forceinline__ JobTable load_table(int lane)
 // Work item g -> its job (the last one whose first item is <= g) and position in it.
 __device__ __forceinline__ ItemCtx load_item(const JobTable& tb, int g)
 {
-    const unsigned long long m = __builtin_amdgcn_ballot_w64(g >= tb.item0) & 0xFFFFull;
+    const unsigned long long m = __builtin_amdgcn_ballot_w64(g >= tb.item0) & ((1ull << kMaxJobs) - 1);
     const int ji = __builtin_popcountll(m) - 1;
     uint32_t f[16];
 #pragma unroll
@@ -478,7 +478,7 @@ gemv_stream_kernel(GemvBatch b)
     if constexpr (MULTI) {
         const JobTable table = load_table(lane);
         J = load_item(table, int(blockIdx.x));             // idx: position among the job's workgroups
-        const unsigned long long m = __builtin_amdgcn_ballot_w64(int(blockIdx.x) >= table.item0) & 0xFFFFull;
+        const unsigned long long m = __builtin_amdgcn_ballot_w64(int(blockIdx.x) >= table.item0) & ((1ull << kMaxJobs) - 1);
         const int ji = __builtin_popcountll(m) - 1;
         ipg = int(__builtin_amdgcn_readlane(table.d[14], ji));
         plus = int(__builtin_amdgcn_readlane(table.d[15], ji));
