@@ -36,11 +36,13 @@ constexpr int64_t kGemvMaxM = 4096;
 // Small-M kernel (blocks of 16 or 32 activation rows that each stream W) or LDS-tiled MFMA
 // kernel, when both can run the shape: whichever the cost models below make cheaper.  They are
 // fits to measurements (us; W in MB of packed weights):
-//  * small-M, blocks of 32 rows: 4 + blocks x (0.45 + 0.205 W)      (4096 -> 14336: 3.46 us per block);
-//    0.33 W when K needs several passes (11008 -> 4096: 4.1 us per block)
+//  * small-M, blocks of 32 rows, one pass over K: 4 + blocks x (0.31 + 0.2 W)
+//    (4096 -> 14336: 3.2 us per block); several passes: launches of up to 4096 tiles, each
+//    passes x (8.7 + 0.88 x its longest run of tiles per workgroup)
+//    (11008 -> 4096: 16 blocks 68 us, 8 blocks 47 us)
 //  * small-M, blocks of 16 rows: 3.8 + blocks x W x (0.17 while W stays in the L2 caches, 0.21
 //    beyond, 0.264 when K needs several passes), at least 0.5 per block
-//  * MFMA, 128 x 128 tiles (at most one per CU): 3 + K/64 x (0.60 + 0.08 tiles/256)
+//  * MFMA, 128 x 128 tiles (at most one per CU): 4 + K/64 x (0.53 + 0.04 tiles/256)
 //  * MFMA, 128 x 256 tiles: (5 + K/64 x 0.86) x f(tiles/256), f(r) = 1 up to one tile per CU, then
 //    max(r, 0.82 ceil(r)): a round that is not full costs most of a full one
 //    (4096 -> 14336: 336 tiles 98 us, 448 tiles 107 us, 896 tiles 219 us).
@@ -50,8 +52,16 @@ inline bool prefer_small_m(int64_t M, int64_t N, int64_t K)
     const double w_mb = double(N) * double(K) / 4.0e6;
     const int64_t slices = (K + 511) / 512;
     double t_small;
-    if (tl::gemv_two_blocks(M, N, K)) {
-        t_small = 4.0 + double((M + 31) / 32) * (0.45 + (slices > 8 ? 0.33 : 0.205) * w_mb);
+    if (tl::gemv_two_blocks(M, N, K) && slices > 8) {
+        // several passes over K: launches of at most 4096 tiles; a launch costs, per pass, a
+        // start plus its longest run of tiles
+        const int64_t blocks = (M + 31) / 32, tiles = (N + 15) / 16;
+        const int64_t cap = tiles >= 4096 ? 1 : 4096 / tiles;
+        const double passes = double((slices + 7) / 8);
+        auto launch_us = [&](int64_t b) { return passes * (8.7 + 0.88 * double((b * tiles + 255) / 256)); };
+        t_small = double(blocks / cap) * launch_us(cap) + (blocks % cap ? launch_us(blocks % cap) : 0.0);
+    } else if (tl::gemv_two_blocks(M, N, K)) {
+        t_small = 4.0 + double((M + 31) / 32) * (0.31 + 0.2 * w_mb);
     } else {
         const double per_mb = slices > 8 ? 0.264 : (w_mb < 8.4 ? 0.17 : 0.21);
         const double per_block = per_mb * w_mb > 0.5 ? per_mb * w_mb : 0.5;
@@ -63,7 +73,7 @@ inline bool prefer_small_m(int64_t M, int64_t N, int64_t K)
     double t_mfma;
     if (wide <= 128.0) {                                   // 128 x 128 tiles, at most one per CU
         const double tiles = row_blocks * double((N + 127) / 128);
-        t_mfma = 3.0 + steps * (0.60 + 0.08 * tiles / 256.0);
+        t_mfma = 4.0 + steps * (0.53 + 0.04 * tiles / 256.0);
     } else {                                               // 128 x 256 tiles, in rounds of 256
         const double r = wide / 256.0;
         const double rounds = double(int64_t(r) + (r > double(int64_t(r)) ? 1 : 0));

@@ -8,9 +8,9 @@
 //
 //  * W stays packed all the way into LDS.  Per step a wave needs 16 bytes (64 codes) of each
 //    of its NW rows: one `global_load_lds_dwordx4` drops them into a wave-private ring of
-//    stages, several steps ahead, with no registers and no barrier involved.  A lane
+//    stages, three steps ahead, with no registers and no barrier involved.  A lane
 //    (column i, k half g) reads its row's 16 bytes back (one ds_read_b128 per 32 columns and
-//    step) and decodes, per 16-k block, the half-word it needs: `(w >> 8g) & (3 << 2j | 3 <<
+//    step, issued one step early) and decodes, per 16-k block, the half-word it needs: `(w >> 8g) & (3 << 2j | 3 <<
 //    (2j+16)) | 0x64006400` is the fp16 pair (1024 + 4^j c_j', 1024 + 4^j c_j'+8), j' = 4g + j,
 //    and one packed fma with 4^-j and -(1024 4^-j + 1) turns it into (c - 1, c - 1) exactly:
 //    2 VALU operations per operand register, and an operand register set feeds 4 MFMAs.
@@ -31,7 +31,7 @@ constexpr int BK = 64;                 // K elements per step
 constexpr int BM = 128;                // rows of X per workgroup
 constexpr int XROW = 144;              // bytes per X row in LDS: 128 + 16, keeps b128 reads conflict-free
 constexpr int XBUF = BM * XROW;        // one X buffer
-constexpr int WSTAGES = 8;             // steps of packed W in flight per wave
+constexpr int WSTAGES = 4;             // steps of packed W in flight per wave
 constexpr int WSTAGE = 1024;           // bytes per stage: 64 rows x 16 bytes
 
 int g_wide_min = 129;                  // 128 x 256 tiles from this many of them on (measured crossover)
@@ -59,14 +59,14 @@ __device__ __forceinline__ uint32_t pk_fma(uint32_t a, uint32_t b, uint32_t c)
 }
 
 // The 8 codes (j, j + 8), j = 0..3, of a half-word-shifted packed word -> 4 fp16 pairs (w_j, w_j+8).
-__device__ __forceinline__ f16x8 decode_half(uint32_t hw)
+__device__ __forceinline__ f16x8 decode_half(uint32_t hw, uint32_t k1024)
 {
     constexpr uint32_t kScale[4] = {0x3C003C00u, 0x34003400u, 0x2C002C00u, 0x24002400u};   // 4^-j
     constexpr uint32_t kOff[4] = {0xE401E401u, 0xDC04DC04u, 0xD410D410u, 0xCC40CC40u};     // -(1024 4^-j + 1)
     u32x4 o;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        const uint32_t t = (hw & (0x00030003u << (2 * j))) | 0x64006400u;
+        const uint32_t t = (hw & (0x00030003u << (2 * j))) | k1024;
         o[j] = pk_fma(t, kScale[j], kOff[j]);
     }
     return __builtin_bit_cast(f16x8, o);
@@ -181,17 +181,37 @@ mfma_kernel(MfmaParams p)
     const uint32_t b_addr =                                 // LDS byte address of this lane's row in stage 0
         uint32_t(uintptr_t((const __attribute__((address_space(3))) unsigned char*)(wring + fi * 16)));
     const uint32_t hshift = 8u * uint32_t(fg);
+    // The exponent pattern lives in a vector register the compiler cannot see through: with the
+    // mask in a scalar register, mask and merge are then one v_and_or_b32 (as two literals they
+    // are two instructions, since that encoding takes no literal).
+    uint32_t k1024;
+    asm volatile("v_mov_b32 %0, 0x64006400" : "=v"(k1024));
 
+    // The packed words of the next step are read from the ring before the barrier that ends a
+    // step (its wait for LDS covers them).  W of step t: (WSTAGES - 2) steps of 4 X loads and
+    // 1 transfer each were issued after it by then.  Hand-written ds_read: for an LDS read it can
+    // see, the compiler waits until every LDS-DMA transfer in flight has landed.
+    u32x4 wnext[FN];
+    auto read_w = [&](int t) {
+        __builtin_amdgcn_s_waitcnt(vm_imm(5 * (WSTAGES - 2)));
+        const uint32_t waddr = b_addr + uint32_t(t & (WSTAGES - 1)) * WSTAGE;
+        if constexpr (FN == 2) {
+            asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:512"
+                         : "=&v"(wnext[0]), "=&v"(wnext[1]) : "v"(waddr));
+        } else {
+            asm volatile("ds_read_b128 %0, %1" : "=&v"(wnext[0]) : "v"(waddr));
+        }
+    };
     // ---- prologue ---------------------------------------------------------------------------
     // Order of the memory operations of a wave, per step: 4 X loads, then 1 W transfer.  The
     // compiler counts the X loads itself; the W transfers (LDS-DMA) are waited for by hand.
     load_x(0, 0);
-    issue_w(0);
+#pragma unroll
+    for (int d = 0; d < WSTAGES - 1; ++d) issue_w(d);
     store_x(0, 0);
 #pragma unroll
     for (int d = 1; d <= XS; ++d) load_x(d % XS, d);   // slot j % XS holds X of step j
-#pragma unroll
-    for (int d = 1; d < WSTAGES - 1; ++d) issue_w(d);
+    read_w(0);
     lds_barrier();
 
     auto step_body = [&](auto slot_tag, int s) {
@@ -201,19 +221,14 @@ mfma_kernel(MfmaParams p)
         store_x(SLOT, PAR ^ 1);
         load_x(SLOT, s + 1 + XS);
         issue_w(s + WSTAGES - 1);
-        // W of step s: at least WSTAGES - 1 transfers and 8 X loads were issued after it
-        __builtin_amdgcn_s_waitcnt(vm_imm(WSTAGES - 1 + 8));
         const unsigned char* const xb = a_frag + PAR * XBUF;
-        // The ring is read with hand-written ds_read: for an LDS read it can see, the compiler
-        // waits until every LDS-DMA transfer in flight has landed, which would undo the ring.
         u32x4 wq[FN];
-        const uint32_t waddr = b_addr + uint32_t(s & (WSTAGES - 1)) * WSTAGE;
-        if constexpr (FN == 2) {
-            asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:512\n\ts_waitcnt lgkmcnt(0)"
-                         : "=&v"(wq[0]), "=&v"(wq[1]) : "v"(waddr));
-        } else {
-            asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(wq[0]) : "v"(waddr));
-        }
+        // read before the barrier behind us, which waited for it; the compiler does not know, so
+        // the values count as produced here
+        if constexpr (FN == 2) asm volatile("" : "+v"(wnext[0]), "+v"(wnext[1]));
+        else asm volatile("" : "+v"(wnext[0]));
+#pragma unroll
+        for (int b = 0; b < FN; ++b) wq[b] = wnext[b];
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
             f16x8 af[FM], bf[FN];
@@ -221,13 +236,14 @@ mfma_kernel(MfmaParams p)
             for (int a = 0; a < FM; ++a)
                 af[a] = *reinterpret_cast<const f16x8*>(xb + a * 32 * XROW + ks * 32);
 #pragma unroll
-            for (int b = 0; b < FN; ++b) bf[b] = decode_half(wq[b][ks] >> hshift);
+            for (int b = 0; b < FN; ++b) bf[b] = decode_half(wq[b][ks] >> hshift, k1024);
 #pragma unroll
             for (int a = 0; a < FM; ++a)
 #pragma unroll
                 for (int b = 0; b < FN; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[a], bf[b], acc[a][b], 0, 0, 0);
         }
+        read_w(s + 1);
         lds_barrier();
     };
 
