@@ -93,11 +93,18 @@ probe_read_kernel(const u32x4* __restrict__ src, size_t n16, unsigned* __restric
 }
 
 // ---- generic GEMM ---------------------------------------------------------------
-// One wavefront per output row n and per group of MB activation rows.  Lane l walks the
-// words l, l+64, ... of the packed row, decodes each code with shift-and-mask exactly as
-// Sec. 3.1 states it, and adds or subtracts x (no multiply); fp32 partial sums are folded
-// across the wave with a shuffle butterfly.
-constexpr int MB = 4;
+// Takes every shape (any K: packed rows and activation rows may start at any word / any even
+// byte).  A workgroup of 4 waves computes 16 activation rows x 16 output rows and walks K in
+// chunks of 1024.  The chunk's activations are staged in LDS as fp16 with coalesced 4-byte
+// (K even) or 2-byte loads, zero past K, so a code beyond K meets a zero.  Wave w
+// owns output rows 4w .. 4w+3: lane l decodes word l of the chunk of each of them with
+// shift-and-mask exactly as Sec. 3.1 states it (w = code - 1), reads its 16 activations of a
+// row from LDS and accumulates w x in fp32; the lanes' sums are folded across the wave at the end.
+constexpr int MB = 4;                  // activation rows per workgroup of the other generic kernels
+constexpr int GM = 16;                 // activation rows per workgroup
+constexpr int GN = 16;                 // output rows per workgroup (4 per wave)
+constexpr int GKC = 1024;              // K per chunk: one packed word per lane
+constexpr int GROW = GKC + 8;          // halves per staged row (16 bytes of padding)
 
 __device__ __forceinline__ float wave_sum(float v)
 {
@@ -109,31 +116,118 @@ __global__ void __launch_bounds__(256)
 gemm_generic_kernel(const __half* __restrict__ x, const uint32_t* __restrict__ Wp, float gamma,
                     __half* __restrict__ y, int64_t M, int64_t N, int64_t K, int64_t words)
 {
-    const int lane = threadIdx.x & 63;
-    const int64_t n = blockIdx.x * int64_t(4) + (threadIdx.x >> 6);
-    const int64_t m0 = blockIdx.y * int64_t(MB);
-    if (n >= N) return;                               // whole wave leaves together
-    float acc[MB];
-    for (int r = 0; r < MB; ++r) acc[r] = 0.f;
-    const uint32_t* row = Wp + n * words;
-    for (int64_t i = lane; i < words; i += 64) {
-        uint32_t word = row[i];
-        const int64_t base = 16 * i;
-        const int len = (K - base < 16) ? int(K - base) : 16;
-        for (int j = 0; j < len; ++j, word >>= 2) {
-            const int w = int(word & 3u) - 1;
-            for (int r = 0; r < MB; ++r) {
-                if (m0 + r < M) {
-                    const float xv = __half2float(x[(m0 + r) * K + base + j]);
-                    acc[r] += (w > 0) ? xv : ((w < 0) ? -xv : 0.f);
+    __shared__ __attribute__((aligned(16))) __half xs[GM * GROW];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int64_t n0 = blockIdx.x * int64_t(GN) + wave * 4;
+    const int64_t m0 = blockIdx.y * int64_t(GM);
+    const int mrem = int(M - m0 < GM ? M - m0 : GM);
+    float acc[GM][4];
+#pragma unroll
+    for (int r = 0; r < GM; ++r)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[r][c] = 0.f;
+
+    for (int64_t kc = 0; kc < K; kc += GKC) {
+        // this chunk's packed words first: they travel while the activations are staged
+        const int64_t i = kc / 16 + lane;
+        uint32_t word[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int64_t n = n0 + c;
+            word[c] = 0x55555555u;                     // all codes 1: weights 0
+            if (n < N && i < words) word[c] = Wp[n * words + i];
+        }
+        __syncthreads();                               // the chunk before has been consumed
+        // rows that exist only; 8 loads in flight per thread
+        if ((K & 1) == 0) {
+            const int total = mrem * (GKC / 2);
+            for (int base = tid; base < total; base += 256 * 8) {
+                uint32_t v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int idx = base + u * 256;
+                    const int r = idx / (GKC / 2);
+                    const int kp = (idx - r * (GKC / 2)) * 2;
+                    v[u] = 0u;
+                    if (idx < total && kc + kp < K)    // K and kp even: the pair lies inside the row
+                        v[u] = *reinterpret_cast<const uint32_t*>(x + (m0 + r) * K + kc + kp);
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int idx = base + u * 256;
+                    const int r = idx / (GKC / 2);
+                    const int kp = (idx - r * (GKC / 2)) * 2;
+                    if (idx < total) *reinterpret_cast<uint32_t*>(xs + r * GROW + kp) = v[u];
+                }
+            }
+        } else {
+            const int total = mrem * GKC;
+            for (int base = tid; base < total; base += 256 * 8) {
+                __half v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int idx = base + u * 256;
+                    const int r = idx / GKC;
+                    const int k = idx - r * GKC;
+                    v[u] = __ushort_as_half(0);
+                    if (idx < total && kc + k < K) v[u] = x[(m0 + r) * K + kc + k];
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int idx = base + u * 256;
+                    const int r = idx / GKC;
+                    const int k = idx - r * GKC;
+                    if (idx < total) xs[r * GROW + k] = v[u];
                 }
             }
         }
+        __syncthreads();
+
+        float wf[4][16];
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) wf[c][j] = float(int((word[c] >> (2 * j)) & 3u) - 1);
+#pragma unroll
+        for (int r = 0; r < GM; ++r) {
+            if (r < mrem) {
+                const f16x8 lo = *reinterpret_cast<const f16x8*>(xs + r * GROW + 16 * lane);
+                const f16x8 hi = *reinterpret_cast<const f16x8*>(xs + r * GROW + 16 * lane + 8);
+                float xf[16];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    xf[q] = float(lo[q]);
+                    xf[8 + q] = float(hi[q]);
+                }
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) acc[r][c] = fmaf(wf[c][j], xf[j], acc[r][c]);
+            }
+        }
     }
-    for (int r = 0; r < MB; ++r) {
-        const float s = wave_sum(acc[r]);
-        if (lane == 0 && m0 + r < M) y[(m0 + r) * N + n] = __float2half_rn(gamma * s);
+    // Fold the 64 sums of every lane across the wave: each butterfly step halves the values a
+    // lane carries (it keeps the half its lane bit selects and adds the partner's copy of it), so
+    // after 6 steps lane l holds the total of sum number l = 4 r + c.
+    float v[GM * 4];
+#pragma unroll
+    for (int r = 0; r < GM; ++r)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) v[4 * r + c] = acc[r][c];
+#pragma unroll
+    for (int half = 32; half >= 1; half >>= 1) {
+        const bool upper = (lane & half) != 0;
+#pragma unroll
+        for (int q = 0; q < half; ++q) {
+            const float send = upper ? v[q] : v[q + half];
+            const float keep = upper ? v[q + half] : v[q];
+            v[q] = keep + __shfl_xor(send, half, 64);
+        }
     }
+    const int r = lane >> 2, c = lane & 3;
+    if (r < mrem && n0 + c < N) y[(m0 + r) * N + n0 + c] = __float2half_rn(gamma * v[0]);
 }
 
 // The same with one fp16 scale per `group` weights along K and output row, s[K / group][N]
@@ -257,7 +351,7 @@ hipError_t launch_gemm_generic(const __half* x, const uint32_t* Wp, float gamma,
                                int64_t M, int64_t N, int64_t K, hipStream_t s)
 {
     const int64_t words = (K + 15) / 16;
-    dim3 grid(blocks_for(N, 4), blocks_for(M, MB));
+    dim3 grid(blocks_for(N, GN), blocks_for(M, GM));
     hipLaunchKernelGGL(gemm_generic_kernel, grid, dim3(256), 0, s, x, Wp, gamma, y, M, N, K, words);
     return hipGetLastError();
 }

@@ -957,14 +957,15 @@ hipError_t launch_stream(GemvBatch& b, int max_slices, int nb, hipStream_t s, bo
     b.pad = 0;
     const bool multi = gs || b.count > 1;              // the scaled form always reads the job table
     KernelFn fn = gs ? pick_stream_gs(T, multi_pass) : pick_stream(T, multi, multi_pass, nb);
-    static bool lds_raised[6][2][kTMax + 1];
+    static bool lds_raised[kMaxDevices][6][2][kTMax + 1];
     const int variant = gs ? (multi_pass ? 4 : 3) : (nb == 2 ? (multi_pass ? 5 : 2) : (multi_pass ? 1 : 0));
-    if (!lds_raised[variant][multi][T]) {
+    const int dev = device_slot();
+    if (dev < 0 || !lds_raised[dev][variant][multi][T]) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
                                            hipFuncAttributeMaxDynamicSharedMemorySize,
                                            8 * stream_wave_lds(T) + kStreamMaxRun * 1024);
         if (e != hipSuccess) return e;
-        lds_raised[variant][multi][T] = true;
+        if (dev >= 0) lds_raised[dev][variant][multi][T] = true;
     }
     hipLaunchKernelGGL(fn, dim3(grid), dim3(NW * 64), lds, s, b);
     return hipGetLastError();
@@ -1033,13 +1034,14 @@ hipError_t launch_batch(GemvBatch& b, bool grouped, bool stream_form, int nb, hi
     const bool multi = b.count > 1;
     KernelFn fn = pick_kernel(T, multi);
     // More than the default 64 KB of dynamic LDS needs the attribute; it is set once per
-    // kernel instance (idempotent, so a race only repeats it).
-    static bool lds_raised[2][kTMax + 1];
-    if (!lds_raised[multi][T]) {
+    // kernel instance and device (idempotent, so a race only repeats it).
+    static bool lds_raised[kMaxDevices][2][kTMax + 1];
+    const int dev = device_slot();
+    if (dev < 0 || !lds_raised[dev][multi][T]) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds);
         if (e != hipSuccess) return e;
-        lds_raised[multi][T] = true;
+        if (dev >= 0) lds_raised[dev][multi][T] = true;
     }
     hipLaunchKernelGGL(fn, dim3(grid), dim3(NW * 64), size_t(lds), s, b);
     return hipGetLastError();

@@ -530,13 +530,14 @@ hipError_t launch_gemv3(const __half* x, const uint8_t* Wp, int64_t stride, floa
     p.slices = int((stride + 127) / 128);
     const int NW = p.slices < kNW3Max ? p.slices : kNW3Max;
     int groups = p.tiles < 256 ? p.tiles : 256;
-    static bool lds_raised[2][kT3Max + 1];
+    static bool lds_raised[kMaxDevices][2][kT3Max + 1];
+    const int dev = device_slot();
     auto raise = [&](Kernel3Fn fn, int form, int T) -> hipError_t {
-        if (lds_raised[form][T]) return hipSuccess;
+        if (dev >= 0 && lds_raised[dev][form][T]) return hipSuccess;
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize,
                                                  kNW3Max * kWave3Lds + kLutBytes);
-        if (e == hipSuccess) lds_raised[form][T] = true;
+        if (e == hipSuccess && dev >= 0) lds_raised[dev][form][T] = true;
         return e;
     };
     dim3 grid(groups, unsigned((M + 15) / 16));

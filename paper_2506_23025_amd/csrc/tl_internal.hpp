@@ -82,6 +82,16 @@ hipError_t launch_mfma(const __half* x, const uint32_t* Wp, float gamma, __half*
                        int64_t M, int64_t N, int64_t K, hipStream_t s);
 
 // Prepare every kernel instance on the current device (dynamic-LDS limits); idempotent.
+// Once-per-device flags (a function attribute holds for the device it was set on): index of the
+// current device, or -1 when it cannot be tracked, in which case the caller does the work again.
+constexpr int kMaxDevices = 64;
+inline int device_slot()
+{
+    int d = -1;
+    if (hipGetDevice(&d) != hipSuccess) return -1;
+    return d >= 0 && d < kMaxDevices ? d : -1;
+}
+
 hipError_t gemv_init();
 hipError_t gemv3_init();
 
