@@ -112,8 +112,13 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
+// GS: one fp16 scale per `group` weights along K and output row, s[K / group][N] (group % 16 == 0,
+// so a packed word lies inside one group), instead of gamma: the word's weights are scaled as
+// they are decoded (s w is exact), y = fp16(sum).
+template <bool GS>
 __global__ void __launch_bounds__(256)
 gemm_generic_kernel(const __half* __restrict__ x, const uint32_t* __restrict__ Wp, float gamma,
+                    const __half* __restrict__ scales, int64_t group,
                     __half* __restrict__ y, int64_t M, int64_t N, int64_t K, int64_t words)
 {
     __shared__ __attribute__((aligned(16))) __half xs[GM * GROW];
@@ -133,11 +138,16 @@ gemm_generic_kernel(const __half* __restrict__ x, const uint32_t* __restrict__ W
         // this chunk's packed words first: they travel while the activations are staged
         const int64_t i = kc / 16 + lane;
         uint32_t word[4];
+        float sc[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const int64_t n = n0 + c;
             word[c] = 0x55555555u;                     // all codes 1: weights 0
-            if (n < N && i < words) word[c] = Wp[n * words + i];
+            sc[c] = GS ? 0.f : 1.f;
+            if (n < N && i < words) {
+                word[c] = Wp[n * words + i];
+                if constexpr (GS) sc[c] = __half2float(scales[((16 * i) / group) * N + n]);
+            }
         }
         __syncthreads();                               // the chunk before has been consumed
         // rows that exist only; 8 loads in flight per thread
@@ -189,7 +199,10 @@ gemm_generic_kernel(const __half* __restrict__ x, const uint32_t* __restrict__ W
 #pragma unroll
         for (int c = 0; c < 4; ++c)
 #pragma unroll
-            for (int j = 0; j < 16; ++j) wf[c][j] = float(int((word[c] >> (2 * j)) & 3u) - 1);
+            for (int j = 0; j < 16; ++j) {
+                const float w = float(int((word[c] >> (2 * j)) & 3u) - 1);
+                wf[c][j] = GS ? sc[c] * w : w;
+            }
 #pragma unroll
         for (int r = 0; r < GM; ++r) {
             if (r < mrem) {
@@ -227,46 +240,7 @@ gemm_generic_kernel(const __half* __restrict__ x, const uint32_t* __restrict__ W
         }
     }
     const int r = lane >> 2, c = lane & 3;
-    if (r < mrem && n0 + c < N) y[(m0 + r) * N + n0 + c] = __float2half_rn(gamma * v[0]);
-}
-
-// The same with one fp16 scale per `group` weights along K and output row, s[K / group][N]
-// (group % 16 == 0, so a packed word lies inside one group): every word's sum is weighted by
-// its group's scale.
-__global__ void __launch_bounds__(256)
-gemm_generic_gs_kernel(const __half* __restrict__ x, const uint32_t* __restrict__ Wp,
-                       const __half* __restrict__ scales, int64_t group, __half* __restrict__ y,
-                       int64_t M, int64_t N, int64_t K, int64_t words)
-{
-    const int lane = threadIdx.x & 63;
-    const int64_t n = blockIdx.x * int64_t(4) + (threadIdx.x >> 6);
-    const int64_t m0 = blockIdx.y * int64_t(MB);
-    if (n >= N) return;                               // whole wave leaves together
-    float acc[MB];
-    for (int r = 0; r < MB; ++r) acc[r] = 0.f;
-    const uint32_t* row = Wp + n * words;
-    for (int64_t i = lane; i < words; i += 64) {
-        uint32_t word = row[i];
-        const int64_t base = 16 * i;
-        const int len = (K - base < 16) ? int(K - base) : 16;
-        const float sc = __half2float(scales[(base / group) * N + n]);
-        float part[MB];
-        for (int r = 0; r < MB; ++r) part[r] = 0.f;
-        for (int j = 0; j < len; ++j, word >>= 2) {
-            const int w = int(word & 3u) - 1;
-            for (int r = 0; r < MB; ++r) {
-                if (m0 + r < M) {
-                    const float xv = __half2float(x[(m0 + r) * K + base + j]);
-                    part[r] += (w > 0) ? xv : ((w < 0) ? -xv : 0.f);
-                }
-            }
-        }
-        for (int r = 0; r < MB; ++r) acc[r] += sc * part[r];
-    }
-    for (int r = 0; r < MB; ++r) {
-        const float s = wave_sum(acc[r]);
-        if (lane == 0 && m0 + r < M) y[(m0 + r) * N + n] = __float2half_rn(s);
-    }
+    if (r < mrem && n0 + c < N) y[(m0 + r) * N + n0 + c] = __float2half_rn(GS ? v[0] : gamma * v[0]);
 }
 
 __global__ void __launch_bounds__(256)
@@ -352,7 +326,8 @@ hipError_t launch_gemm_generic(const __half* x, const uint32_t* Wp, float gamma,
 {
     const int64_t words = (K + 15) / 16;
     dim3 grid(blocks_for(N, GN), blocks_for(M, GM));
-    hipLaunchKernelGGL(gemm_generic_kernel, grid, dim3(256), 0, s, x, Wp, gamma, y, M, N, K, words);
+    hipLaunchKernelGGL(gemm_generic_kernel<false>, grid, dim3(256), 0, s, x, Wp, gamma,
+                       static_cast<const __half*>(nullptr), int64_t(16), y, M, N, K, words);
     return hipGetLastError();
 }
 
@@ -361,8 +336,8 @@ hipError_t launch_gemm_generic_gs(const __half* x, const uint32_t* Wp, const __h
                                   hipStream_t s)
 {
     const int64_t words = (K + 15) / 16;
-    dim3 grid(blocks_for(N, 4), blocks_for(M, MB));
-    hipLaunchKernelGGL(gemm_generic_gs_kernel, grid, dim3(256), 0, s, x, Wp, scales, group, y, M, N, K, words);
+    dim3 grid(blocks_for(N, GN), blocks_for(M, GM));
+    hipLaunchKernelGGL(gemm_generic_kernel<true>, grid, dim3(256), 0, s, x, Wp, 1.f, scales, group, y, M, N, K, words);
     return hipGetLastError();
 }
 

@@ -53,7 +53,7 @@ def test_unpack_dev_1p6bit_bit_exact(N, K):
 
 
 GENERIC_SHAPES = [(1, 1, 1), (1, 3, 16), (2, 5, 17), (3, 70, 100), (5, 129, 4096), (1, 2048, 2048),
-                  (4, 64, 11008), (17, 33, 1000)]
+                  (4, 64, 11008), (17, 33, 1000), (33, 100, 2047), (16, 4096, 4095), (40, 50, 2050)]
 
 
 @pytest.mark.parametrize("M,N,K", GENERIC_SHAPES)
@@ -486,6 +486,7 @@ GS_SHAPES = [
     (300, 64, 1024, 256), (2, 1152, 1344, 256), (1, 14336, 4096, 256),
     # plain kernel: any other group (multiple of 16), N or K
     (3, 7, 100, 16), (2, 33, 4096, 64), (5, 6, 4096, 256), (4, 12, 1000, 256),
+    (16, 4096, 4096, 128), (17, 300, 4000, 80), (1, 64, 1001, 16), (35, 21, 2047, 32),
 ]
 
 
