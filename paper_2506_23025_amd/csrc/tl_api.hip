@@ -42,7 +42,8 @@ constexpr int64_t kGemvMaxM = 4096;
 //    (11008 -> 4096: 16 blocks 68 us, 8 blocks 47 us)
 //  * small-M, blocks of 16 rows: 3.8 + blocks x W x (0.17 while W stays in the L2 caches, 0.21
 //    beyond, 0.264 when K needs several passes), at least 0.5 per block
-//  * MFMA, 128 x 128 tiles (at most one per CU): 4 + K/64 x (0.53 + 0.04 tiles/256)
+//  * MFMA, 128 x 128 tiles (at most one per CU): 7 + K/64 x (0.43 + 0.09 (tiles - 128)/128 beyond 128
+//    tiles) with two sets of waves per tile (K % 128 == 0), else 4 + K/64 x (0.53 + 0.04 tiles/256)
 //  * MFMA, 128 x 256 tiles: (5 + K/64 x 0.86) x f(tiles/256), f(r) = 1 up to one tile per CU, then
 //    max(r, 0.82 ceil(r)): a round that is not full costs most of a full one
 //    (4096 -> 14336: 336 tiles 98 us, 448 tiles 107 us, 896 tiles 219 us).
@@ -73,7 +74,10 @@ inline bool prefer_small_m(int64_t M, int64_t N, int64_t K)
     double t_mfma;
     if (wide <= 128.0) {                                   // 128 x 128 tiles, at most one per CU
         const double tiles = row_blocks * double((N + 127) / 128);
-        t_mfma = 4.0 + steps * (0.53 + 0.04 * tiles / 256.0);
+        if (K % 128 == 0)                                  // two sets of waves per tile
+            t_mfma = 7.0 + steps * (0.43 + 0.09 * (tiles > 128.0 ? (tiles - 128.0) / 128.0 : 0.0));
+        else
+            t_mfma = 4.0 + steps * (0.53 + 0.04 * tiles / 256.0);
     } else {                                               // 128 x 256 tiles, in rounds of 256
         const double r = wide / 256.0;
         const double rounds = double(int64_t(r) + (r > double(int64_t(r)) ? 1 : 0));

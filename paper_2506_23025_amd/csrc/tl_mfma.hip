@@ -10,8 +10,8 @@
 //    of its NW rows: one `global_load_lds_dwordx4` drops them into a wave-private ring of
 //    stages, three steps ahead, with no registers and no barrier involved.  A lane
 //    (column i, k half g) reads its row's 16 bytes back (one ds_read_b128 per 32 columns and
-//    step, issued one step early) and decodes, per 16-k block, the half-word it needs: `(w >> 8g) & (3 << 2j | 3 <<
-//    (2j+16)) | 0x64006400` is the fp16 pair (1024 + 4^j c_j', 1024 + 4^j c_j'+8), j' = 4g + j,
+//    step, issued one step early) and decodes, per 16-k block, the half-word it needs:
+//    `(w >> 8g) & (3 << 2j | 3 << (2j+16)) | 0x64006400` is the fp16 pair (1024 + 4^j c_j', 1024 + 4^j c_j'+8), j' = 4g + j,
 //    and one packed fma with 4^-j and -(1024 4^-j + 1) turns it into (c - 1, c - 1) exactly:
 //    2 VALU operations per operand register, and an operand register set feeds 4 MFMAs.
 //  * That pairs k with k + 8 inside every 16-k block.  The matrix instruction does not care
@@ -21,6 +21,8 @@
 //    in LDS (padded rows, conflict-free b128 reads), so a step costs one barrier.
 //  * Every wave runs v_mfma_f32_32x32x16_f16 over a 128 x NW sub-tile (4 x NW/32 fragments),
 //    X as the 32-row operand and W as the 32-column operand.
+//  * Launches of at most one 128 x 128 tile per CU use two such sets of 4 waves per workgroup,
+//    each with half of the K steps (SPLIT below).
 #include "tl_internal.hpp"
 
 namespace tl {
@@ -35,6 +37,7 @@ constexpr int WSTAGES = 4;             // steps of packed W in flight per wave
 constexpr int WSTAGE = 1024;           // bytes per stage: 64 rows x 16 bytes
 
 int g_wide_min = 129;                  // 128 x 256 tiles from this many of them on (measured crossover)
+int g_split = 1;                       // 128 x 128 tiles: two sets of waves per tile when K allows
 
 struct MfmaParams {
     const __half* x;
@@ -72,20 +75,30 @@ __device__ __forceinline__ f16x8 decode_half(uint32_t hw, uint32_t k1024)
     return __builtin_bit_cast(f16x8, o);
 }
 
-// NW: columns of Y per wave (64 or 32); XS: steps of X in flight in registers (even)
-template <int NW, int XS>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+// NW: columns of Y per wave (64 or 32); XS: steps of X in flight in registers (even).
+// SPLIT = 2: the workgroup has two such sets of 4 waves; set h takes the K steps 2 t + h (K a
+// multiple of 128), with X buffers and W rings of its own, and the sets' sums are added through
+// LDS at the end.  For launches of at most one tile per CU, where a lone set leaves each SIMD
+// with one wave that waits out every load, LDS round trip and barrier of a step.
+template <int SPLIT>
+constexpr int mfma_lds_bytes() { return SPLIT * (2 * XBUF + 4 * WSTAGES * WSTAGE); }
+
+template <int NW, int XS, int SPLIT>
+__global__ void __launch_bounds__(256 * SPLIT) __attribute__((amdgpu_waves_per_eu(2, 2)))
 mfma_kernel(MfmaParams p)
 {
     constexpr int FM = BM / 32;                        // 4 fragments down
     constexpr int FN = NW / 32;                        // 2 or 1 fragments across
     constexpr int BN = 4 * NW;
-    __shared__ __attribute__((aligned(16))) unsigned char Xs[2 * XBUF];
-    __shared__ __attribute__((aligned(16))) unsigned char Ws[4 * WSTAGES * WSTAGE];
+    static_assert(SPLIT == 1 || (SPLIT == 2 && FN == 1), "the sums of the second set go through the X buffers");
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_all[];
 
-    const int tid = threadIdx.x;
+    const int set = SPLIT == 2 ? __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 8) : 0;
+    const int tid = threadIdx.x & 255;
     const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);        // within the set
+    unsigned char* const Xs = lds_all + set * (2 * XBUF);
+    unsigned char* const Ws = lds_all + SPLIT * (2 * XBUF) + set * (4 * WSTAGES * WSTAGE);
 
     // XCD-aware tile order: consecutive workgroup ids go to different XCDs (8 of them), so a
     // group's position inside its XCD picks neighbouring tiles that share a W column block.
@@ -101,7 +114,12 @@ mfma_kernel(MfmaParams p)
     const int m_base = tm * BM;
     const int n_base = tn * BN + wave * NW;            // this wave's first column
     const int K = p.K;
-    const int steps = K / BK;
+    const int steps = K / BK / SPLIT;                  // steps of this set
+    // step t of this set as a step of K; past the end: a valid one, loaded and never used
+    auto kstep = [&](int t) {
+        if (t >= steps) t = steps - 1;
+        return t * SPLIT + set;
+    };
 
     // ---- X: thread t copies the 64 bytes (32 k) at row t / 2, half t % 2 of every step --------
     const int xr = tid >> 1, xh = tid & 1;
@@ -115,8 +133,7 @@ mfma_kernel(MfmaParams p)
     typedef const __attribute__((address_space(1))) u32x4* gptr;
     u32x4 xreg[XS][4];                                  // XS steps in flight
     auto load_x = [&](int slot, int step) {
-        if (step >= steps) step = steps - 1;            // past the end: loaded again, never used
-        const unsigned char* src = xsrc + size_t(step) * (BK * 2);
+        const unsigned char* src = xsrc + size_t(kstep(step)) * (BK * 2);
 #pragma unroll
         for (int i = 0; i < 4; ++i) xreg[slot][i] = *(gptr)(src + 16 * i);
     };
@@ -154,8 +171,7 @@ mfma_kernel(MfmaParams p)
     const uint32_t wring_addr = uint32_t(uintptr_t((const __attribute__((address_space(3))) unsigned char*)wring));
     auto issue_w = [&](int step) {
         const uint32_t stage = uint32_t(step & (WSTAGES - 1));
-        if (step >= steps) step = steps - 1;
-        const unsigned char* src = wsrc + size_t(step) * 16;
+        const unsigned char* src = wsrc + size_t(kstep(step)) * 16;
         const uint32_t base = __builtin_amdgcn_readfirstlane(wring_addr + stage * WSTAGE);
         asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(base) : "memory");
     };
@@ -229,6 +245,28 @@ mfma_kernel(MfmaParams p)
         else asm volatile("" : "+v"(wnext[0]));
 #pragma unroll
         for (int b = 0; b < FN; ++b) wq[b] = wnext[b];
+        if constexpr (SPLIT == 2) {
+            // The two waves of a SIMD belong to the two sets and run in step (same barriers), so
+            // neither hides the other's waits: all X fragments of the step are requested up front.
+            f16x8 af[4][FM];
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+                for (int a = 0; a < FM; ++a)
+                    af[ks][a] = *reinterpret_cast<const f16x8*>(xb + a * 32 * XROW + ks * 32);
+            __builtin_amdgcn_sched_barrier(0);         // or the scheduler moves each read down to its use
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                f16x8 bf[FN];
+#pragma unroll
+                for (int b = 0; b < FN; ++b) bf[b] = decode_half(wq[b][ks] >> hshift, k1024);
+#pragma unroll
+                for (int a = 0; a < FM; ++a)
+#pragma unroll
+                    for (int b = 0; b < FN; ++b)
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[ks][a], bf[b], acc[a][b], 0, 0, 0);
+            }
+        } else {
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
             f16x8 af[FM], bf[FN];
@@ -242,6 +280,7 @@ mfma_kernel(MfmaParams p)
 #pragma unroll
                 for (int b = 0; b < FN; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[a], bf[b], acc[a][b], 0, 0, 0);
+        }
         }
         read_w(s + 1);
         lds_barrier();
@@ -262,6 +301,27 @@ mfma_kernel(MfmaParams p)
     if constexpr (XS == 4)
         if (s < steps) { step_body(std::integral_constant<int, 3>{}, s); ++s; }
     __builtin_amdgcn_s_waitcnt(vm_imm(0));             // nothing of this wave's ring is left in flight
+
+    if constexpr (SPLIT == 2) {
+        // Every wave is past the barrier of its last step: the X buffers are free.  16 KB per wave.
+        float* const red = reinterpret_cast<float*>(lds_all) + wave * (FM * FN * 16 * 64) + lane;
+        if (set == 1) {
+#pragma unroll
+            for (int a = 0; a < FM; ++a)
+#pragma unroll
+                for (int b = 0; b < FN; ++b)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) red[((a * FN + b) * 16 + r) * 64] = acc[a][b][r];
+        }
+        lds_barrier();
+        if (set == 1) return;
+#pragma unroll
+        for (int a = 0; a < FM; ++a)
+#pragma unroll
+            for (int b = 0; b < FN; ++b)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[a][b][r] += red[((a * FN + b) * 16 + r) * 64];
+    }
 
     // ---- epilogue: y[m][n] = fp16(gamma * acc) ---------------------------------------------
     // D[i][j] of a 32x32 fragment: j = lane % 32, i = 8 (r / 4) + 4 (lane / 32) + r % 4.
@@ -284,6 +344,7 @@ mfma_kernel(MfmaParams p)
 
 #ifdef TL_DEV_HOOKS
 extern "C" void tl_dev_mfma(int wide_min) { g_wide_min = wide_min; }
+extern "C" void tl_dev_split(int on) { g_split = on; }
 #endif
 
 bool mfma_supports(int64_t M, int64_t N, int64_t K)
@@ -304,10 +365,22 @@ hipError_t launch_mfma(const __half* x, const uint32_t* Wp, float gamma, __half*
     const int64_t wide = int64_t(p.tiles_m) * ((N + 255) / 256);
     if (wide >= g_wide_min) {
         p.tiles_n = int((N + 255) / 256);
-        hipLaunchKernelGGL((mfma_kernel<64, 4>), dim3(p.tiles_m * p.tiles_n), dim3(256), 0, s, p);
+        hipLaunchKernelGGL((mfma_kernel<64, 4, 1>), dim3(p.tiles_m * p.tiles_n), dim3(256), mfma_lds_bytes<1>(), s, p);
+    } else if (g_split && K % (2 * BK) == 0) {
+        // at most one tile per CU: two sets of waves per tile, each with half of the K steps
+        static bool raised[kMaxDevices];
+        const int dev = device_slot();
+        if (dev < 0 || !raised[dev]) {
+            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&mfma_kernel<32, 4, 2>),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, mfma_lds_bytes<2>());
+            if (e != hipSuccess) return e;
+            if (dev >= 0) raised[dev] = true;
+        }
+        p.tiles_n = int((N + 127) / 128);
+        hipLaunchKernelGGL((mfma_kernel<32, 4, 2>), dim3(p.tiles_m * p.tiles_n), dim3(512), mfma_lds_bytes<2>(), s, p);
     } else {
         p.tiles_n = int((N + 127) / 128);
-        hipLaunchKernelGGL((mfma_kernel<32, 4>), dim3(p.tiles_m * p.tiles_n), dim3(256), 0, s, p);
+        hipLaunchKernelGGL((mfma_kernel<32, 4, 1>), dim3(p.tiles_m * p.tiles_n), dim3(256), mfma_lds_bytes<1>(), s, p);
     }
     return hipGetLastError();
 }

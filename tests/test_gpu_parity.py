@@ -227,6 +227,8 @@ def test_small_m_kernel_blocks_of_32_rows(M, N, K):
 MFMA_SHAPES = [
     (256, 256, 64), (1, 16, 64), (300, 200, 128), (128, 128, 4096), (512, 384, 1024),
     (257, 130, 192), (64, 1000, 2048), (1024, 512, 512), (31, 257, 11008),
+    # 128 x 128 tiles: K % 128 == 0 runs two sets of waves per tile (1 and 2 steps each), else one
+    (4, 33, 128), (130, 260, 256), (100, 140, 320), (384, 4096, 4096),
 ]
 
 
