@@ -289,6 +289,7 @@ def main():
                 ring3[i].copy_(ring3[0])
             group = 256
             sc = torch.from_numpy(si.group_scales(frng, K // group, N).view(np.int16)).to(dev)
+            sc128 = torch.from_numpy(si.group_scales(frng, K // 128, N).view(np.int16)).to(dev)
             for M in (1, 4, 16):
                 cur = [0]
                 fy = torch.empty((M, N), dtype=torch.int16, device=dev)    # the sweep's outputs stay as they are
@@ -301,10 +302,10 @@ def main():
                     if st != tl.TL_OK:
                         raise tl.TlError(st, "tl_ternary_gemm_1p6")
 
-                def call_gs():
+                def call_gs(scales=sc, grp=group):
                     i = cursor[name]
                     cursor[name] = (i + 1) % lay["copies"]
-                    st = L.tl_ternary_gemm_gs(xd[M].data_ptr(), lay["ring"][i].data_ptr(), sc.data_ptr(), group,
+                    st = L.tl_ternary_gemm_gs(xd[M].data_ptr(), lay["ring"][i].data_ptr(), scales.data_ptr(), grp,
                                               fy.data_ptr(), M, N, K, stream)
                     if st != tl.TL_OK:
                         raise tl.TlError(st, "tl_ternary_gemm_gs")
@@ -313,12 +314,14 @@ def main():
                 us2 = timed(lambda: launch(name, M), reps) * 1e3 / reps
                 us3 = timed(call3, reps) * 1e3 / reps
                 usg = timed(call_gs, reps) * 1e3 / reps
+                usg128 = timed(lambda: call_gs(sc128, 128), reps) * 1e3 / reps
                 b2 = algorithmic_bytes(M, N, K)
                 b3 = N * W3.shape[1] + 2 * M * K + 2 * M * N
                 formats.append(dict(layer=name, M=M, N=N, K=K,
                                     two_bit=dict(us=round(us2, 3), GBps=round(b2 / us2 / 1e3, 1)),
                                     one_point_six_bit=dict(us=round(us3, 3), GBps=round(b3 / us3 / 1e3, 1)),
-                                    two_bit_group_scales_256=dict(us=round(usg, 3), GBps=round((b2 + 2 * (K // group) * N) / usg / 1e3, 1))))
+                                    two_bit_group_scales_256=dict(us=round(usg, 3), GBps=round((b2 + 2 * (K // group) * N) / usg / 1e3, 1)),
+                                    two_bit_group_scales_128=dict(us=round(usg128, 3), GBps=round((b2 + 2 * (K // 128) * N) / usg128 / 1e3, 1))))
             del ring3
 
     # dominant kernel: the small-M kernel in its grouped launch; one launch = one step

@@ -217,9 +217,10 @@ tl_status tl_ternary_gemm_1p6_fx(const void* x, const void* Wpacked, uint16_t ga
  * scales held in a separate buffer).  `scales` is a device pointer to fp16
  * [ceil(K / group)][N], 16-byte aligned; the last group may be short.  x, Wpacked (2-bit
  * format), y, stream, accumulation and rounding as for tl_ternary_gemm.  `group` must be a
- * multiple of 16 (TL_ERR_SHAPE otherwise).  group % 256 == 0, K % 64 == 0 and N % 4 == 0 run
- * in the weight-streaming small-M kernel (M in blocks of 16 rows); everything else in a plain
- * kernel without tiling.  Nothing is allocated; the call is asynchronous on `stream`.
+ * multiple of 16 (TL_ERR_SHAPE otherwise).  group % 128 == 0, K % 64 == 0 and N % 4 == 0 run
+ * in the weight-streaming small-M kernel (M in blocks of 16 rows; multiples of 256 a little
+ * faster than odd multiples of 128); everything else in the generic kernel on the vector ALUs.
+ * Nothing is allocated; the call is asynchronous on `stream`.
  */
 tl_status tl_ternary_gemm_gs(const void* x, const void* Wpacked, const void* scales, int64_t group,
                              void* y, int64_t M, int64_t N, int64_t K, void* stream);

@@ -451,7 +451,7 @@ constexpr int stream_wave_lds(int T)
 // GPU kernel: scales kept in a separate buffer) instead of one gamma: the two 256-weight halves
 // of a slice are accumulated apart, each multiplied by the scale of its group and output row.
 // Groups are multiples of 256 weights; the scales lie as [K / group][N].
-template <int T, bool MULTI, bool PASSES, int NB, bool GS = false>
+template <int T, bool MULTI, bool PASSES, int NB, int GS = 0>
 __global__ void __launch_bounds__(512)
 gemv_stream_kernel(GemvBatch b)
 {
@@ -461,8 +461,11 @@ gemv_stream_kernel(GemvBatch b)
     const int NW = blockDim.x >> 6;
     // LDS of a wave: activation rows (16 KB) while the operands are built; afterwards two tile
     // regions at 0 and 2 KB, and from 4 KB two sets of T NB partial-sum tiles (1 KB each).
-    static_assert(!GS || (NB == 1 && MULTI), "per-group scales: one row block, job table");
-    constexpr int H = GS ? 2 : 1;             // accumulator sets per tile: one per 256-weight half
+    // GS: 0, or the number of scale units in a wave's 512-weight slice: 2 (units of 256 weights, an
+    // MFMA's whole k range) or 4 (units of 128: an MFMA's lane groups 0,1 and 2,3 lie in different
+    // units, so every product is issued twice, each time with the other pair's weights masked off)
+    static_assert(GS == 0 || ((GS == 2 || GS == 4) && NB == 1 && MULTI), "per-group scales: one row block, job table");
+    constexpr int H = GS ? GS : 1;            // accumulator sets per tile: one per scale unit
     constexpr int kStride = stream_wave_lds(T * NB);
     unsigned char* const my_lds = lds_raw + wave * kStride;
 
@@ -512,8 +515,10 @@ gemv_stream_kernel(GemvBatch b)
     typedef const __attribute__((address_space(1))) u32x4* gptr;
 
     u32x4 wreg[T][2];
-    f16x4 sreg[T][H];                          // GS: the scales of the lane's four output rows, per half
-    uint32_t sc_off[2] = {0u, 0u};             // GS: byte offset of the halves' groups in the scales
+    f16x4 sreg[T][H];                          // GS: the scales of the lane's four output rows, per unit
+    uint32_t sc_off[H] = {};                   // GS: byte offset of the units' groups in the scales
+    // GS == 4: all ones in the lanes whose k lies in the first (second) unit of an MFMA's range
+    const uint32_t pair_mask[2] = {(lane >> 5) == 0 ? 0xFFFFFFFFu : 0u, (lane >> 5) == 1 ? 0xFFFFFFFFu : 0u};
     auto issue_w = [&](int first, int t) {
         int tile = first + t;
         if (tile >= tile_end) tile = tile_end - 1;         // past the run: its last tile again, never stored
@@ -528,7 +533,7 @@ gemv_stream_kernel(GemvBatch b)
             int n0 = tile * 16 + 4 * mg;                   // the lane's rows of the result: n0 .. n0 + 3
             if (n0 > J.N - 4) n0 = J.N - 4;                // rows past N (N % 4 == 0): any scale will do
 #pragma unroll
-            for (int hh = 0; hh < 2; ++hh)
+            for (int hh = 0; hh < H; ++hh)
                 sreg[t][hh] = *(const __attribute__((address_space(1))) f16x4*)(J.sc + sc_off[hh] + uint32_t(n0) * 2u);
         }
     };
@@ -554,11 +559,12 @@ gemv_stream_kernel(GemvBatch b)
 #pragma unroll
         for (int hh = 0; hh < H; ++hh) nsx[nb][hh] = f32x4{0.f, 0.f, 0.f, 0.f};
     if constexpr (GS) {
-        // groups of this wave's two halves; a half past K (its activations are zeros) takes the last group
-        const int last_group = (J.K - 1) / (256 * J.hpg);
+        // groups of this wave's units (J.hpg units per group); a unit past K (its activations are
+        // zeros) takes the last group
+        const int last_group = (J.K - 1) / ((kSliceK / H) * J.hpg);
 #pragma unroll
-        for (int hh = 0; hh < 2; ++hh) {
-            int g = (2 * slice + hh) / J.hpg;
+        for (int hh = 0; hh < H; ++hh) {
+            int g = (H * slice + hh) / J.hpg;
             if (g > last_group) g = last_group;
             sc_off[hh] = uint32_t(g) * uint32_t(J.N) * 2u;
         }
@@ -603,7 +609,7 @@ gemv_stream_kernel(GemvBatch b)
 #pragma unroll
                 for (int t = 0; t < T; ++t) issue_w(tile0, t);
                 // the compiler does not track LDS-DMA: wait until only the 2T weight loads are outstanding
-                __builtin_amdgcn_s_waitcnt(vmcnt_imm((GS ? 4 : 2) * T));
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm((2 + GS) * T));
             } else {
                 __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // requested after the weights: wait for all
             }
@@ -638,7 +644,15 @@ gemv_stream_kernel(GemvBatch b)
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const u32x4 bb = u32x4{breg[nb][h][0][e], breg[nb][h][1][e], breg[nb][h][2][e], breg[nb][h][3][e]};
-                    nsx[nb][GS ? h : 0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), as_f16x8(bb), nsx[nb][GS ? h : 0], 0, 0, 0);
+                    if constexpr (GS == 4) {
+#pragma unroll
+                        for (int q = 0; q < 2; ++q) {
+                            const u32x4 aq = a & pair_mask[q];
+                            nsx[nb][2 * h + q] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(aq), as_f16x8(bb), nsx[nb][2 * h + q], 0, 0, 0);
+                        }
+                    } else {
+                        nsx[nb][GS ? h : 0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), as_f16x8(bb), nsx[nb][GS ? h : 0], 0, 0, 0);
+                    }
                 }
             if (NB > 1 && nb == 0) __builtin_amdgcn_s_waitcnt(0xF | (0x3 << 14) | (0x7 << 4));   // staging read before it is refilled
         } else {
@@ -700,7 +714,15 @@ gemv_stream_kernel(GemvBatch b)
 #pragma unroll
                             for (int nb = 0; nb < NB; ++nb) {
                                 const u32x4 bb = u32x4{breg[nb][h][0][e], breg[nb][h][1][e], breg[nb][h][2][e], breg[nb][h][3][e]};
-                                acc[nb][GS ? h : 0][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), as_f16x8(bb), acc[nb][GS ? h : 0][j], 0, 0, 0);
+                                if constexpr (GS == 4) {
+#pragma unroll
+                                    for (int q = 0; q < 2; ++q) {
+                                        const u32x4 aq = sh[src] & (mask & pair_mask[q]);
+                                        acc[nb][2 * h + q][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(aq), as_f16x8(bb), acc[nb][2 * h + q][j], 0, 0, 0);
+                                    }
+                                } else {
+                                    acc[nb][GS ? h : 0][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), as_f16x8(bb), acc[nb][GS ? h : 0][j], 0, 0, 0);
+                                }
                             }
                         }
                     }
@@ -710,7 +732,7 @@ gemv_stream_kernel(GemvBatch b)
                             // register r of the accumulator is output row 4 (lane / 16) + r of the tile
                             f32x4 sum = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                            for (int hh = 0; hh < 2; ++hh) {
+                            for (int hh = 0; hh < H; ++hh) {
                                 const f32x4 sc = f32x4{float(sc_cur[hh][0]), float(sc_cur[hh][1]), float(sc_cur[hh][2]), float(sc_cur[hh][3])};
                                 sum += sc * (acc[nb][hh][0] * 1048576.f + acc[nb][hh][1] * 262144.f + acc[nb][hh][2] * 65536.f);
                             }
@@ -811,12 +833,17 @@ KernelFn pick_stream_t(int T)
     }
 }
 
-KernelFn pick_stream_gs(int T, bool passes)
+// units: scale units per 512-weight slice, 2 (256 weights each) or 4 (128 each, at most 2 tiles per item)
+KernelFn pick_stream_gs(int T, bool passes, int units)
 {
+    if (units == 4) {
+        if (T == 1) return passes ? gemv_stream_kernel<1, true, true, 1, 4> : gemv_stream_kernel<1, true, false, 1, 4>;
+        return passes ? gemv_stream_kernel<2, true, true, 1, 4> : gemv_stream_kernel<2, true, false, 1, 4>;
+    }
     switch (T) {
-        case 1: return passes ? gemv_stream_kernel<1, true, true, 1, true> : gemv_stream_kernel<1, true, false, 1, true>;
-        case 2: return passes ? gemv_stream_kernel<2, true, true, 1, true> : gemv_stream_kernel<2, true, false, 1, true>;
-        default: return passes ? gemv_stream_kernel<3, true, true, 1, true> : gemv_stream_kernel<3, true, false, 1, true>;
+        case 1: return passes ? gemv_stream_kernel<1, true, true, 1, 2> : gemv_stream_kernel<1, true, false, 1, 2>;
+        case 2: return passes ? gemv_stream_kernel<2, true, true, 1, 2> : gemv_stream_kernel<2, true, false, 1, 2>;
+        default: return passes ? gemv_stream_kernel<3, true, true, 1, 2> : gemv_stream_kernel<3, true, false, 1, 2>;
     }
 }
 
@@ -851,6 +878,7 @@ struct GemvPolicy {
     int stream_groups = 256;            // workgroups of the stream form (one per CU)
     int two_blocks = 1;                 // jobs of more than 16 rows go in blocks of 32 (two row blocks per wave)
     double start_up_per_row = 0.15;     // stream form: start-up of a pass in tiles per activation row
+    double pass_start = 3.0;            // stream form: wait of every pass but the first for its activations, in tiles
     int t_stream = 0;                   // stream form: cap on tiles per item (0: none)
     int long_k_min_run = 3;             // K > 4096 streams if the call averages this many tile passes per workgroup
 };
@@ -864,7 +892,7 @@ constexpr int kStreamMaxRun = 32;       // tiles of a run whose sums fit the 32 
 // out to the jobs so that all finish together (see run_cost below); spare ones go to the job
 // with the costliest runs, one by one.  Returns hipErrorInvalidValue without launching if a multi-pass job's
 // runs would not fit the LDS (the caller then uses the general kernel).
-hipError_t launch_stream(GemvBatch& b, int max_slices, int nb, hipStream_t s, bool gs = false)
+hipError_t launch_stream(GemvBatch& b, int max_slices, int nb, hipStream_t s, int gs = 0)
 {
     const GemvPolicy pol = g_policy;
     const int NW = max_slices < kStreamWaves ? max_slices : kStreamWaves;
@@ -886,7 +914,7 @@ hipError_t launch_stream(GemvBatch& b, int max_slices, int nb, hipStream_t s, bo
     // first, counted as 3 tiles more.  Bisection on the common finishing time gives the group counts.
     auto start_up = [&](int j) {
         const int rows = b.job[j].Mrem < 16 * nb ? b.job[j].Mrem : 16 * nb;
-        return pol.start_up_per_row * double(rows) + (passes(j) > 1 ? 3.0 : 0.0);
+        return pol.start_up_per_row * double(rows) + (passes(j) > 1 ? pol.pass_start : 0.0);
     };
     auto run_cost = [&](int j, int w) {
         return double(passes(j)) * (double((b.job[j].tiles + w - 1) / w) + start_up(j));
@@ -935,6 +963,7 @@ hipError_t launch_stream(GemvBatch& b, int max_slices, int nb, hipStream_t s, bo
     int T = run <= 3 ? run : (run == 4 ? 2 : 3);
     if (T > NW) T = NW;                  // the epilogue gives every thread at most one output quad
     if (pol.t_stream > 0 && T > pol.t_stream) T = pol.t_stream;
+    if (gs == 4 && T > 2) T = 2;         // scale units of 128 weights: 12 accumulators per tile (registers)
     if (nb == 2) {                       // two row blocks per job: at most 2 tiles per item (registers)
         if (T > 2) T = 2;
         if (2 * T > NW) T = NW / 2;
@@ -955,10 +984,11 @@ hipError_t launch_stream(GemvBatch& b, int max_slices, int nb, hipStream_t s, bo
     b.total_items = total_items;
     b.red_off = 0;
     b.pad = 0;
-    const bool multi = gs || b.count > 1;              // the scaled form always reads the job table
-    KernelFn fn = gs ? pick_stream_gs(T, multi_pass) : pick_stream(T, multi, multi_pass, nb);
-    static bool lds_raised[kMaxDevices][6][2][kTMax + 1];
-    const int variant = gs ? (multi_pass ? 4 : 3) : (nb == 2 ? (multi_pass ? 5 : 2) : (multi_pass ? 1 : 0));
+    const bool multi = gs != 0 || b.count > 1;         // the scaled form always reads the job table
+    KernelFn fn = gs ? pick_stream_gs(T, multi_pass, gs) : pick_stream(T, multi, multi_pass, nb);
+    static bool lds_raised[kMaxDevices][8][2][kTMax + 1];
+    const int variant = gs == 4 ? (multi_pass ? 7 : 6)
+                                : (gs ? (multi_pass ? 4 : 3) : (nb == 2 ? (multi_pass ? 5 : 2) : (multi_pass ? 1 : 0)));
     const int dev = device_slot();
     if (dev < 0 || !lds_raised[dev][variant][multi][T]) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
@@ -1063,6 +1093,7 @@ extern "C" void tl_dev_stream(int stream, int groups, int long_k_min_run)
 extern "C" void tl_dev_two_blocks(int on) { g_policy.two_blocks = on; }
 extern "C" void tl_dev_stream_t(int t) { g_policy.t_stream = t; }
 extern "C" void tl_dev_start_up(double v) { g_policy.start_up_per_row = v; }
+extern "C" void tl_dev_pass_start(double v) { g_policy.pass_start = v; }
 #endif
 
 // Raises the dynamic-LDS limit of every kernel instance of this file on the current device (the
@@ -1079,7 +1110,8 @@ hipError_t gemv_init()
             for (int passes = 0; passes < 2 && e == hipSuccess; ++passes) {
                 e = raise(pick_stream(T, multi != 0, passes != 0, 1), stream_lds);
                 if (e == hipSuccess && T <= 2) e = raise(pick_stream(T, multi != 0, passes != 0, 2), stream_lds);
-                if (e == hipSuccess && T <= 3) e = raise(pick_stream_gs(T, passes != 0), stream_lds);
+                if (e == hipSuccess && T <= 3) e = raise(pick_stream_gs(T, passes != 0, 2), stream_lds);
+                if (e == hipSuccess && T <= 2) e = raise(pick_stream_gs(T, passes != 0, 4), stream_lds);
             }
             if (e != hipSuccess) return e;
         }
@@ -1172,7 +1204,7 @@ hipError_t launch_gemv_jobs(const GemmDesc* jobs, int count, hipStream_t s)
 bool gemv_gs_supports(int64_t M, int64_t N, int64_t K, int64_t group)
 {
     const int64_t slices = (K + kSliceK - 1) / kSliceK;
-    return gemv_supports(M, N, K) && group >= 256 && group % 256 == 0 && N >= 4 && N % 4 == 0 &&
+    return gemv_supports(M, N, K) && group >= 128 && group % 128 == 0 && N >= 4 && N % 4 == 0 &&
            slices <= kStreamWaves * kStreamMaxPasses &&
            (slices <= kStreamWaves || (N + 15) / 16 <= int64_t(256) * kStreamMaxRun);
 }
@@ -1183,7 +1215,9 @@ hipError_t launch_gemv_gs(const __half* x, const uint32_t* Wp, const __half* sca
     if (!gemv_gs_supports(M, N, K, group)) return hipErrorInvalidValue;
     const int slices = int((K + kSliceK - 1) / kSliceK);
     const uintptr_t sp = reinterpret_cast<uintptr_t>(scales);
-    const int hpg = int(group / 256);
+    // scale units per slice: 2 of 256 weights when the groups allow, else 4 of 128; hpg = units per group
+    const int units = group % 256 == 0 ? 2 : 4;
+    const int hpg = int(group / (kSliceK / units));
     GemvBatch b;
     b.count = 0;
     for (int64_t m0 = 0; m0 < M; m0 += 16) {
@@ -1201,7 +1235,7 @@ hipError_t launch_gemv_gs(const __half* x, const uint32_t* Wp, const __half* sca
         j.pad[0] = j.pad[1] = 0;
         b.job[b.count++] = j;
         if (b.count == kMaxJobs || m0 + 16 >= M) {
-            const hipError_t e = launch_stream(b, slices, 1, s, true);
+            const hipError_t e = launch_stream(b, slices, 1, s, units);
             if (e != hipSuccess) return e;
             b.count = 0;
         }

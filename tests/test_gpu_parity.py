@@ -482,13 +482,16 @@ def run_gemm_gs(x, Wp, sc, group, N, K):
 
 
 GS_SHAPES = [
-    # small-M stream kernel: group % 256 == 0, K % 64 == 0, N % 4 == 0
+    # small-M stream kernel: group % 128 == 0, K % 64 == 0, N % 4 == 0
     (1, 64, 512, 256), (3, 100, 1024, 256), (16, 4096, 4096, 256), (5, 272, 4096, 512), (16, 144, 4096, 1024),
     (7, 48, 4096, 4096), (1, 4100, 4096, 256), (33, 128, 2048, 256), (4, 40, 11008, 256), (2, 64, 8192, 768),
     (300, 64, 1024, 256), (2, 1152, 1344, 256), (1, 14336, 4096, 256),
+    # the same kernel with scale units of 128 weights: group % 128 == 0 but not % 256
+    (1, 64, 512, 128), (3, 100, 1024, 128), (16, 4096, 4096, 128), (5, 272, 4096, 384), (4, 40, 11008, 128),
+    (33, 128, 2048, 128), (2, 1152, 1344, 128), (1, 14336, 4096, 128), (7, 48, 4096, 640), (16, 64, 8192, 1152),
     # plain kernel: any other group (multiple of 16), N or K
     (3, 7, 100, 16), (2, 33, 4096, 64), (5, 6, 4096, 256), (4, 12, 1000, 256),
-    (16, 4096, 4096, 128), (17, 300, 4000, 80), (1, 64, 1001, 16), (35, 21, 2047, 32),
+    (16, 4096, 4096, 64), (17, 300, 4000, 80), (1, 64, 1001, 16), (35, 21, 2047, 32), (3, 30, 4096, 128),
 ]
 
 
