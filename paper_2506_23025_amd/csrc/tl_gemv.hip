@@ -448,9 +448,9 @@ constexpr int stream_wave_lds(int T)
 // operand feeds two MFMAs, one per block: the decode, which is what limits the kernel, is paid
 // once for 32 rows.  With PASSES the kept sums take 1 KB per tile and row block.
 // GS: per-group scales (Sec. 3.3, CPU inference: one fp16 scale per block along K; App. on the
-// GPU kernel: scales kept in a separate buffer) instead of one gamma: the two 256-weight halves
-// of a slice are accumulated apart, each multiplied by the scale of its group and output row.
-// Groups are multiples of 256 weights; the scales lie as [K / group][N].
+// GPU kernel: scales kept in a separate buffer) instead of one gamma: the GS (2 or 4) scale units
+// of a slice, 256 or 128 weights each, are accumulated apart, each multiplied by the scale of its
+// group and output row.  Groups are multiples of 128 weights; the scales lie as [K / group][N].
 template <int T, bool MULTI, bool PASSES, int NB, int GS = 0>
 __global__ void __launch_bounds__(512)
 gemv_stream_kernel(GemvBatch b)

@@ -62,7 +62,7 @@ inline bool gemv_two_blocks(int64_t M, int64_t N, int64_t K)
 hipError_t launch_gemv_jobs(const GemmDesc* jobs, int count, hipStream_t s);
 
 // Per-group scales s[K / group][N] in place of gamma (stream form of the small-M kernel; M in
-// blocks of 16).  Needs what gemv_supports needs and group % 256 == 0, N % 4 == 0.
+// blocks of 16).  Needs what gemv_supports needs and group % 128 == 0, N % 4 == 0.
 bool gemv_gs_supports(int64_t M, int64_t N, int64_t K, int64_t group);
 hipError_t launch_gemv_gs(const __half* x, const uint32_t* Wp, const __half* scales, int64_t group,
                           __half* y, int64_t M, int64_t N, int64_t K, hipStream_t s);
