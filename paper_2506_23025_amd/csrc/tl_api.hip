@@ -30,7 +30,7 @@ inline bool dims_ok(int64_t M, int64_t N, int64_t K)
 
 inline tl_status from_hip(hipError_t e) { return e == hipSuccess ? TL_OK : TL_ERR_HIP; }
 
-// M at and below which the 1.6-bit weight-streaming kernel is used.
+// Most activation rows one launch of the 1.6-bit weight-streaming kernel takes.
 constexpr int64_t kGemvMaxM = 4096;
 
 // Small-M kernel (blocks of 16 or 32 activation rows that each stream W) or LDS-tiled MFMA
@@ -197,9 +197,18 @@ tl_status gemm_1p6(const void* x, const void* Wpacked, uint16_t gamma_fp16_bits,
     const float gamma = tl::half_bits_to_float(gamma_fp16_bits);
     const int64_t stride = static_cast<int64_t>(tl_row_stride_bytes(TL_FMT_1P6BIT, K));
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (M <= tl::kGemvMaxM && tl::gemv3_supports(M, N, K))
-        return tl::from_hip(tl::launch_gemv3(static_cast<const __half*>(x), static_cast<const uint8_t*>(Wpacked),
-                                             stride, gamma, static_cast<__half*>(y), M, N, K, fx, s));
+    if (tl::gemv3_supports(M < tl::kGemvMaxM ? M : tl::kGemvMaxM, N, K)) {
+        // more rows than one launch takes: one launch per kGemvMaxM rows
+        const __half* xh = static_cast<const __half*>(x);
+        __half* yh = static_cast<__half*>(y);
+        for (int64_t m0 = 0; m0 < M; m0 += tl::kGemvMaxM) {
+            const int64_t rows = M - m0 < tl::kGemvMaxM ? M - m0 : tl::kGemvMaxM;
+            const hipError_t e = tl::launch_gemv3(xh + m0 * K, static_cast<const uint8_t*>(Wpacked), stride, gamma,
+                                                  yh + m0 * N, rows, N, K, fx, s);
+            if (e != hipSuccess) return tl::from_hip(e);
+        }
+        return TL_OK;
+    }
     return tl::from_hip(tl::launch_gemm3_generic(static_cast<const __half*>(x),
                                                  static_cast<const uint8_t*>(Wpacked), stride, gamma,
                                                  static_cast<__half*>(y), M, N, K, fx, s));
