@@ -519,6 +519,16 @@ gemv_stream_kernel(GemvBatch b)
     uint32_t sc_off[H] = {};                   // GS: byte offset of the units' groups in the scales
     // GS == 4: all ones in the lanes whose k lies in the first (second) unit of an MFMA's range
     const uint32_t pair_mask[2] = {(lane >> 5) == 0 ? 0xFFFFFFFFu : 0u, (lane >> 5) == 1 ? 0xFFFFFFFFu : 0u};
+    auto chunk_offset = [&](int sl) {
+        int chunk = sl * 8 + lc;                           // 16-byte chunk of this lane within the row
+        if (chunk >= J.chunks) chunk = 0;                  // past K: multiplied by zero activations
+        return uint32_t(chunk) * 16u;
+    };
+    // Several passes, one row block of at most 4 rows: the next pass's activation rows are fetched
+    // into registers while the last item of this pass is worked on (plain loads, so the compiler's
+    // wait counts stay exact), and that item refills with the next pass's first weights.
+    constexpr bool kAheadOk = PASSES && NB == 1 && GS == 0;
+    u32x4 xpre[kAheadOk ? 4 : 1];
     auto issue_w = [&](int first, int t) {
         int tile = first + t;
         if (tile >= tile_end) tile = tile_end - 1;         // past the run: its last tile again, never stored
@@ -546,14 +556,12 @@ gemv_stream_kernel(GemvBatch b)
         for (int hh = 0; hh < H; ++hh) nsx[nb][hh] = f32x4{0.f, 0.f, 0.f, 0.f};
     // Start of a pass: fetch this wave's activation slice and the first item's weights together,
     // then turn the activations into operand registers.
-    auto begin_pass = [&](int pass) {
+    // ahead_here: the end of the pass before has requested this pass's activation rows (into xpre)
+    // and its first item's weights already.
+    auto begin_pass = [&](int pass, bool ahead_here) {
     slice = pass * NW + wave;
     active = slice < J.slices;
-    {
-        int chunk = slice * 8 + lc;                        // 16-byte chunk of this lane within the row
-        if (chunk >= J.chunks) chunk = 0;                  // past K: multiplied by zero activations
-        col_off = uint32_t(chunk) * 16u;
-    }
+    if (!ahead_here) col_off = chunk_offset(slice);
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
@@ -584,7 +592,13 @@ gemv_stream_kernel(GemvBatch b)
             typedef const __attribute__((address_space(1))) unsigned char* gbytes;
             const size_t row_stride = size_t(J.K) * 2;
             gbytes src = (gbytes)(J.xb + size_t(16 * nb) * row_stride + size_t(slice) * (kSliceK * 2));
-            if ((slice + 1) * kSliceK <= J.K) {            // the whole slice lies inside K
+            if (kAheadOk && ahead_here) {
+                if constexpr (kAheadOk) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        if (r < rows) *reinterpret_cast<u32x4*>(my_lds + r * 1024 + (uint32_t(lane) << 4)) = xpre[r];
+                }
+            } else if ((slice + 1) * kSliceK <= J.K) {     // the whole slice lies inside K
                 const uint32_t lane16 = uint32_t(lane) << 4;
 #pragma unroll 1
                 for (int r = 0; r < rows; ++r) {
@@ -605,7 +619,9 @@ gemv_stream_kernel(GemvBatch b)
                     src += row_stride;
                 }
             }
-            if (nb == 0) {
+            if (kAheadOk && ahead_here) {
+                // nothing to request; the registers' own loads are waited for by the compiler
+            } else if (nb == 0) {
 #pragma unroll
                 for (int t = 0; t < T; ++t) issue_w(tile0, t);
                 // the compiler does not track LDS-DMA: wait until only the 2T weight loads are outstanding
@@ -669,7 +685,7 @@ gemv_stream_kernel(GemvBatch b)
     // One item (tiles first .. first + T - 1): tile t goes through LDS region t & 1 into MFMA
     // order, is decoded and multiplied; REFILL: its registers are loaded again at once for the
     // next item.  Tiles past the run are computed from whatever was loaded and never stored.
-    auto item = [&](auto refill_tag, int first, int parity, bool first_pass_rt, bool last_pass_rt) {
+    auto item = [&](auto refill_tag, int first, int refill_first, int parity, bool first_pass_rt, bool last_pass_rt) {
         constexpr bool REFILL = decltype(refill_tag)::value;
         const bool first_pass = PASSES ? first_pass_rt : true;
         const bool last_pass = PASSES ? last_pass_rt : true;
@@ -687,7 +703,7 @@ gemv_stream_kernel(GemvBatch b)
                 f16x4 sc_cur[H];                           // this tile's scales, before the refill replaces them
 #pragma unroll
                 for (int hh = 0; hh < H; ++hh) sc_cur[hh] = sreg[t][hh];
-                if constexpr (REFILL) issue_w(first + T, t);
+                if constexpr (REFILL) issue_w(refill_first, t);
                 if (REFILL || first + t < tile_end) {      // the last item may be short
                     f32x4 acc[NB][H][3];
 #pragma unroll
@@ -790,12 +806,33 @@ gemv_stream_kernel(GemvBatch b)
         }
     };
 
+    bool ahead_here = false;
     for (int pass = 0; pass < n_pass; ++pass) {
         const bool first_pass = pass == 0, last_pass = pass + 1 == n_pass;
-        begin_pass(PASSES ? pass : 0);
+        begin_pass(PASSES ? pass : 0, ahead_here);
+        ahead_here = false;
         int i = 0;
-        for (; i + 1 < n_items; ++i) item(std::true_type{}, tile0 + i * T, i & 1, first_pass, last_pass);
-        item(std::false_type{}, tile0 + i * T, i & 1, first_pass, last_pass);
+        for (; i + 1 < n_items; ++i) item(std::true_type{}, tile0 + i * T, tile0 + (i + 1) * T, i & 1, first_pass, last_pass);
+        bool cross = false;
+        if constexpr (kAheadOk) {
+            const int next_slice = (pass + 1) * NW + wave;
+            cross = !last_pass && active && next_slice < J.slices && J.Mrem <= 4;
+            if (cross) {
+                typedef const __attribute__((address_space(1))) unsigned char* gbytes;
+                gbytes src = (gbytes)(J.xb + size_t(next_slice) * (kSliceK * 2));
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int piece = lane ^ (r & 7);      // the staging order of begin_pass
+                    xpre[r] = u32x4{0u, 0u, 0u, 0u};
+                    if (r < J.Mrem && next_slice * kSliceK + piece * 8 < J.K)
+                        xpre[r] = *(gptr)(src + size_t(r) * (size_t(J.K) * 2) + uint32_t(piece) * 16u);
+                }
+                col_off = chunk_offset(next_slice);
+                item(std::true_type{}, tile0 + i * T, tile0, i & 1, first_pass, last_pass);
+                ahead_here = true;
+            }
+        }
+        if (!cross) item(std::false_type{}, tile0 + i * T, 0, i & 1, first_pass, last_pass);
         if (PASSES && !last_pass) {
             // the next pass stages activations over the partial-sum sets: everybody must be done reading
             __builtin_amdgcn_s_waitcnt(0xF | (0x3 << 14) | (0x7 << 4));
@@ -878,7 +915,8 @@ struct GemvPolicy {
     int stream_groups = 256;            // workgroups of the stream form (one per CU)
     int two_blocks = 1;                 // jobs of more than 16 rows go in blocks of 32 (two row blocks per wave)
     double start_up_per_row = 0.15;     // stream form: start-up of a pass in tiles per activation row
-    double pass_start = 3.0;            // stream form: wait of every pass but the first for its activations, in tiles
+    double pass_start = 1.5;            // stream form: wait of every pass but the first for its activations, in tiles
+    int item_cost = 1;                  // stream form: allocation counts items, not only tiles
     int t_stream = 0;                   // stream form: cap on tiles per item (0: none)
     int long_k_min_run = 3;             // K > 4096 streams if the call averages this many tile passes per workgroup
 };
@@ -916,13 +954,29 @@ hipError_t launch_stream(GemvBatch& b, int max_slices, int nb, hipStream_t s, in
         const int rows = b.job[j].Mrem < 16 * nb ? b.job[j].Mrem : 16 * nb;
         return pol.start_up_per_row * double(rows) + (passes(j) > 1 ? pol.pass_start : 0.0);
     };
+    // A run is worked off in items of up to t_max tiles (4 tiles: 2 + 2), and an item costs its
+    // latency and barrier once: measured (block launch, runs of 15 ... 19 tiles) 1.0 us for the
+    // first tile of an item and 0.2 us for each further one, i.e. 2.1 and 0.43 in units of an average tile.
+    const int t_max = (nb == 2 || gs == 4) ? 2 : 3;
+    auto run_time = [&](int run) {
+        if (!pol.item_cost) return double(run);
+        const int items = run <= t_max ? 1 : ((t_max == 3 && run == 4) ? 2 : (run + t_max - 1) / t_max);
+        return 2.1 * double(items) + 0.43 * double(run - items);
+    };
     auto run_cost = [&](int j, int w) {
-        return double(passes(j)) * (double((b.job[j].tiles + w - 1) / w) + start_up(j));
+        return double(passes(j)) * (run_time((b.job[j].tiles + w - 1) / w) + start_up(j));
     };
     auto groups_for = [&](int j, double tau) {            // fewest groups that finish job j by tau
         const double per = tau / double(passes(j)) - start_up(j);
-        if (per < 1.0) return b.job[j].tiles;
-        const int w = int((double(b.job[j].tiles) + per - 1.0) / per);
+        // longest run that fits: from the estimate with whole items, a few steps up or down
+        const double per_tile = pol.item_cost ? (2.1 + 0.43 * double(t_max - 1)) / double(t_max) : 1.0;
+        int run = int(per / per_tile);
+        if (run < 1) run = 1;
+        if (run > b.job[j].tiles) run = b.job[j].tiles;
+        while (run > 1 && run_time(run) > per) --run;
+        while (run < b.job[j].tiles && run_time(run + 1) <= per) ++run;
+        if (run_time(run) > per) return b.job[j].tiles;
+        const int w = (b.job[j].tiles + run - 1) / run;
         return w < 1 ? 1 : (w > b.job[j].tiles ? b.job[j].tiles : w);
     };
     double lo = 0.0, hi = 0.0;
@@ -1094,6 +1148,7 @@ extern "C" void tl_dev_two_blocks(int on) { g_policy.two_blocks = on; }
 extern "C" void tl_dev_stream_t(int t) { g_policy.t_stream = t; }
 extern "C" void tl_dev_start_up(double v) { g_policy.start_up_per_row = v; }
 extern "C" void tl_dev_pass_start(double v) { g_policy.pass_start = v; }
+extern "C" void tl_dev_item_cost(int on) { g_policy.item_cost = on; }
 #endif
 
 // Raises the dynamic-LDS limit of every kernel instance of this file on the current device (the
