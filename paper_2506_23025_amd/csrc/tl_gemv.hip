@@ -917,6 +917,8 @@ struct GemvPolicy {
     double start_up_per_row = 0.15;     // stream form: start-up of a pass in tiles per activation row
     double pass_start = 1.5;            // stream form: wait of every pass but the first for its activations, in tiles
     int item_cost = 1;                  // stream form: allocation counts items, not only tiles
+    double item_first = 2.1;            // cost of the first tile of an item, in average tiles
+    double tile_extra = 0.43;           // cost of each further tile of an item
     int t_stream = 0;                   // stream form: cap on tiles per item (0: none)
     int long_k_min_run = 3;             // K > 4096 streams if the call averages this many tile passes per workgroup
 };
@@ -961,7 +963,7 @@ hipError_t launch_stream(GemvBatch& b, int max_slices, int nb, hipStream_t s, in
     auto run_time = [&](int run) {
         if (!pol.item_cost) return double(run);
         const int items = run <= t_max ? 1 : ((t_max == 3 && run == 4) ? 2 : (run + t_max - 1) / t_max);
-        return 2.1 * double(items) + 0.43 * double(run - items);
+        return pol.item_first * double(items) + pol.tile_extra * double(run - items);
     };
     auto run_cost = [&](int j, int w) {
         return double(passes(j)) * (run_time((b.job[j].tiles + w - 1) / w) + start_up(j));
@@ -969,7 +971,7 @@ hipError_t launch_stream(GemvBatch& b, int max_slices, int nb, hipStream_t s, in
     auto groups_for = [&](int j, double tau) {            // fewest groups that finish job j by tau
         const double per = tau / double(passes(j)) - start_up(j);
         // longest run that fits: from the estimate with whole items, a few steps up or down
-        const double per_tile = pol.item_cost ? (2.1 + 0.43 * double(t_max - 1)) / double(t_max) : 1.0;
+        const double per_tile = pol.item_cost ? (pol.item_first + pol.tile_extra * double(t_max - 1)) / double(t_max) : 1.0;
         int run = int(per / per_tile);
         if (run < 1) run = 1;
         if (run > b.job[j].tiles) run = b.job[j].tiles;
@@ -1149,6 +1151,7 @@ extern "C" void tl_dev_stream_t(int t) { g_policy.t_stream = t; }
 extern "C" void tl_dev_start_up(double v) { g_policy.start_up_per_row = v; }
 extern "C" void tl_dev_pass_start(double v) { g_policy.pass_start = v; }
 extern "C" void tl_dev_item_cost(int on) { g_policy.item_cost = on; }
+extern "C" void tl_dev_item_model(double first, double extra) { g_policy.item_first = first; g_policy.tile_extra = extra; }
 #endif
 
 // Raises the dynamic-LDS limit of every kernel instance of this file on the current device (the
