@@ -947,11 +947,11 @@ hipError_t launch_stream(GemvBatch& b, int max_slices, int nb, hipStream_t s, in
     // workgroups, so that a CU still runs 8 waves (K = 1024: 1024 workgroups of 2 waves).
     const int64_t g_max = int64_t(pol.stream_groups) * (kStreamWaves / NW);
     const int G = total_tiles < g_max ? int(total_tiles) : int(g_max);
-    // Time of a workgroup of job j with w groups, in tile units: passes x (run + start-up).  The
-    // start-up of a pass is fetching the activation slice (1 KB per row and wave through the
+    // Time of a workgroup of job j with w groups, in tile units: passes x (run time + start-up).
+    // The start-up of a pass is fetching the activation slice (1 KB per row and wave through the
     // same address path as the weights) and building the operands: measured about 0.15 tiles per
-    // activation row; a job of several passes waits for that round trip in every pass but the
-    // first, counted as 3 tiles more.  Bisection on the common finishing time gives the group counts.
+    // activation row; a job of several passes pays part of that round trip in every pass but the
+    // first (pass_start tiles).  Bisection on the common finishing time gives the group counts.
     auto start_up = [&](int j) {
         const int rows = b.job[j].Mrem < 16 * nb ? b.job[j].Mrem : 16 * nb;
         return pol.start_up_per_row * double(rows) + (passes(j) > 1 ? pol.pass_start : 0.0);
