@@ -349,7 +349,7 @@ def main():
             raise tl.TlError(st, "tl_probe_read")
 
     us_probe = timed(probe_step, args.steps) * 1e3 / args.steps
-    roofline = dict(bound="hbm", kernel="gemv_stream_kernel<3, true, false, 1>, grouped launch of the ten GEMMs of a step",
+    roofline = dict(bound="hbm", kernel="gemv_stream_kernel<3, true, false, 1, 0>, grouped launch of the ten GEMMs of a step",
                     achieved=round(step_bytes / us_launch / 1e3, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(step_bytes / us_launch / 1e3 / HBM_PEAK_GBS, 4),
                     bytes_per_launch=step_bytes, us_per_launch=round(us_launch, 3), traffic=traffic,
