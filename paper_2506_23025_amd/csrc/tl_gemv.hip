@@ -1035,9 +1035,8 @@ hipError_t launch_stream(GemvBatch& b, int max_slices, int nb, hipStream_t s, in
         b.job[j].pad[1] = b.job[j].tiles % wg[j];
         grid += wg[j];
     }
-    const int total_items = 0;
     const size_t lds = size_t(NW) * stream_wave_lds(T * nb) + (multi_pass ? size_t(kStreamMaxRun) * 1024 : 0);
-    b.total_items = total_items;
+    b.total_items = 0;                                 // the stream form has no item queue
     b.red_off = 0;
     b.pad = 0;
     const bool multi = gs != 0 || b.count > 1;         // the scaled form always reads the job table
