@@ -41,7 +41,8 @@ constexpr int64_t kGemvMaxM = 4096;
 //    passes x (8.7 + 0.88 x its longest run of tiles per workgroup)
 //    (11008 -> 4096: 16 blocks 68 us, 8 blocks 47 us)
 //  * small-M, blocks of 16 rows: 3.8 + blocks x W x (0.17 while W stays in the L2 caches, 0.21
-//    beyond, 0.264 when K needs several passes), at least 0.5 per block
+//    beyond), at least 0.3 per block; when K needs several passes 1 + 3 passes + blocks x 0.175 W
+//    (11008 -> 4096: 2 blocks 13.7 us, 16 blocks 44.2 us)
 //  * MFMA, 128 x 128 tiles (at most one per CU): 7 + K/64 x (0.43 + 0.09 (tiles - 128)/128 beyond 128
 //    tiles) with two sets of waves per tile (K % 128 == 0), else 4 + K/64 x (0.53 + 0.04 tiles/256)
 //  * MFMA, 128 x 256 tiles: (5 + K/64 x 0.86) x f(tiles/256), f(r) = 1 up to one tile per CU, then
@@ -63,9 +64,11 @@ inline bool prefer_small_m(int64_t M, int64_t N, int64_t K)
         t_small = double(blocks / cap) * launch_us(cap) + (blocks % cap ? launch_us(blocks % cap) : 0.0);
     } else if (tl::gemv_two_blocks(M, N, K)) {
         t_small = 4.0 + double((M + 31) / 32) * (0.31 + 0.2 * w_mb);
+    } else if (slices > 8) {
+        t_small = 1.0 + 3.0 * double((slices + 7) / 8) + double((M + 15) / 16) * 0.175 * w_mb;
     } else {
-        const double per_mb = slices > 8 ? 0.264 : (w_mb < 8.4 ? 0.17 : 0.21);
-        const double per_block = per_mb * w_mb > 0.5 ? per_mb * w_mb : 0.5;
+        const double per_mb = w_mb < 8.4 ? 0.17 : 0.21;
+        const double per_block = per_mb * w_mb > 0.3 ? per_mb * w_mb : 0.3;
         t_small = 3.8 + double((M + 15) / 16) * per_block;
     }
     const double steps = double(K / 64);

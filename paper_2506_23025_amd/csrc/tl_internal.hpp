@@ -45,17 +45,21 @@ bool gemv_supports(int64_t M, int64_t N, int64_t K);
 hipError_t launch_gemv(const __half* x, const uint32_t* Wp, float gamma, __half* y,
                        int64_t M, int64_t N, int64_t K, hipStream_t s);
 // Whether the small-M kernel takes a GEMM in blocks of 32 activation rows (every decoded weight
-// operand feeds two MFMAs) rather than 16.  It halves the passes over W but shortens the items,
-// which pays when W is re-read from beyond the L2 cache or the blocks are many (measured:
-// 4096 -> 14336 from M = 64 on, 4096 -> 4096 from M = 384 on).  K up to 64 slices (32768).
+// operand feeds two MFMAs) rather than 16.  It halves the passes over W but shortens the items
+// (2 tiles instead of 3), which pays when W is large or the blocks are many.  Measured, blocks of
+// 32 against blocks of 16 rows (us): 4096 -> 22016 (22.5 MB) M = 17 11.0 / 12.7, M = 64 17.7 / 20.3;
+// 4096 -> 14336 (14.7 MB) M = 48 14.5 / 13.7, M = 64 13.7 / 14.2, M = 128 19.0 / 22.2;
+// 4096 -> 4096 (4.2 MB) M = 192 13.8 / 13.9, M = 256 13.6 / 14.9; 2048 -> 2048 never.
+// Several passes over K (up to 64 slices, 32768): 11008 -> 4096 M = 256 45.1 / 42.7,
+// M = 384 59.6 / 65.5; the run of a workgroup must fit its LDS.
 inline bool gemv_two_blocks(int64_t M, int64_t N, int64_t K)
 {
     const int64_t slices = (K + 511) / 512;
     if (M <= 16 || slices < 2 || slices > 64) return false;
-    // several passes over K: the run of a workgroup must fit its LDS, and the gain starts at M = 128
-    // (11008 -> 4096: M = 64 24.0 against 21.5 us, M = 128 28.6 against 29.3 us, M = 512 65 against 95 us)
-    if (slices > 8 && ((N + 15) / 16 > 256 * 16 || M < 128)) return false;
-    return (M >= 64 && N * K / 4 >= (int64_t(8) << 20)) || M >= 384;
+    if (slices > 8) return (N + 15) / 16 <= 256 * 16 && M >= 384;
+    const int64_t w_bytes = N * K / 4;
+    return w_bytes >= (int64_t(18) << 20) || (M >= 64 && w_bytes >= (int64_t(8) << 20)) ||
+           (M >= 256 && w_bytes >= (int64_t(2) << 20));
 }
 
 // Several independent GEMMs (each passing gemv_supports) in as few launches as possible.
