@@ -159,6 +159,20 @@ def test_auto_path_full_size_sampled_columns():
     assert_close(y[:, cols], ref, x, g, "full size sampled")
 
 
+@pytest.mark.parametrize("M", [17, 33, 48])
+def test_large_w_just_over_16_rows_sampled_columns(M):
+    # W of 18.9 MB: the small-M kernel takes M > 16 in blocks of 32 rows from M = 17 on (a job of
+    # 17 rows is one full block of 16 and one block with a single row); 384 sampled columns
+    N, K = 18432, 4096
+    x, W, g = si.layer(31000 + M, M, N, K)
+    Wp = tl.tl_pack_2bit(W)
+    y = run_gemm(x, Wp, g, N, K)
+    cols = np.sort(np.random.default_rng(M).choice(N, 384, replace=False))
+    cols[-1] = N - 1
+    ref = oracle.gemm(x, np.ascontiguousarray(W[cols]), g)
+    assert_close(y[:, cols], ref, x, g, f"large W, M={M}")
+
+
 def test_config1_square_2048():
     # config 1: 2048 -> 2048, M = 1, gamma = fp16(0.02); the whole matrix against the oracle
     M, N, K = 1, 2048, 2048
