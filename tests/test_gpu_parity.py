@@ -325,6 +325,29 @@ def test_grouped_matches_oracle_and_single_calls():
         assert_close(y1, y.astype(np.float64), x, g, "grouped vs single")
 
 
+@pytest.mark.parametrize("M", [1, 3, 4, 5])
+def test_grouped_long_k_several_passes(M):
+    # K beyond one pass of 8 slices, enough tiles in the call for the streaming form: passes whose
+    # last one has 1, 2, 6 or 8 active waves, a K that ends inside a slice, ragged N; up to 4 rows
+    # the next pass's activations are fetched ahead, M = 5 takes the plain path
+    import torch
+    specs = [(M, 4096, 4160), (M, 4100, 5120), (M, 4096, 11008), (M, 2048, 8192), (M, 1000, 9024)]
+    host, dev, jobs = [], [], []
+    for i, (m, N, K) in enumerate(specs):
+        x, W, g = si.layer(7700 + 10 * M + i, m, N, K)
+        Wp = tl.tl_pack_2bit(W)
+        xd, wd = to_dev(x.view(np.int16)), dev_u32(Wp)
+        yd = torch.full((m, N), -21555, dtype=torch.int16, device="cuda")
+        host.append((x, Wp, g))
+        dev.append(yd)
+        jobs.append((xd, wd, si.gamma_bits(g), yd, m, N, K))
+    tl.tl_ternary_gemm_grouped(jobs)
+    torch.cuda.synchronize()
+    for (m, N, K), (x, Wp, g), yd in zip(specs, host, dev):
+        y = yd.cpu().numpy().view(np.float16)
+        assert_close(y, oracle.gemm_packed2(x, Wp, g, K), x, g, f"grouped long K {m}x{N}x{K}")
+
+
 def test_grouped_many_small_k_jobs():
     # more jobs than one launch carries, all of them short enough in K for the kernel form that
     # keeps a wave's activations in registers: ragged N and M, a K slice that ends inside a
