@@ -173,6 +173,20 @@ def test_large_w_just_over_16_rows_sampled_columns(M):
     assert_close(y[:, cols], ref, x, g, f"large W, M={M}")
 
 
+@pytest.mark.parametrize("M,N,K", [(1, 1 << 20, 64), (2, 16, 1 << 20), (100000, 16, 64), (3, 33, 262144 + 64)])
+def test_extreme_dimensions_sampled(M, N, K):
+    # one dimension near what the entry point takes, the others small: a million output rows, a
+    # million-long K (2048 slices through the general kernel), a hundred thousand activation rows
+    x, W, g = si.layer(9900 + M % 97 + N % 89 + K % 83, M, N, K)
+    Wp = tl.tl_pack_2bit(W)
+    y = run_gemm(x, Wp, g, N, K)
+    rows = np.unique(np.concatenate([[0, M - 1], np.random.default_rng(1).integers(0, M, 6)]))
+    cols = np.unique(np.concatenate([[0, N - 1], np.random.default_rng(2).integers(0, N, 300)]))
+    xs = np.ascontiguousarray(x[rows])
+    ref = oracle.gemm(xs, np.ascontiguousarray(W[cols]), g)
+    assert_close(y[np.ix_(rows, cols)], ref, xs, g, f"extreme {M}x{N}x{K}")
+
+
 def test_config1_square_2048():
     # config 1: 2048 -> 2048, M = 1, gamma = fp16(0.02); the whole matrix against the oracle
     M, N, K = 1, 2048, 2048
