@@ -841,6 +841,235 @@ gemv_stream_kernel(GemvBatch b)
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Lean stream kernel: the stream form for launches in which every job takes one pass over K with
+// the same number of 512-weight slices (= waves per workgroup), one block of at most 16
+// activation rows, one gamma, and N a multiple of 16 -- the decode shapes.  What differs from
+// gemv_stream_kernel is the way in and the loop, not the arithmetic:
+//  * Every workgroup has a 64-byte record of its own in the kernel arguments (pointers of its job,
+//    first tile and length of its run), read with one scalar load at an address that depends on
+//    the workgroup index alone: no table search stands between the kernel entry and the first
+//    requests, and one- and many-job launches run the same code.
+//  * A lane's two weight addresses within a tile are computed once; a tile's loads are that
+//    offset on a scalar base which steps from tile to tile, so the loop spends no vector
+//    instructions on addresses.
+//  * Every wave is active in every tile (no predicated tile bodies); the last item comes in one
+//    copy per tile count.
+// The vector ALU is what limits the steady state of these kernels (64 ANDs + 16 shifts + 16 MFMA
+// issues + 12 combine operations per wave and tile are 108 of the ~120 issue slots a tile may
+// take if the loop is to keep up with HBM), so every instruction that is not decode counts.
+constexpr int kLeanMaxGroups = 256;
+
+struct WgRec {                    // 64 bytes; rec[blockIdx.x] is read with scalar loads
+    const unsigned char* W;       // packed row 0 of the first tile of the run
+    const unsigned char* x;       // activations of the job, fp16 [Mrem][K]
+    __half* y;                    // outputs of the job, fp16 [Mrem][N]
+    float gamma;
+    int K, N;
+    int Mrem;                     // 1..16
+    int tile0, ntiles;            // the run: tiles tile0 .. tile0 + ntiles - 1 of the job (ntiles >= 1)
+    int pad[4];
+};
+static_assert(sizeof(WgRec) == 64, "one record per 64-byte line");
+
+struct LeanBatch {
+    WgRec rec[kLeanMaxGroups];
+};
+
+template <int T>
+__global__ void __launch_bounds__(512)
+gemv_lean_kernel(LeanBatch b)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int NW = blockDim.x >> 6;
+    constexpr int kStride = stream_wave_lds(T);
+    unsigned char* const my_lds = lds_raw + wave * kStride;
+    typedef const __attribute__((address_space(1))) unsigned char* gbytes;
+
+    const WgRec& R = b.rec[blockIdx.x];
+    const int K = R.K, N = R.N, rows = R.Mrem, ntiles = R.ntiles;
+    const unsigned char* const Wrun = R.W;
+    const uint32_t row_bytes = uint32_t(K) >> 2;
+    const uint32_t tile_bytes = 16u * row_bytes;
+
+    const int lr = lane >> 3, lc = lane & 7;   // load mapping: row of the half tile, chunk of the slice
+    const int mi = lane & 15, mg = lane >> 4;  // MFMA mapping: row / activation column, k group
+
+    // ---- activations of this wave's slice: LDS-DMA, swizzled (lane l fetches piece l ^ (r & 7) of row r)
+    {
+        const size_t row_stride = size_t(K) * 2;
+        gbytes src = (gbytes)(R.x + size_t(wave) * (kSliceK * 2));
+        if ((wave + 1) * kSliceK <= K) {                    // the whole slice lies inside K
+            const uint32_t lane16 = uint32_t(lane) << 4;
+#pragma unroll 1
+            for (int r = 0; r < rows; ++r) {
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + (lane16 ^ (uint32_t(r & 7) << 4))),
+                                                 (__attribute__((address_space(3))) void*)(my_lds + r * 1024), 16, 0, 0);
+                src += row_stride;
+            }
+        } else {
+#pragma unroll 1
+            for (int r = 0; r < rows; ++r) {
+                const int kk = (lane ^ (r & 7)) << 3;      // first of this lane's 8 activations within the slice
+                if (wave * kSliceK + kk < K) {
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + uint32_t(kk) * 2u),
+                                                     (__attribute__((address_space(3))) void*)(my_lds + r * 1024), 16, 0, 0);
+                } else {
+                    *reinterpret_cast<u32x4*>(my_lds + r * 1024 + (uint32_t(lane) << 4)) = u32x4{0u, 0u, 0u, 0u};
+                }
+                src += row_stride;
+            }
+        }
+    }
+    // ---- weights: the lane's two 16-byte pieces of a tile, relative to the tile's first row
+    uint32_t chunk = uint32_t(wave) * 8u + uint32_t(lc);
+    if (chunk >= (uint32_t(K) >> 6)) chunk = 0;            // past K: multiplied by zero activations
+    const uint32_t voff0 = uint32_t(lr) * row_bytes + chunk * 16u;
+    const uint32_t voff1 = voff0 + 8u * row_bytes;
+    // the run as a raw buffer (no stride, byte offsets, size = the run): base in scalar registers
+    const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(Wrun), 0, uint32_t(ntiles) * tile_bytes, 0x00020000);
+    u32x4 wreg[T][2];
+    auto issue_w = [&](int idx, int t) {                   // idx: tile of the run; past the run: its last tile again
+        const int c = idx < ntiles ? idx : ntiles - 1;
+        // Buffer loads: descriptor and tile offset are scalar, the lane offset is a register that
+        // never changes, so a request costs the vector ALU nothing.  That matters beyond the
+        // instruction count: a wave whose data has arrived must get its next request out while
+        // the other wave of its SIMD keeps the vector ALU busy.
+        const uint32_t so = uint32_t(c) * tile_bytes;
+        wreg[t][0] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(wres, voff0, so, 2));   // 2: nt
+        wreg[t][1] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(wres, voff1, so, 2));
+    };
+    // in tile order, and kept so: the loop's wait counts are the worse of this order and its own
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+        issue_w(t, t);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    // the compiler does not track LDS-DMA: wait until only the 2T weight loads are outstanding
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * T));
+
+    // ---- activations -> MFMA B operands (see gemv_stream_kernel) and the -sum(x) seed ----------
+    uint32_t breg[2][4][8];
+    f32x4 nsx = f32x4{0.f, 0.f, 0.f, 0.f};
+    {
+        int mr = 1;
+        while (mr < rows) mr *= 2;
+        const int xrow = mi & (mr - 1);
+        const uint32_t xr_off = uint32_t(xrow) * 1024u + uint32_t(mg) * 128u;
+        const uint32_t sw = uint32_t(xrow & 7);
+        const bool live = mi < rows;
+        const uint32_t sel_lo = live ? 0x05040100u : 0x0c0c0c0cu;
+        const uint32_t sel_hi = live ? 0x07060302u : 0x0c0c0c0cu;
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int wd = 0; wd < 4; ++wd) {
+                const u32x4 lo = *reinterpret_cast<const u32x4*>(my_lds + xr_off + h * 512 + ((uint32_t(2 * wd) ^ sw) << 4));
+                const u32x4 hi = *reinterpret_cast<const u32x4*>(my_lds + xr_off + h * 512 + ((uint32_t(2 * wd + 1) ^ sw) << 4));
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    breg[h][wd][2 * r] = __builtin_amdgcn_perm(hi[r], lo[r], sel_lo);
+                    breg[h][wd][2 * r + 1] = __builtin_amdgcn_perm(hi[r], lo[r], sel_hi);
+                }
+            }
+        const uint32_t c = 0x80108010u;                   // fp16 pair of -2^-20
+        const u32x4 a = u32x4{c, c, c, c};
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const u32x4 bb = u32x4{breg[h][0][e], breg[h][1][e], breg[h][2][e], breg[h][3][e]};
+                nsx = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), as_f16x8(bb), nsx, 0, 0, 0);
+            }
+    }
+
+    const uint32_t ww_off = uint32_t(lr) * 128u + (uint32_t(lc ^ lr) << 4);
+    const uint32_t wr_off0 = uint32_t(mi) * 128u + (uint32_t((mg) ^ (mi & 7)) << 4);
+    const uint32_t wr_off1 = uint32_t(mi) * 128u + (uint32_t((4 + mg) ^ (mi & 7)) << 4);
+    const float gamma = R.gamma;
+    typedef __attribute__((address_space(1))) __half* gh_ptr;
+    // the output quad this thread owns in an item's epilogue: tile t = threadIdx.x / 64 of the item
+    const int ot = int(threadIdx.x) >> 6;
+    const uint32_t ycol = uint32_t(R.tile0) * 16u + 4u * uint32_t(mg);       // + 16 (first + ot)
+    gh_ptr const yrow = (gh_ptr)(R.y + size_t(mi) * size_t(N));
+
+    // One item of NT tiles starting at tile `first` of the run.  REFILL: each tile's registers are
+    // loaded again at once with the tile T further on.
+    auto item = [&](auto nt_tag, auto refill_tag, int first, int parity) {
+        constexpr int NT = decltype(nt_tag)::value;
+        constexpr bool REFILL = decltype(refill_tag)::value;
+        f32x4 part[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            unsigned char* const reg_t = my_lds + (t & 1) * 2048;
+            // Writing a tile to LDS and asking for the tile that takes its registers is a handful
+            // of LDS, scalar and memory instructions; they run at raised priority so that they do
+            // not queue behind the other wave's decode (measured: decode sweep 17.55 -> 17.2 us).
+            if constexpr (REFILL) __builtin_amdgcn_s_setprio(3);
+            *reinterpret_cast<u32x4*>(reg_t + ww_off) = wreg[t][0];
+            *reinterpret_cast<u32x4*>(reg_t + 1024 + ww_off) = wreg[t][1];
+            if constexpr (REFILL) {
+                issue_w(first + T + t, t);
+                __builtin_amdgcn_s_setprio(0);
+                // the requests leave here, as soon as the registers are free: left to itself the
+                // scheduler sinks all of an item's loads to its end, which costs two tiles of lead
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            f32x4 acc[3];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const u32x4 wv = *reinterpret_cast<const u32x4*>(reg_t + (h ? wr_off1 : wr_off0));
+                // element e of each half-word sits at bits 2e, 2e+1; the mantissa bits 4..9 (classes
+                // 0..2 -> accumulators) hold e = 2,3,4 as loaded, e = 0,1 after << 4 and e = 5,6,7 after >> 6
+                const u32x4 sh[3] = {wv << 4, wv, wv >> 6};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int src = e < 2 ? 0 : (e < 5 ? 1 : 2);
+                    const int j = e < 2 ? e : (e < 5 ? e - 2 : e - 5);
+                    const uint32_t mask = 0x00300030u << (2 * j);
+                    const u32x4 a = sh[src] & mask;
+                    const u32x4 bb = u32x4{breg[h][0][e], breg[h][1][e], breg[h][2][e], breg[h][3][e]};
+                    // first product of an accumulator: class 0 starts from the -sum(x) seed, the others from zero
+                    const f32x4 c0 = (h == 0 && (e == 0 || e == 1 || e == 4)) ? (j == 0 ? nsx : f32x4{0.f, 0.f, 0.f, 0.f}) : acc[j];
+                    acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), as_f16x8(bb), c0, 0, 0, 0);
+                }
+            }
+            part[t] = acc[0] * 1048576.f + acc[1] * 262144.f + acc[2] * 65536.f;
+        }
+        // split-K: partial sums into this wave's set `parity`, one LDS-only barrier, fixed-order sum
+        unsigned char* const red = my_lds + 4096 + parity * (T * 1024);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) reinterpret_cast<f32x4*>(red + t * 1024)[lane] = part[t];
+        __builtin_amdgcn_s_waitcnt(0xF | (0x3 << 14) | (0x7 << 4));
+        __builtin_amdgcn_s_barrier();
+        if (ot < NT) {
+            f32x4 v[8];
+#pragma unroll
+            for (int w = 0; w < 8; ++w)
+                v[w] = (w < NW) ? reinterpret_cast<const f32x4*>(lds_raw + w * kStride + 4096 + parity * (T * 1024) + ot * 1024)[lane]
+                                : f32x4{0.f, 0.f, 0.f, 0.f};
+            const f32x4 s = ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
+            if (mi < rows) {
+                const f16x2 lo = {(_Float16)(gamma * s[0]), (_Float16)(gamma * s[1])};
+                const f16x2 hi = {(_Float16)(gamma * s[2]), (_Float16)(gamma * s[3])};
+                *(__attribute__((address_space(1))) u32x2*)(yrow + (ycol + 16u * uint32_t(first + ot))) =
+                    u32x2{__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
+            }
+        }
+    };
+
+    const int n_items = (ntiles + T - 1) / T;
+    int i = 0;
+    for (; i + 1 < n_items; ++i)
+        item(std::integral_constant<int, T>{}, std::true_type{}, i * T, i & 1);
+    const int rem = ntiles - i * T;                        // 1 .. T tiles are left
+    if (T == 1 || rem == 1) item(std::integral_constant<int, 1>{}, std::false_type{}, i * T, i & 1);
+    else if (T == 2 || rem == 2) item(std::integral_constant<int, (T >= 2 ? 2 : 1)>{}, std::false_type{}, i * T, i & 1);
+    else item(std::integral_constant<int, T>{}, std::false_type{}, i * T, i & 1);
+}
+
 using KernelFn = void (*)(GemvBatch);
 
 template <bool MULTI>
@@ -921,12 +1150,59 @@ struct GemvPolicy {
     double tile_extra = 0.43;           // cost of each further tile of an item
     int t_stream = 0;                   // stream form: cap on tiles per item (0: none)
     int long_k_min_run = 3;             // K > 4096 streams if the call averages this many tile passes per workgroup
+    int lean = 1;                       // launches the lean kernel can take go to it
 };
 GemvPolicy g_policy;
 
 constexpr int kStreamWaves = 8;         // waves of a stream-form workgroup when K >= 4096
 constexpr int kStreamMaxPasses = 8;     // passes over K the stream form takes: K <= 32768
 constexpr int kStreamMaxRun = 32;       // tiles of a run whose sums fit the 32 KB of LDS left over
+
+using LeanFn = void (*)(LeanBatch);
+
+LeanFn pick_lean(int T)
+{
+    switch (T) {
+        case 1: return gemv_lean_kernel<1>;
+        case 2: return gemv_lean_kernel<2>;
+        default: return gemv_lean_kernel<3>;
+    }
+}
+
+// Launch of the lean kernel: wg[j] workgroups for job j, each with a run of consecutive tiles
+// (the first tiles % wg[j] of them one tile longer), written out as one record per workgroup.
+hipError_t launch_lean(const GemvBatch& b, const int* wg, int NW, int T, hipStream_t s)
+{
+    LeanBatch lb;
+    int grid = 0;
+    for (int j = 0; j < b.count; ++j) {
+        const GemvJob& J = b.job[j];
+        const int per = J.tiles / wg[j], plus = J.tiles % wg[j];
+        const size_t tile_bytes = size_t(16) * (size_t(J.K) / 4);
+        for (int g = 0; g < wg[j]; ++g) {
+            WgRec& r = lb.rec[grid++];
+            r.tile0 = g * per + (g < plus ? g : plus);
+            r.ntiles = per + (g < plus ? 1 : 0);
+            r.W = reinterpret_cast<const unsigned char*>(J.W) + size_t(r.tile0) * tile_bytes;
+            r.x = reinterpret_cast<const unsigned char*>(J.x);
+            r.y = J.y;
+            r.gamma = J.gamma;
+            r.K = J.K; r.N = J.N; r.Mrem = J.Mrem;
+            r.pad[0] = r.pad[1] = r.pad[2] = r.pad[3] = 0;
+        }
+    }
+    LeanFn fn = pick_lean(T);
+    static bool lds_raised[kMaxDevices][4];
+    const int dev = device_slot();
+    if (dev < 0 || !lds_raised[dev][T]) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 8 * stream_wave_lds(3));
+        if (e != hipSuccess) return e;
+        if (dev >= 0) lds_raised[dev][T] = true;
+    }
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(NW * 64), size_t(NW) * stream_wave_lds(T), s, lb);
+    return hipGetLastError();
+}
 
 // Stream form: one job per workgroup, a run of consecutive tiles each.  Workgroups are dealt
 // out to the jobs so that all finish together (see run_cost below); spare ones go to the job
@@ -1026,6 +1302,15 @@ hipError_t launch_stream(GemvBatch& b, int max_slices, int nb, hipStream_t s, in
         if (T < 1) return hipErrorInvalidValue;
     }
     if (T < 1) T = 1;
+    // The lean kernel takes the launch when every job has the same number of slices (one per wave),
+    // N is a multiple of 16 throughout and the workgroups fit its record table.
+    bool lean = pol.lean && !multi_pass && nb == 1 && gs == 0 && T <= 3;
+    int total_groups = 0;
+    for (int j = 0; j < b.count; ++j) {
+        lean = lean && b.job[j].slices == NW && (b.job[j].N & 15) == 0;
+        total_groups += wg[j];
+    }
+    if (lean && total_groups <= kLeanMaxGroups) return launch_lean(b, wg, NW, T, s);
     for (int j = 0; j < kMaxJobs; ++j) b.item0[j] = 0x7fffffff;
     int grid = 0;
     for (int j = 0; j < b.count; ++j) {
@@ -1146,6 +1431,7 @@ extern "C" void tl_dev_stream(int stream, int groups, int long_k_min_run)
     if (long_k_min_run > 0) g_policy.long_k_min_run = long_k_min_run;
 }
 extern "C" void tl_dev_two_blocks(int on) { g_policy.two_blocks = on; }
+extern "C" void tl_dev_lean(int on) { g_policy.lean = on; }
 extern "C" void tl_dev_stream_t(int t) { g_policy.t_stream = t; }
 extern "C" void tl_dev_start_up(double v) { g_policy.start_up_per_row = v; }
 extern "C" void tl_dev_pass_start(double v) { g_policy.pass_start = v; }
@@ -1161,6 +1447,10 @@ hipError_t gemv_init()
     auto raise = [](KernelFn fn, int bytes) {
         return hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
     };
+    for (int T = 1; T <= 3; ++T) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(pick_lean(T)), hipFuncAttributeMaxDynamicSharedMemorySize, 8 * stream_wave_lds(3));
+        if (e != hipSuccess) return e;
+    }
     for (int T = 1; T <= kTMax; ++T)
         for (int multi = 0; multi < 2; ++multi) {
             hipError_t e = raise(pick_kernel(T, multi != 0), kMaxLds);
