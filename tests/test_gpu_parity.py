@@ -5,7 +5,7 @@ import pytest
 import oracle
 import paper_2506_23025_amd as tl
 import synth_inputs as si
-from parity import assert_close, dev_u32, to_dev
+from parity import REL_TOL, assert_close, dev_u32, floors, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -139,13 +139,59 @@ def test_gemv_large_and_tiny_activations():
     assert_close(y, oracle.gemm(x, W, g), x, g, "range")
 
 
-def test_gemv_is_deterministic_and_odd_symmetric():
+def test_gemv_is_deterministic():
     M, N, K = 8, 4096, 4096
     x, W, g = si.layer(99, M, N, K)
     Wp = tl.tl_pack_2bit(W)
     y0 = run_gemm(x, Wp, g, N, K, tl.TL_PATH_GEMV)
     for _ in range(5):
         assert np.array_equal(run_gemm(x, Wp, g, N, K, tl.TL_PATH_GEMV).view(np.uint16), y0.view(np.uint16))
+
+
+def test_gemv_odd_symmetry_within_tolerance():
+    # y(-W) = -y holds exactly for the oracle.  The small-M kernel computes sum (w + 1) x - sum x in
+    # fp32, which is not an odd function of W bit for bit, so the two GPU results are compared at
+    # the tolerance (each against its own oracle value) and their disagreement is bounded by two
+    # output roundings plus the accumulation floor; the generic kernel (w x summed directly) is odd
+    # bit for bit.
+    M, N, K = 8, 1024, 4096
+    x, W, g = si.layer(98, M, N, K)
+    ref = oracle.gemm(x, W, g)
+    assert np.array_equal(oracle.gemm(x, -W, g), -ref)
+    yp = run_gemm(x, tl.tl_pack_2bit(W), g, N, K, tl.TL_PATH_GEMV)
+    yn = run_gemm(x, tl.tl_pack_2bit(-W), g, N, K, tl.TL_PATH_GEMV)
+    assert_close(yp, ref, x, g, "y(W)")
+    assert_close(yn, -ref, x, g, "y(-W)")
+    d = np.abs(yp.astype(np.float64) + yn.astype(np.float64))
+    assert np.all(d <= 2 * REL_TOL * np.maximum(np.abs(ref), floors(x, g, K)))
+    gp = run_gemm(x, tl.tl_pack_2bit(W), g, N, K, tl.TL_PATH_GENERIC)
+    gn = run_gemm(x, tl.tl_pack_2bit(-W), g, N, K, tl.TL_PATH_GENERIC)
+    assert np.array_equal(gp.view(np.uint16) ^ np.uint16(0x8000), gn.view(np.uint16))
+
+
+def test_gemv_exact_cases_error_in_floor_units():
+    # W = 0 and W = I have exact answers (0 and fp16(gamma x)).  The small-M kernel reaches them
+    # through sum (w + 1) x - sum x, so what is left is fp32 accumulation noise of the two sums:
+    # measured here in units of the accumulation floor 2^-24 sqrt(K) ||x||_2 gamma (the tolerance
+    # allows 4 of them), for a short and a long K.
+    rng = np.random.default_rng(97)
+    g = np.float16(0.03)
+    for K in (512, 4096, 32768):
+        x = si.activations(rng, 4, K)
+        unit = float(g) * 2.0 ** -24 * np.sqrt(K) * np.sqrt((x.astype(np.float64) ** 2).sum(axis=1, keepdims=True))
+        y0 = run_gemm(x, tl.tl_pack_2bit(np.zeros((64, K), np.int8)), g, 64, K, tl.TL_PATH_GEMV)
+        worst0 = float(np.max(np.abs(y0.astype(np.float64)) / unit))
+        assert worst0 <= 4.0, f"W = 0, K = {K}: {worst0:.2f} floor units"
+        N = min(K, 1024)
+        I = np.zeros((N, K), np.int8)
+        I[np.arange(N), np.arange(N)] = 1
+        yi = run_gemm(x, tl.tl_pack_2bit(I), g, N, K, tl.TL_PATH_GEMV)
+        exact = float(g) * x[:, :N].astype(np.float64)
+        err = np.abs(yi.astype(np.float64) - exact)
+        # fp16 rounding of the output (half an ulp of |exact|, at most 2^-11 relative) plus the floor
+        assert np.all(err <= 2.0 ** -11 * np.abs(exact) + 4.0 * unit + 2.0 ** -25), f"W = I, K = {K}"
+        print(f"K={K}: W=0 worst {worst0:.2f} floor units; W=I worst excess "
+              f"{float(np.max((err - 2.0 ** -11 * np.abs(exact)) / unit)):.2f} floor units")
 
 
 def test_auto_path_full_size_sampled_columns():
@@ -668,3 +714,51 @@ def test_non_finite_activations_stay_in_their_row():
         assert np.array_equal(y[m].view(np.uint16), clean[m].view(np.uint16))
     assert not np.isfinite(y[1].astype(np.float32)).any()
     assert not np.isfinite(y[3].astype(np.float32)).any()
+
+
+# --- the workload configurations under the floor first proposed for the comparison ---------------
+
+def _rms_floor_err(y_gpu, y_ref):
+    """max |y_gpu - y_ref| / max(|y_ref|, 1e-2 rms_n(y_ref[m, :])): the relative error with a floor of
+    one hundredth of the row's rms, which needs no model of the accumulation; and the plain
+    relative error over the entries that are at least as large as the row's rms."""
+    yg, yr = y_gpu.astype(np.float64), np.asarray(y_ref, dtype=np.float64)
+    rms = np.sqrt(np.mean(yr ** 2, axis=1, keepdims=True))
+    e_floor = float(np.max(np.abs(yg - yr) / np.maximum(np.abs(yr), 1e-2 * rms)))
+    big = np.abs(yr) >= rms
+    e_big = float(np.max(np.abs(yg - yr)[big] / np.abs(yr)[big])) if big.any() else 0.0
+    return e_floor, e_big
+
+
+def _sample_cols(N, n, seed):
+    if N <= n:
+        return np.arange(N)
+    cols = np.sort(np.random.default_rng(seed).choice(N, n, replace=False))
+    cols[-1] = N - 1
+    return cols
+
+
+Q6_CASES = ([("c1", "2bit", 1, 2048, 2048)] +
+            [("c2", "2bit", M, N, 4096) for N in (4096, 14336) for M in (1, 16)] +
+            [("c3", "2bit", M, si.SHAPES[n][1], si.SHAPES[n][0]) for n in si.BLOCK_SHAPES for M in (1, 16, 64)] +
+            [("c4", "2bit", 256, 14336, 4096)] +
+            [("c5", "1p6", M, N, 4096) for N in (4096, 14336) for M in (1, 16)])
+
+
+@pytest.mark.parametrize("cfg,fmt,M,N,K", Q6_CASES)
+def test_workload_configs_under_the_rms_floor(cfg, fmt, M, N, K):
+    # Every configuration of the workload definition with the iid weights it names, judged by a
+    # floor that does not depend on the kernel: 2e-3 relative to max(|y|, 1e-2 rms of the row), and
+    # plain 2e-3 wherever |y| >= rms.  (The tolerance of parity.py models fp32 accumulation instead
+    # and coincides with this floor at K = 4096; this test shows that the model is not what lets
+    # these cases pass.)  Large N: 384 sampled output columns.
+    x, W, g = si.layer(si.SEEDS[cfg] + 7 * M + N % 1000, M, N, K)
+    cols = _sample_cols(N, 384, N + M)
+    ref = oracle.gemm(x, np.ascontiguousarray(W[cols]), g)
+    if fmt == "2bit":
+        y = run_gemm(x, tl.tl_pack_2bit(W), g, N, K)
+    else:
+        y = run_gemm3(x, tl.tl_pack_1p6bit(W), g, N, K)
+    e_floor, e_big = _rms_floor_err(y[:, cols], ref)
+    assert e_floor <= REL_TOL, f"{cfg} {fmt} M={M} {K}->{N}: {e_floor:.3e} with the rms floor"
+    assert e_big <= REL_TOL, f"{cfg} {fmt} M={M} {K}->{N}: {e_big:.3e} on entries >= rms"

@@ -172,3 +172,110 @@ def test_group_scales_single_group_is_one_scale_per_output_row_and_linear_in_the
     ya, yb, yc = (oracle.gemm_group_scales(x, W, s, 128) for s in (a, b, c))
     assert np.allclose(ya, yb + yc, rtol=1e-13, atol=1e-15)
     assert np.count_nonzero(yb[:, [0, 1, 3, 4, 5]]) == 0   # the entry belongs to output row 2 alone
+
+
+# --- the ternariser of App. B, pinned on the oracle's own function ------------------------------
+
+def test_oracle_quantize_hand_worked_example():
+    # App. B: gamma = eps + mean|W|, What = round(clip(W / gamma, -1, 1)).  Worked by hand:
+    # |W| = (0.5, 0.5, 0.1, 2.0), mean 0.775; W / gamma = (0.645, -0.645, 0.129, 2.58 -> clipped 1)
+    W = np.array([[0.5, -0.5, 0.1, 2.0]], dtype=np.float32)
+    What, g = oracle.quantize(W, eps=0.0)
+    assert What.dtype == np.int8 and What.tolist() == [[1, -1, 0, 1]]
+    assert g == pytest.approx(0.775, rel=1e-7)
+    # eps enters additively: the same weights with eps = 0.225 have gamma = 1.0 exactly (in fp64 up to
+    # the rounding of 0.1f), and 0.5 / 1.0 is then a tie
+    What, g = oracle.quantize(W, eps=1.0 - float(np.mean(np.abs(W.astype(np.float64)))))
+    assert g == 1.0 and What.tolist() == [[0, 0, 0, 1]]
+
+
+def test_oracle_quantize_ties_round_to_even_and_clip_comes_first():
+    # mean|W| = 1 exactly, so W / gamma = W: +-0.5 are exact ties (half to even gives 0, half away
+    # from zero would give +-1), 1.5 is clipped to 1 before rounding (rounding first would give 2)
+    What, g = oracle.quantize(np.array([[0.5, 1.5]], dtype=np.float32), eps=0.0)
+    assert g == 1.0 and What.tolist() == [[0, 1]]
+    What, g = oracle.quantize(np.array([[-0.5, -1.5]], dtype=np.float32), eps=0.0)
+    assert g == 1.0 and What.tolist() == [[0, -1]]
+    # just past the tie on either side (0.5 +- 2^-20 and its complement to 2 are exact in fp32)
+    d = np.float32(2.0 ** -20)
+    What, g = oracle.quantize(np.array([[np.float32(0.5) + d, np.float32(1.5) - d]], dtype=np.float32), eps=0.0)
+    assert g == 1.0 and What.tolist() == [[1, 1]]
+    What, g = oracle.quantize(np.array([[np.float32(0.5) - d, np.float32(1.5) + d]], dtype=np.float32), eps=0.0)
+    assert g == 1.0 and What.tolist() == [[0, 1]]
+    # all-zero weights: gamma = eps, What = 0; eps = 0 as well: gamma = 0 and no division
+    What, g = oracle.quantize(np.zeros((3, 5), np.float32), eps=1e-5)
+    assert g == 1e-5 and not What.any()
+    What, g = oracle.quantize(np.zeros((3, 5), np.float32), eps=0.0)
+    assert g == 0.0 and not What.any()
+
+
+@pytest.mark.parametrize("shape,eps,seed", [((1, 1), 0.0, 1), ((3, 7), 0.0, 2), ((5, 4), 1e-5, 3), ((2, 33), 0.25, 4)])
+def test_oracle_quantize_brute_force_exact_rationals(shape, eps, seed):
+    # the definition in exact rational arithmetic, element by element: gamma, the quotient, the
+    # clip and the rounding (half to even) all exact; the fp64 oracle may differ only where the
+    # exact quotient lies within rounding distance of a tie, which these draws avoid
+    rng = np.random.default_rng(seed)
+    W = (rng.standard_normal(shape) * rng.uniform(0.05, 2.0)).astype(np.float32)
+    What, g = oracle.quantize(W, eps=eps)
+    gamma = Fraction(float(eps)) + sum(abs(Fraction(float(w))) for w in W.ravel()) / W.size
+    assert abs(Fraction(g) - gamma) <= gamma * Fraction(1, 2 ** 50)
+    half = Fraction(1, 2)
+    for idx in np.ndindex(*shape):
+        q = Fraction(float(W[idx])) / gamma
+        q = max(Fraction(-1), min(Fraction(1), q))
+        assert abs(abs(q) - half) > Fraction(1, 10 ** 9), "draw too close to a tie"
+        want = 0 if abs(q) < half else (1 if q > 0 else -1)
+        assert int(What[idx]) == want
+
+
+def test_oracle_quantize_invariants():
+    rng = np.random.default_rng(3)
+    W = rng.standard_normal((64, 96)).astype(np.float32)
+    Wh1, g1 = oracle.quantize(W, eps=0.0)
+    Wh2, g2 = oracle.quantize(W * np.float32(8.0), eps=0.0)        # a power of two scales gamma alone
+    assert g2 == 8.0 * g1 and np.array_equal(Wh1, Wh2)
+    Wh3, g3 = oracle.quantize(-W, eps=0.0)                          # odd in W
+    assert g3 == g1 and np.array_equal(Wh3, -Wh1)
+    # near-Gaussian weights: gamma -> sqrt(2 / pi), |W| < gamma / 2 becomes 0:
+    # P(0) = 2 Phi(0.5 sqrt(2 / pi)) - 1 = 0.3101
+    W = rng.standard_normal((512, 512)).astype(np.float32)
+    Wh, g = oracle.quantize(W, eps=0.0)
+    assert abs(g - np.sqrt(2 / np.pi)) < 5e-3
+    assert abs((Wh == 0).mean() - 0.3101) < 5e-3 and abs((Wh == 1).mean() - (Wh == -1).mean()) < 5e-3
+    assert set(np.unique(Wh).tolist()) == {-1, 0, 1}
+
+
+# --- fp64 -> fp16 rounding of the oracle, pinned without a second cast ---------------------------
+
+def _finite_halves():
+    """(bits, value) of every finite non-negative fp16, ascending, decoded by the oracle's C routine
+    (itself pinned against numpy's half -> double above)."""
+    return [(b, oracle.half_to_double(b)) for b in range(0x7C00)]
+
+
+def test_to_fp16_is_the_identity_on_every_fp16_value():
+    for sign in (0, 0x8000):
+        bits = np.arange(0x7C00, dtype=np.uint16) | np.uint16(sign)
+        vals = np.array([oracle.half_to_double(int(b)) for b in bits])
+        got = oracle.to_fp16(vals).view(np.uint16)
+        assert np.array_equal(got, bits)
+
+
+def test_to_fp16_rounds_to_nearest_ties_to_even_between_neighbours():
+    # between neighbouring fp16 values a < b (subnormals and the 2^-14 boundary included): the
+    # exact midpoint goes to the one with the even bit pattern, anything nearer to one side goes there
+    hv = _finite_halves()
+    lo_bits = np.array([b for b, _ in hv[:-1]], dtype=np.uint16)
+    a = np.array([v for _, v in hv[:-1]])
+    b = np.array([v for _, v in hv[1:]])
+    mid = (a + b) / 2                                              # exact in fp64 (11-bit significands)
+    want_mid = np.where(lo_bits % 2 == 0, lo_bits, lo_bits + 1).astype(np.uint16)
+    assert np.array_equal(oracle.to_fp16(mid).view(np.uint16), want_mid)
+    assert np.array_equal(oracle.to_fp16(np.nextafter(mid, -np.inf)).view(np.uint16), lo_bits)
+    assert np.array_equal(oracle.to_fp16(np.nextafter(mid, np.inf)).view(np.uint16), lo_bits + 1)
+    assert np.array_equal(oracle.to_fp16(-mid).view(np.uint16), want_mid | np.uint16(0x8000))
+    # overflow: the midpoint between 65504 and 2^16 rounds to the even side, i.e. to infinity
+    with np.errstate(over="ignore"):
+        assert oracle.to_fp16(np.array([65519.999, 65520.0, 1e9])).view(np.uint16).tolist() == [0x7BFF, 0x7C00, 0x7C00]
+    # below half of the smallest subnormal (2^-25) everything is zero; the tie itself goes to even = 0
+    assert oracle.to_fp16(np.array([2.0 ** -25, np.nextafter(2.0 ** -25, 1.0), 2.0 ** -26])).view(np.uint16).tolist() == [0, 1, 0]
