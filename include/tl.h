@@ -15,7 +15,9 @@
  *   - All functions return a tl_status and never throw, abort or print.
  *   - "host" pointers are ordinary CPU memory; "device" pointers are HBM
  *     addresses valid on the current HIP device.  The caller owns every
- *     buffer; the library allocates nothing and keeps no state between calls.
+ *     buffer; the library allocates nothing.  The only state it keeps between calls is
+ *     a set of once-per-device flags that record that a kernel's launch attribute (its
+ *     dynamic-LDS limit) has been set; tl_init sets them all.  Results never depend on it.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Device entry points only enqueue work on that stream and return; they
  *     never synchronise.  Errors reported by the launch come back as
@@ -47,8 +49,10 @@ typedef enum tl_status {
 typedef enum tl_format {
     TL_FMT_2BIT = 0,   /* paper Sec. 3.1 with k = 16 digits per 32-bit word      */
     TL_FMT_1P6BIT = 1, /* 5 trits per byte, plain base 3 (see tl_pack_1p6bit)    */
-    TL_FMT_1P6BIT_FX = 2 /* 5 trits per byte, the fixed-point code as the paper prints it
+    TL_FMT_1P6BIT_FX = 2, /* 5 trits per byte, the fixed-point code as the paper prints it
                             (see tl_pack_1p6bit_fx); same row geometry as TL_FMT_1P6BIT */
+    TL_FMT_INT_RANGE_ = 0x7fffffff /* not a format: makes every non-negative int a value the type
+                            can hold, so that an unknown code is reported, not undefined */
 } tl_format;
 
 /* Kernel choice for tl_ternary_gemm_path.  AUTO is what tl_ternary_gemm uses. */
@@ -56,7 +60,8 @@ typedef enum tl_path {
     TL_PATH_AUTO = 0,
     TL_PATH_GENERIC = 1, /* plain VALU kernel, any M, N, K                        */
     TL_PATH_GEMV = 2,    /* weight-streaming small-M kernel: M <= 16 per pass     */
-    TL_PATH_MFMA = 3     /* LDS-tiled fp16 MFMA prefill kernel                    */
+    TL_PATH_MFMA = 3,    /* LDS-tiled fp16 MFMA prefill kernel                    */
+    TL_PATH_INT_RANGE_ = 0x7fffffff /* not a path (see TL_FMT_INT_RANGE_)         */
 } tl_path;
 
 /* Human-readable name of a status code (static storage, never NULL). */

@@ -11,7 +11,8 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libtl.so")
+# TL_LIB_PATH: another build of the same library (the host-sanitizer build, see README)
+LIB_PATH = os.environ.get("TL_LIB_PATH") or os.path.join(_HERE, "libtl.so")
 
 TL_OK = 0
 TL_ERR_NULL, TL_ERR_SHAPE, TL_ERR_VALUE, TL_ERR_ALIGN, TL_ERR_UNSUPPORTED, TL_ERR_HIP = 1, 2, 3, 4, 5, 6

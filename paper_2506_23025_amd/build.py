@@ -28,7 +28,29 @@ def _newest_dep():
     return t
 
 
-def build(force=True, verbose=False, extra_flags=()):
+# Host-side sanitizer build (AddressSanitizer + UBSan on the host pass only; the device code is
+# compiled as usual): for running the CPU test suite over the packers, the ternariser and the
+# argument checks.  See README, "Sanitizer pass".
+SAN_FLAGS = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+             "-Xarch_host", "-fno-omit-frame-pointer", "-Xarch_host", "-g"]
+SAN_LIB = os.path.join(HERE, "_build", "san", "libtl.so")
+
+
+def build(force=True, verbose=False, extra_flags=(), sanitize=False):
+    global OBJDIR, LIB
+    if sanitize:
+        objdir, lib = os.path.join(HERE, "_build", "san"), SAN_LIB
+        saved = OBJDIR, LIB
+        OBJDIR, LIB = objdir, lib
+        try:
+            return _build(True, verbose, tuple(extra_flags) + tuple(SAN_FLAGS),
+                          ["-fsanitize=address", "-fsanitize=undefined", "-shared-libsan"])
+        finally:
+            OBJDIR, LIB = saved
+    return _build(force, verbose, extra_flags, [])
+
+
+def _build(force, verbose, extra_flags, link_flags):
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     os.makedirs(OBJDIR, exist_ok=True)
     dep_time = _newest_dep()
@@ -57,10 +79,10 @@ def build(force=True, verbose=False, extra_flags=()):
             sys.stderr.write(text + "\n")
     if failed:
         raise RuntimeError("hipcc failed")
-    link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *link_flags, "-o", LIB, *objs]
     subprocess.run(link, check=True)
     return LIB
 
 
 if __name__ == "__main__":
-    print(build(force="--incremental" not in sys.argv, verbose=True))
+    print(build(force="--incremental" not in sys.argv, verbose=True, sanitize="--sanitize" in sys.argv))

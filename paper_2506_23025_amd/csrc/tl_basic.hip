@@ -23,16 +23,19 @@ unpack2_kernel(const uint32_t* __restrict__ packed, int64_t N, int64_t K, int64_
 }
 
 // Digit i (0..4) of a 1.6-bit byte as w + 1.  Plain form: base-3 digits, least significant
-// first.  Fixed-point form (Sec. 3.2 with k = 5, p = 8): App. F, Alg. 1 -- multiply by 3, the
-// digit is what spills over the byte, the low byte goes on; most significant digit first.
+// first.  Fixed-point form (Sec. 3.2 with k = 5, p = 8): the byte is b = ceil(256 V / 243) for the
+// block value V = sum_j d_j 3^(4-j) < 243, so V = floor(243 b / 256) gives it back, and its base-3
+// digits are taken most significant first.  (The multiply-by-3 peeling of App. F, Alg. 1 yields
+// the same digits for every byte; the tests check this decode against it.)
 __device__ __forceinline__ void digits5(unsigned v, bool fx, unsigned (&d)[5])
 {
     if (fx) {
+        v = (v * 243u) >> 8;
 #pragma unroll
-        for (int i = 0; i < 5; ++i) {
-            const unsigned t = v * 3u;
-            d[i] = t >> 8;
-            v = t & 0xFFu;
+        for (int i = 4; i >= 0; --i) {
+            const unsigned q = v / 3u;
+            d[i] = v - 3u * q;
+            v = q;
         }
     } else {
         v = (v >= 243u) ? v - 243u : v;
@@ -321,14 +324,23 @@ hipError_t launch_probe_read(const void* src, size_t bytes, void* sink, hipStrea
     return hipGetLastError();
 }
 
+// The row blocks of these kernels lie on grid.y, which holds 65535 of them: more activation rows go
+// out as several launches.
+constexpr int64_t kMaxGridY = 65535;
+
 hipError_t launch_gemm_generic(const __half* x, const uint32_t* Wp, float gamma, __half* y,
                                int64_t M, int64_t N, int64_t K, hipStream_t s)
 {
     const int64_t words = (K + 15) / 16;
-    dim3 grid(blocks_for(N, GN), blocks_for(M, GM));
-    hipLaunchKernelGGL(gemm_generic_kernel<false>, grid, dim3(256), 0, s, x, Wp, gamma,
-                       static_cast<const __half*>(nullptr), int64_t(16), y, M, N, K, words);
-    return hipGetLastError();
+    for (int64_t m0 = 0; m0 < M; m0 += kMaxGridY * GM) {
+        const int64_t rows = M - m0 < kMaxGridY * GM ? M - m0 : kMaxGridY * GM;
+        dim3 grid(blocks_for(N, GN), blocks_for(rows, GM));
+        hipLaunchKernelGGL(gemm_generic_kernel<false>, grid, dim3(256), 0, s, x + m0 * K, Wp, gamma,
+                           static_cast<const __half*>(nullptr), int64_t(16), y + m0 * N, rows, N, K, words);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 hipError_t launch_gemm_generic_gs(const __half* x, const uint32_t* Wp, const __half* scales,
@@ -336,17 +348,28 @@ hipError_t launch_gemm_generic_gs(const __half* x, const uint32_t* Wp, const __h
                                   hipStream_t s)
 {
     const int64_t words = (K + 15) / 16;
-    dim3 grid(blocks_for(N, GN), blocks_for(M, GM));
-    hipLaunchKernelGGL(gemm_generic_kernel<true>, grid, dim3(256), 0, s, x, Wp, 1.f, scales, group, y, M, N, K, words);
-    return hipGetLastError();
+    for (int64_t m0 = 0; m0 < M; m0 += kMaxGridY * GM) {
+        const int64_t rows = M - m0 < kMaxGridY * GM ? M - m0 : kMaxGridY * GM;
+        dim3 grid(blocks_for(N, GN), blocks_for(rows, GM));
+        hipLaunchKernelGGL(gemm_generic_kernel<true>, grid, dim3(256), 0, s, x + m0 * K, Wp, 1.f, scales, group,
+                           y + m0 * N, rows, N, K, words);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 hipError_t launch_gemm3_generic(const __half* x, const uint8_t* Wp, int64_t stride, float gamma,
                                 __half* y, int64_t M, int64_t N, int64_t K, bool fx, hipStream_t s)
 {
-    dim3 grid(blocks_for(N, 4), blocks_for(M, MB));
-    hipLaunchKernelGGL(gemm3_generic_kernel, grid, dim3(256), 0, s, x, Wp, stride, gamma, y, M, N, K, fx);
-    return hipGetLastError();
+    for (int64_t m0 = 0; m0 < M; m0 += kMaxGridY * MB) {
+        const int64_t rows = M - m0 < kMaxGridY * MB ? M - m0 : kMaxGridY * MB;
+        dim3 grid(blocks_for(N, 4), blocks_for(rows, MB));
+        hipLaunchKernelGGL(gemm3_generic_kernel, grid, dim3(256), 0, s, x + m0 * K, Wp, stride, gamma, y + m0 * N, rows, N, K, fx);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 }  // namespace tl

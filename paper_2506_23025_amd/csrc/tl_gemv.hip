@@ -14,12 +14,14 @@
 //    (i, g) to hold row i.  The 2 KB tile slice is turned through wave-private LDS
 //    (ds_write_b128 / ds_read_b128, XOR-swizzled, no barrier: a wave only reads what it
 //    wrote itself).
-//  * Decode costs 10 VALU operations per 16 weights.  `word & (3 << 2j | 3 << (2j+16))`
+//  * Decode costs 10 to 11 VALU operations per 16 weights.  `word & (3 << 2j | 3 << (2j+16))`
 //    leaves two codes in the mantissa fields of an fp16 pair, i.e. the subnormal numbers
 //    c * 4^j * 2^-24 (gfx950 MFMA does not flush fp16 subnormals).  The matrix core aligns
 //    products by their exponent FIELDS, so a code low in the mantissa loses accuracy
-//    (measured: ~2^-17 relative at j = 0, none at j >= 3).  The word as loaded and two shifted
-//    copies (<< 4, >> 6) therefore bring every code to j in {2, 3, 4}.  Products of
+//    (measured: ~2^-17 relative at j = 0, none at j >= 3).  Shifted copies of the word therefore
+//    bring every code to j in {2, 3, 4}: the stream and lean kernels use the word as loaded and
+//    two copies (<< 4, >> 6: 2 shifts + 8 ANDs per word), the general kernel three copies
+//    (<< 4, >> 2, >> 8: 3 shifts + 8 ANDs).  Products of
 //    different j carry different power-of-two factors, so they go to three accumulators
 //    that are combined once per tile: sum_j 2^(24-2j) acc_j = sum_k x_k c_k.  With
 //    c = w + 1 the result is sum_k x_k c_k - sum_k x_k; the second sum comes from one more
@@ -28,9 +30,11 @@
 //    by gamma, rounded to fp16 (RNE) and stored.  No atomics: results are deterministic.
 //  * One launch can carry up to 32 independent jobs (a job = one matrix and at most 16, in
 //    one variant 32, activation rows); a workgroup finds its job from its index.
-//  * Two forms.  The stream form (gemv_stream_kernel: K up to 8 slices per pass, the usual
-//    case) gives a wave one slice for the whole kernel and a workgroup a run of consecutive
-//    tiles of one job, so activations are staged once and only weights move afterwards.  The
+//  * Three forms.  The stream form (gemv_stream_kernel: K up to 8 slices per pass) gives a wave
+//    one slice for the whole kernel and a workgroup a run of consecutive tiles of one job, so
+//    activations are staged once and only weights move afterwards.  The lean form
+//    (gemv_lean_kernel) is the stream form cut down to the decode shapes (one pass over K, one
+//    block of 16 rows, one gamma, N a multiple of 16) and is what those launches run.  The
 //    general form (gemv_kernel) loops a wave over slices and a workgroup over items of any
 //    job; it takes lone calls with long K.
 #include "tl_internal.hpp"
@@ -45,20 +49,23 @@ namespace {
 constexpr int kTMax = 4;          // tiles per work item
 constexpr int kSliceK = 512;      // K elements a wave owns per pass
 constexpr int kWaveLds = 16384;   // bytes of LDS per wave: 16 activation rows x 1 KB
-constexpr int kMaxJobs = 32;      // jobs per launch (the table is 2.2 KB of kernel arguments)
+constexpr int kMaxJobs = 32;      // jobs per launch (the table is 2.7 KB of kernel arguments)
 
-struct GemvJob {                  // 64 bytes, lives in the kernel argument segment
+struct GemvJob {                  // 80 bytes, lives in the kernel argument segment
     const __half* x;              // first activation row of this 16-row block
     const uint32_t* W;
     __half* y;                    // first output row of this block
-    float gamma;                  // per-group scales: bits of the int "256-weight halves per group"
-    int Mrem;                     // 1..16 activation rows
+    float gamma;
+    int Mrem;                     // 1..16 activation rows (stream form with two row blocks: 1..32)
     int N, K;
     int tiles;                    // ceil(N / 16)
-    int items;                    // work items of this job: ceil(tiles / T); per-group scales: low word of the scales pointer
+    int items;                    // general form: work items of this job, ceil(tiles / T)
     int slices;                   // ceil(K / 512)
-    int mr;                       // staged rows: power of two >= Mrem; per-group scales: high word of the scales pointer
-    int pad[2];
+    int mr;                       // general form: staged rows, the power of two >= Mrem
+    int run, plus;                // stream form: tiles per workgroup, and how many of the job's first workgroups take one more
+    const __half* scales;         // per-group scales [K / group][N] (kernels with GS), else unused
+    int hpg;                      // per-group scales: scale units of a slice per group
+    int reserved;
 };
 
 struct GemvBatch {
@@ -102,7 +109,7 @@ struct ItemCtx {
 // segment with vector loads: every workgroup needs one entry chosen by its index, and a
 // scalar look-up would be two dependent trips to memory before the first weight is requested.
 struct JobTable {
-    uint32_t d[16];               // the 16 dwords of GemvJob
+    uint32_t d[20];               // the 20 dwords of GemvJob
     int item0;
 };
 
@@ -114,7 +121,7 @@ __device__ __forceinline__ JobTable load_table(int lane)
     JobTable r;
     r.item0 = 0x7fffffff;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) r.d[i] = 0u;
+    for (int i = 0; i < 20; ++i) r.d[i] = 0u;
     // only lanes 0 .. kMaxJobs - 1 load (the entries are read with v_readlane from those lanes): half
     // of the addresses for the CU's address path, which all eight waves go through at once
     if (lane < kMaxJobs) {
@@ -122,7 +129,7 @@ __device__ __forceinline__ JobTable load_table(int lane)
         const __attribute__((address_space(4))) u32x4* jp =
             (const __attribute__((address_space(4))) u32x4*)(ka + offsetof(GemvBatch, job) + sizeof(GemvJob) * k);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < 5; ++i) {
             const u32x4 q = jp[i];
             r.d[4 * i] = q[0]; r.d[4 * i + 1] = q[1]; r.d[4 * i + 2] = q[2]; r.d[4 * i + 3] = q[3];
         }
@@ -135,9 +142,9 @@ __device__ __forceinline__ ItemCtx load_item(const JobTable& tb, int g)
 {
     const unsigned long long m = __builtin_amdgcn_ballot_w64(g >= tb.item0) & ((1ull << kMaxJobs) - 1);
     const int ji = __builtin_popcountll(m) - 1;
-    uint32_t f[16];
+    uint32_t f[20];
 #pragma unroll
-    for (int i = 0; i < 14; ++i) f[i] = __builtin_amdgcn_readlane(tb.d[i], ji);
+    for (int i = 0; i < 19; ++i) f[i] = __builtin_amdgcn_readlane(tb.d[i], ji);
     const int item0 = __builtin_amdgcn_readlane(tb.item0, ji);
     ItemCtx c;
     c.xb = reinterpret_cast<const unsigned char*>(uintptr_t(f[0]) | (uintptr_t(f[1]) << 32));
@@ -151,12 +158,13 @@ __device__ __forceinline__ ItemCtx load_item(const JobTable& tb, int g)
     c.tiles = int(f[10]); c.items = int(f[11]); c.idx = g - item0;
     c.slices = int(f[12]);
     c.MR = int(f[13]);
-    c.sc = reinterpret_cast<const unsigned char*>(uintptr_t(f[11]) | (uintptr_t(f[13]) << 32));
-    c.hpg = int(f[6]);
+    c.sc = reinterpret_cast<const unsigned char*>(uintptr_t(f[16]) | (uintptr_t(f[17]) << 32));
+    c.hpg = int(f[18]);
     return c;
 }
 
-static_assert(sizeof(GemvJob) == 64 && offsetof(GemvJob, gamma) == 24 && offsetof(GemvJob, mr) == 52,
+static_assert(sizeof(GemvJob) == 80 && offsetof(GemvJob, gamma) == 24 && offsetof(GemvJob, mr) == 52 &&
+              offsetof(GemvJob, run) == 56 && offsetof(GemvJob, scales) == 64 && offsetof(GemvJob, hpg) == 72,
               "load_item decodes GemvJob by dword position");
 
 // T: tiles per work item; MULTI: the launch carries more than one job.
@@ -438,7 +446,7 @@ constexpr int stream_wave_lds(int T)
 // wave w owns K slice w for good, so its activations are fetched and turned into MFMA operands
 // once, and all that moves afterwards is the weight stream.  A workgroup serves one job (its
 // index picks the job; GemvBatch::item0[j] is the first workgroup of job j) and walks a run of
-// consecutive tiles of it, T at a time (GemvJob::pad: tiles per workgroup, and how many of the
+// consecutive tiles of it, T at a time (GemvJob::run, plus: tiles per workgroup, and how many of the
 // job's first workgroups take one more).  While item i is decoded the loads of item i + 1 are in flight,
 // each tile waits only for its own two loads, and there is one LDS-only barrier per item.
 // The loop body holds nothing but weight loads and the output stores, which is what keeps the
@@ -497,7 +505,7 @@ gemv_stream_kernel(GemvBatch b)
         J.chunks = G.K >> 6;
         J.tiles = G.tiles; J.items = G.items; J.idx = int(blockIdx.x);
         J.slices = G.slices;
-        ipg = G.pad[0]; plus = G.pad[1];
+        ipg = G.run; plus = G.plus;
     }
     const int local = J.idx;
     const int tile0 = local * ipg + (local < plus ? local : plus);      // first tile of the run
@@ -1152,7 +1160,7 @@ struct GemvPolicy {
     int long_k_min_run = 3;             // K > 4096 streams if the call averages this many tile passes per workgroup
     int lean = 1;                       // launches the lean kernel can take go to it
 };
-GemvPolicy g_policy;
+const GemvPolicy g_policy{};   // fixed in the library; development builds patch this line to try other values
 
 constexpr int kStreamWaves = 8;         // waves of a stream-form workgroup when K >= 4096
 constexpr int kStreamMaxPasses = 8;     // passes over K the stream form takes: K <= 32768
@@ -1315,9 +1323,9 @@ hipError_t launch_stream(GemvBatch& b, int max_slices, int nb, hipStream_t s, in
     int grid = 0;
     for (int j = 0; j < b.count; ++j) {
         b.item0[j] = grid;
-        if (!gs) b.job[j].items = 0;                       // (the scaled form keeps half of a pointer there)
-        b.job[j].pad[0] = b.job[j].tiles / wg[j];
-        b.job[j].pad[1] = b.job[j].tiles % wg[j];
+        b.job[j].items = 0;
+        b.job[j].run = b.job[j].tiles / wg[j];
+        b.job[j].plus = b.job[j].tiles % wg[j];
         grid += wg[j];
     }
     const size_t lds = size_t(NW) * stream_wave_lds(T * nb) + (multi_pass ? size_t(kStreamMaxRun) * 1024 : 0);
@@ -1419,26 +1427,6 @@ hipError_t launch_batch(GemvBatch& b, bool grouped, bool stream_form, int nb, hi
 
 }  // namespace
 
-#ifdef TL_DEV_HOOKS
-extern "C" void tl_dev_policy(int nw_single, int nw_grouped, int grid_cap, int t_grouped)
-{
-    g_policy.nw_single = nw_single; g_policy.nw_grouped = nw_grouped;
-    g_policy.grid_cap = grid_cap; g_policy.t_grouped = t_grouped;
-}
-extern "C" void tl_dev_stream(int stream, int groups, int long_k_min_run)
-{
-    g_policy.stream = stream; g_policy.stream_groups = groups;
-    if (long_k_min_run > 0) g_policy.long_k_min_run = long_k_min_run;
-}
-extern "C" void tl_dev_two_blocks(int on) { g_policy.two_blocks = on; }
-extern "C" void tl_dev_lean(int on) { g_policy.lean = on; }
-extern "C" void tl_dev_stream_t(int t) { g_policy.t_stream = t; }
-extern "C" void tl_dev_start_up(double v) { g_policy.start_up_per_row = v; }
-extern "C" void tl_dev_pass_start(double v) { g_policy.pass_start = v; }
-extern "C" void tl_dev_item_cost(int on) { g_policy.item_cost = on; }
-extern "C" void tl_dev_item_model(double first, double extra) { g_policy.item_first = first; g_policy.tile_extra = extra; }
-#endif
-
 // Raises the dynamic-LDS limit of every kernel instance of this file on the current device (the
 // launchers do it on first use otherwise).
 hipError_t gemv_init()
@@ -1520,7 +1508,8 @@ hipError_t launch_gemv_jobs(const GemmDesc* jobs, int count, hipStream_t s)
             j.items = 0;
             j.slices = slices;
             j.mr = pow2_at_least(j.Mrem < 16 ? j.Mrem : 16);
-            j.pad[0] = j.pad[1] = 0;
+            j.run = j.plus = 0;
+            j.scales = nullptr; j.hpg = 0; j.reserved = 0;
             const bool streams = j.slices <= kStreamWaves ||
                                  (long_k_streams && j.slices <= kStreamWaves * kStreamMaxPasses);
             GemvBatch& b = two_blocks ? bs2 : (streams ? bs : bg);
@@ -1551,6 +1540,8 @@ hipError_t launch_gemv_jobs(const GemmDesc* jobs, int count, hipStream_t s)
 bool gemv_gs_supports(int64_t M, int64_t N, int64_t K, int64_t group)
 {
     const int64_t slices = (K + kSliceK - 1) / kSliceK;
+    // (the kernel addresses the scales with 32-bit byte offsets)
+    if (((K + group - 1) / group) * N * 2 >= (int64_t(1) << 31)) return false;
     return gemv_supports(M, N, K) && group >= 128 && group % 128 == 0 && N >= 4 && N % 4 == 0 &&
            slices <= kStreamWaves * kStreamMaxPasses &&
            (slices <= kStreamWaves || (N + 15) / 16 <= int64_t(256) * kStreamMaxRun);
@@ -1561,7 +1552,6 @@ hipError_t launch_gemv_gs(const __half* x, const uint32_t* Wp, const __half* sca
 {
     if (!gemv_gs_supports(M, N, K, group)) return hipErrorInvalidValue;
     const int slices = int((K + kSliceK - 1) / kSliceK);
-    const uintptr_t sp = reinterpret_cast<uintptr_t>(scales);
     // scale units per slice: 2 of 256 weights when the groups allow, else 4 of 128; hpg = units per group
     const int units = group % 256 == 0 ? 2 : 4;
     const int hpg = int(group / (kSliceK / units));
@@ -1572,14 +1562,15 @@ hipError_t launch_gemv_gs(const __half* x, const uint32_t* Wp, const __half* sca
         j.x = x + m0 * K;
         j.W = Wp;
         j.y = y + m0 * N;
-        j.gamma = __builtin_bit_cast(float, hpg);
+        j.gamma = 1.f;
         j.Mrem = int(M - m0 < 16 ? M - m0 : 16);
         j.N = int(N); j.K = int(K);
         j.tiles = int((N + 15) / 16);
-        j.items = int(uint32_t(sp));
+        j.items = 0;
         j.slices = slices;
-        j.mr = int(uint32_t(sp >> 32));
-        j.pad[0] = j.pad[1] = 0;
+        j.mr = pow2_at_least(j.Mrem);
+        j.run = j.plus = 0;
+        j.scales = scales; j.hpg = hpg; j.reserved = 0;
         b.job[b.count++] = j;
         if (b.count == kMaxJobs || m0 + 16 >= M) {
             const hipError_t e = launch_stream(b, slices, 1, s, units);

@@ -83,17 +83,17 @@ __device__ __forceinline__ uint32_t byte_times_8(uint32_t w)
 }
 
 // byte -> digits table.  Plain form: base-3 digits, least significant first (bytes 243..255
-// never occur; they decode like byte - 243).  Fixed-point form: App. F, Alg. 1, run here once
-// per byte value -- multiply by 3, the digit is what spills over the byte, most significant
-// digit first; all 256 bytes decode.
+// never occur; they decode like byte - 243).  Fixed-point form (Sec. 3.2): the block value is
+// floor(243 b / 256), the inverse of b = ceil(256 V / 243), and its base-3 digits go most
+// significant first; all 256 bytes decode, and to the digits App. F, Alg. 1 gives.
 __device__ __forceinline__ void fill_table(u32x2* lut, bool fx)
 {
     for (unsigned b = threadIdx.x; b < 256; b += blockDim.x) {
         unsigned c[5];
         if (fx) {
-            unsigned v = b;
+            unsigned v = (b * 243u) >> 8;
 #pragma unroll
-            for (int i = 0; i < 5; ++i) { const unsigned t = v * 3u; c[i] = t >> 8; v = t & 0xFFu; }
+            for (int i = 4; i >= 0; --i) { c[i] = v % 3u; v /= 3u; }
         } else {
             unsigned v = b >= 243 ? b - 243 : b;
 #pragma unroll

@@ -57,8 +57,8 @@ size_t tl_row_stride_bytes(tl_format fmt, int64_t K) {
         case TL_FMT_2BIT: return static_cast<size_t>(4 * ceil_div(K, 16));
         case TL_FMT_1P6BIT:
         case TL_FMT_1P6BIT_FX: return static_cast<size_t>(16 * ceil_div(ceil_div(K, kTritsPerByte), 16));
+        default: return 0;                       // an unknown format
     }
-    return 0;
 }
 
 size_t tl_packed_bytes(tl_format fmt, int64_t N, int64_t K) {
@@ -194,21 +194,21 @@ tl_status tl_pack_1p6bit_fx(const int8_t* W, int64_t N, int64_t K, uint8_t* out)
     return bad ? TL_ERR_VALUE : TL_OK;
 }
 
-// App. F, Alg. 1: peel the digits off the top of the byte by repeated multiplication by 3.
+// Decode of the fixed-point code: b = ceil(256 V / 243) is inverted by V = floor(243 b / 256),
+// and V's base-3 digits, most significant first, are the weights + 1.  (App. F, Alg. 1 peels the
+// same digits off with multiplications by 3; the tests hold this decode against it.)
 tl_status tl_unpack_1p6bit_fx(const uint8_t* packed, int64_t N, int64_t K, int8_t* W_out) {
     if (!packed || !W_out) return TL_ERR_NULL;
     if (!shape_ok(N, K)) return TL_ERR_SHAPE;
     const int64_t stride = static_cast<int64_t>(tl_row_stride_bytes(TL_FMT_1P6BIT, K));
+    static const unsigned kPow3[kTritsPerByte] = {81u, 27u, 9u, 3u, 1u};
     for (int64_t n = 0; n < N; ++n) {
         const uint8_t* src = packed + n * stride;
         int8_t* row = W_out + n * K;
         for (int64_t base = 0; base < K; base += kTritsPerByte) {
-            unsigned rem = src[base / kTritsPerByte];
-            for (int i = 0; i < kTritsPerByte && base + i < K; ++i) {
-                const unsigned t = rem * 3u;
-                row[base + i] = static_cast<int8_t>(static_cast<int>(t >> 8) - 1);
-                rem = t & 0xFFu;
-            }
+            const unsigned value = (243u * src[base / kTritsPerByte]) >> 8;
+            for (int i = 0; i < kTritsPerByte && base + i < K; ++i)
+                row[base + i] = static_cast<int8_t>(static_cast<int>((value / kPow3[i]) % 3u) - 1);
         }
     }
     return TL_OK;

@@ -98,6 +98,7 @@ inline int device_slot()
 
 hipError_t gemv_init();
 hipError_t gemv3_init();
+hipError_t mfma_init();
 
 // fp16 bits -> float on the host (exact).
 float half_bits_to_float(uint16_t h);

@@ -8,7 +8,7 @@
 //
 //  * W stays packed all the way into LDS.  Per step a wave needs 16 bytes (64 codes) of each
 //    of its NW rows: one `global_load_lds_dwordx4` drops them into a wave-private ring of
-//    stages, three steps ahead, with no registers and no barrier involved.  A lane
+//    WSTAGES = 4 stages, three steps ahead, with no registers and no barrier involved.  A lane
 //    (column i, k half g) reads its row's 16 bytes back (one ds_read_b128 per 32 columns and
 //    step, issued one step early) and decodes, per 16-k block, the half-word it needs:
 //    `(w >> 8g) & (3 << 2j | 3 << (2j+16)) | 0x64006400` is the fp16 pair (1024 + 4^j c_j', 1024 + 4^j c_j'+8), j' = 4g + j,
@@ -16,7 +16,7 @@
 //    2 VALU operations per operand register, and an operand register set feeds 4 MFMAs.
 //  * That pairs k with k + 8 inside every 16-k block.  The matrix instruction does not care
 //    in which order k runs as long as both operands agree, so X is stored to LDS in the same
-//    order: on its way from global memory through registers (prefetched two steps ahead) each
+//    order: on its way from global memory through registers (prefetched XS = 4 steps ahead) each
 //    thread interleaves the two 8-k pieces of a block with v_perm_b32.  X is double-buffered
 //    in LDS (padded rows, conflict-free b128 reads), so a step costs one barrier.
 //  * Every wave runs v_mfma_f32_32x32x16_f16 over a 128 x NW sub-tile (4 x NW/32 fragments),
@@ -36,8 +36,8 @@ constexpr int XBUF = BM * XROW;        // one X buffer
 constexpr int WSTAGES = 4;             // steps of packed W in flight per wave
 constexpr int WSTAGE = 1024;           // bytes per stage: 64 rows x 16 bytes
 
-int g_wide_min = 129;                  // 128 x 256 tiles from this many of them on (measured crossover)
-int g_split = 1;                       // 128 x 128 tiles: two sets of waves per tile when K allows
+constexpr int kWideMin = 129;          // 128 x 256 tiles from this many of them on (measured crossover)
+constexpr bool kSplit = true;          // 128 x 128 tiles: two sets of waves per tile when K allows
 
 struct MfmaParams {
     const __half* x;
@@ -173,7 +173,7 @@ mfma_kernel(MfmaParams p)
         const uint32_t stage = uint32_t(step & (WSTAGES - 1));
         const unsigned char* src = wsrc + size_t(kstep(step)) * 16;
         const uint32_t base = __builtin_amdgcn_readfirstlane(wring_addr + stage * WSTAGE);
-        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(base) : "memory");
+        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(base) : "memory");   // (m0 is never allocated by the compiler: it sets it right before each of its own uses)
     };
 
     // Barrier that waits for this wave's LDS traffic only: global loads and W transfers stay in
@@ -203,19 +203,21 @@ mfma_kernel(MfmaParams p)
     uint32_t k1024;
     asm volatile("v_mov_b32 %0, 0x64006400" : "=v"(k1024));
 
-    // The packed words of the next step are read from the ring before the barrier that ends a
-    // step (its wait for LDS covers them).  W of step t: (WSTAGES - 2) steps of 4 X loads and
-    // 1 transfer each were issued after it by then.  Hand-written ds_read: for an LDS read it can
-    // see, the compiler waits until every LDS-DMA transfer in flight has landed.
+    // The packed words of the next step are read from the ring right before the barrier that ends
+    // a step.  W of step t: (WSTAGES - 2) steps of 4 X loads and 1 transfer each were issued after
+    // it by then.  Hand-written ds_read: for an LDS read it can see, the compiler waits until every
+    // LDS-DMA transfer in flight has landed.  Read, wait and barrier are one statement, so that the
+    // registers count as written only once the wait is behind them; the wait is for LDS traffic
+    // only: global loads and W transfers stay in flight across it (__syncthreads would drain them).
     u32x4 wnext[FN];
-    auto read_w = [&](int t) {
+    auto read_w_and_barrier = [&](int t) {
         __builtin_amdgcn_s_waitcnt(vm_imm(5 * (WSTAGES - 2)));
         const uint32_t waddr = b_addr + uint32_t(t & (WSTAGES - 1)) * WSTAGE;
         if constexpr (FN == 2) {
-            asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:512"
-                         : "=&v"(wnext[0]), "=&v"(wnext[1]) : "v"(waddr));
+            asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:512\n\ts_waitcnt lgkmcnt(0)\n\ts_barrier"
+                         : "=&v"(wnext[0]), "=&v"(wnext[1]) : "v"(waddr) : "memory");
         } else {
-            asm volatile("ds_read_b128 %0, %1" : "=&v"(wnext[0]) : "v"(waddr));
+            asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)\n\ts_barrier" : "=&v"(wnext[0]) : "v"(waddr) : "memory");
         }
     };
     // ---- prologue ---------------------------------------------------------------------------
@@ -227,8 +229,7 @@ mfma_kernel(MfmaParams p)
     store_x(0, 0);
 #pragma unroll
     for (int d = 1; d <= XS; ++d) load_x(d % XS, d);   // slot j % XS holds X of step j
-    read_w(0);
-    lds_barrier();
+    read_w_and_barrier(0);
 
     auto step_body = [&](auto slot_tag, int s) {
         constexpr int SLOT = decltype(slot_tag)::value;        // (s + 1) % XS
@@ -239,10 +240,6 @@ mfma_kernel(MfmaParams p)
         issue_w(s + WSTAGES - 1);
         const unsigned char* const xb = a_frag + PAR * XBUF;
         u32x4 wq[FN];
-        // read before the barrier behind us, which waited for it; the compiler does not know, so
-        // the values count as produced here
-        if constexpr (FN == 2) asm volatile("" : "+v"(wnext[0]), "+v"(wnext[1]));
-        else asm volatile("" : "+v"(wnext[0]));
 #pragma unroll
         for (int b = 0; b < FN; ++b) wq[b] = wnext[b];
         if constexpr (SPLIT == 2) {
@@ -282,8 +279,7 @@ mfma_kernel(MfmaParams p)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[a], bf[b], acc[a][b], 0, 0, 0);
         }
         }
-        read_w(s + 1);
-        lds_barrier();
+        read_w_and_barrier(s + 1);
     };
 
     // steps in groups of XS, so that register slots and buffer parity are compile-time
@@ -342,10 +338,12 @@ mfma_kernel(MfmaParams p)
 
 }  // namespace
 
-#ifdef TL_DEV_HOOKS
-extern "C" void tl_dev_mfma(int wide_min) { g_wide_min = wide_min; }
-extern "C" void tl_dev_split(int on) { g_split = on; }
-#endif
+// Raises the dynamic-LDS limit of the two-set instance on the current device (104 KB).
+hipError_t mfma_init()
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&mfma_kernel<32, 4, 2>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, mfma_lds_bytes<2>());
+}
 
 bool mfma_supports(int64_t M, int64_t N, int64_t K)
 {
@@ -363,10 +361,10 @@ hipError_t launch_mfma(const __half* x, const uint32_t* Wp, float gamma, __half*
     // 128 x 256 tiles, two workgroups resident per CU; 128 x 128 tiles while those would leave
     // half of the CUs without work
     const int64_t wide = int64_t(p.tiles_m) * ((N + 255) / 256);
-    if (wide >= g_wide_min) {
+    if (wide >= kWideMin) {
         p.tiles_n = int((N + 255) / 256);
         hipLaunchKernelGGL((mfma_kernel<64, 4, 1>), dim3(p.tiles_m * p.tiles_n), dim3(256), mfma_lds_bytes<1>(), s, p);
-    } else if (g_split && K % (2 * BK) == 0) {
+    } else if (kSplit && K % (2 * BK) == 0) {
         // at most one tile per CU: two sets of waves per tile, each with half of the K steps
         static bool raised[kMaxDevices];
         const int dev = device_slot();

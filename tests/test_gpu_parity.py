@@ -233,6 +233,21 @@ def test_extreme_dimensions_sampled(M, N, K):
     assert_close(y[np.ix_(rows, cols)], ref, xs, g, f"extreme {M}x{N}x{K}")
 
 
+def test_generic_kernels_take_more_row_blocks_than_one_grid_holds():
+    # the plain kernels keep their row blocks on grid.y (65535 of them): 16 rows per block for the
+    # 2-bit form (K not a multiple of 64), 4 for the 1.6-bit form (K not a multiple of 8); more
+    # rows than that go out as several launches.  Checked on sampled rows, the last ones included.
+    rng = np.random.default_rng(65535)
+    for fmt, M, N, K in (("2bit", 65535 * 16 + 40, 3, 16), ("1p6", 65535 * 4 + 9, 2, 5)):
+        x = si.activations(rng, M, K)
+        W = si.ternary_weights(rng, N, K)
+        g = np.float16(0.02)
+        y = run_gemm(x, tl.tl_pack_2bit(W), g, N, K) if fmt == "2bit" else run_gemm3(x, tl.tl_pack_1p6bit(W), g, N, K)
+        rows = np.unique(np.concatenate([rng.choice(M, 4096, replace=False), np.arange(M - 64, M), np.arange(64)]))
+        xs = np.ascontiguousarray(x[rows])
+        assert_close(y[rows], oracle.gemm(xs, W, g), xs, g, f"{fmt} M={M}")
+
+
 def test_config1_square_2048():
     # config 1: 2048 -> 2048, M = 1, gamma = fp16(0.02); the whole matrix against the oracle
     M, N, K = 1, 2048, 2048

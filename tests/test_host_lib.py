@@ -72,6 +72,17 @@ def test_pack_1p6bit_fx_matches_paper_code_and_alg1_decode():
         assert oracle.unpack_fx_alg1_block(int(Pw[1, b])).tolist() == W[1, 5 * b:5 * b + 5].tolist()
 
 
+def test_unpack_1p6bit_fx_closed_form_equals_alg1_on_every_byte():
+    # the library inverts the code in closed form (V = floor(243 b / 256), then base-3 digits);
+    # App. F, Alg. 1 (in the oracle) peels digits with multiplications by 3: same digits for all
+    # 256 byte values, also the 13 that no block produces
+    P = np.zeros((256, 16), dtype=np.uint8)
+    P[:, 0] = np.arange(256)
+    got = tl.tl_unpack_1p6bit_fx(P, 256, 5)
+    want = np.array([oracle.unpack_fx_alg1_block(b) for b in range(256)], dtype=np.int8)
+    assert np.array_equal(got, want)
+
+
 def test_fx_format_through_the_format_enum():
     # TL_FMT_1P6BIT_FX: same geometry as the plain 1.6-bit form; host unpack = Alg. 1 decode;
     # the library's rows equal the oracle's rows byte for byte
