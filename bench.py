@@ -11,6 +11,13 @@ its layers.  The same step issued as ten separate tl_ternary_gemm calls is timed
 Prints one JSON line: `value` is the sweep's algorithmic bytes per second (packed W + x + y
 of all ten GEMMs / time of a step).  `roofline` is measured live for the dominant kernel (the
 grouped launch), `cpu_baseline` is the CPU oracle timed on the same workload.
+
+Timing protocol.  `steps` steps are captured into one HIP graph (a batch).  The graph is replayed
+untimed until the GPU has run that workload for 80 ms -- the chip raises its clock over the first
+tens of milliseconds of sustained load (measured inside the kernel: 1.7-1.9 GHz in the first
+replays after idle, 2.3-2.4 GHz from about 50 ms on), and a step takes 19-24 us before that against
+17-18 us after -- and then 11 batches are timed one by one with events on the launch stream.  A
+figure is the median batch divided by `steps`; p10 and p90 of the batches are printed beside it.
 """
 import argparse
 import json
@@ -37,7 +44,7 @@ def algorithmic_bytes(M, N, K):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--mode", choices=("sweep", "dominant", "copy", "prefill"), default="sweep",
@@ -166,8 +173,12 @@ def main():
     # ---------------- timed region: exactly `steps` steps ---------------------------------
     # The launches are captured once into a HIP graph (as a serving loop would do for a decode
     # step) and replayed, so that the host's per-call cost is not part of the figure.
+    WARM_MS = 80.0          # sustained load before timing (clock ramp)
+    N_BATCH = 11            # timed batches per figure
+
     def timed(fn, reps):
-        """ms for `reps` executions of fn() on a side stream, graph-replayed unless --eager."""
+        """Median, p10 and p90 (ms) over N_BATCH batches of `reps` executions of fn() on a side stream,
+        graph-replayed unless --eager, after WARM_MS of the same load."""
         nonlocal stream
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
@@ -175,68 +186,165 @@ def main():
             stream = side.cuda_stream
             fn()                                            # untimed: loads code, touches buffers
             side.synchronize()
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             if args.eager:
-                a.record(side)
-                for _ in range(reps):
-                    fn()
-                b.record(side)
+                def batch():
+                    for _ in range(reps):
+                        fn()
             else:
                 g = torch.cuda.CUDAGraph()
                 with torch.cuda.graph(g, stream=side):
                     for _ in range(reps):
                         fn()
-                g.replay()                                  # untimed replay
-                side.synchronize()
-                a.record(side)
-                g.replay()
-                b.record(side)
+                batch = g.replay
+            t_w = time.perf_counter()
+            n_w = 0
+            while n_w < 3 or (time.perf_counter() - t_w) * 1e3 < WARM_MS:
+                batch()
+                n_w += 1
+                if n_w % 4 == 0:
+                    side.synchronize()
             side.synchronize()
+            ts = []
+            for _ in range(N_BATCH):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record(side)
+                batch()
+                b.record(side)
+                side.synchronize()
+                ts.append(a.elapsed_time(b))
         stream = torch.cuda.current_stream().cuda_stream
-        return a.elapsed_time(b)
+        ts.sort()
+        return dict(ms=ts[len(ts) // 2], p10=ts[len(ts) // 10], p90=ts[-1 - len(ts) // 10], batches=len(ts))
+
+    def per_unit(st, reps, scale=1e3):
+        """(median, p10, p90) of a timed() result per execution, in us by default."""
+        return tuple(st[k] * scale / reps for k in ("ms", "p10", "p90"))
+
+    def us_row(st, reps):
+        m, lo, hi = per_unit(st, reps)
+        return dict(us=round(m, 3), us_p10=round(lo, 3), us_p90=round(hi, 3))
+
+    # a read-only kernel over `nbytes` bytes (a different stretch of the largest weight ring per
+    # launch): what the memory system gives a single launch of that size
+    big = max(layers.values(), key=lambda l: l["ring"].numel())["ring"].view(-1)
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+
+    def probe_us(nbytes, reps):
+        nbytes = (nbytes + 15) // 16 * 16
+        slots = max(1, big.numel() * 4 // nbytes)
+        pc = [0]
+
+        def probe_step():
+            off = (pc[0] % slots) * nbytes
+            pc[0] += 1
+            st = L.tl_probe_read(big.data_ptr() + off, nbytes, sink.data_ptr(), stream)
+            if st != tl.TL_OK:
+                raise tl.TlError(st, "tl_probe_read")
+
+        return per_unit(timed(probe_step, reps), reps)[0]
 
     for _ in range(args.warmup):
         step_grouped()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    ms_per_step = timed(step_grouped, args.steps) / args.steps
+    head = timed(step_grouped, args.steps)
     wall_ms = (time.perf_counter() - t0) * 1e3
+    ms_per_step = head["ms"] / args.steps
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
+    us_probe = probe_us(step_bytes, args.steps)
+
+    # the same step on the same weight buffers every time (96 MB: it stays in the 256 MB last-level
+    # cache), and the latency of one launch into an idle GPU
+    warm_same = None
+    latency = None
+    if not args.no_per_call:
+        def step_same():
+            jobs = [(xd[M], layers[name]["ring"][0], layers[name]["gbits"], yd[(name, M)], M, layers[name]["N"], K)
+                    for name, M in calls]
+            arr = tl.make_jobs(jobs)
+            st = L.tl_ternary_gemm_grouped(arr, len(arr), stream)
+            if st != tl.TL_OK:
+                raise tl.TlError(st, "tl_ternary_gemm_grouped")
+
+        st = timed(step_same, args.steps)
+        warm_same = dict(us_row(st, args.steps), GBps=round(step_bytes / per_unit(st, args.steps)[0] / 1e3, 1),
+                         note="every step reads the same ten weight buffers (96 MB, resident in the last-level cache)")
+        lat = []
+        cur = torch.cuda.current_stream()
+        for _ in range(21):
+            torch.cuda.synchronize()
+            time.sleep(0.002)
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(cur)
+            step_grouped()
+            b.record(cur)
+            torch.cuda.synchronize()
+            lat.append(a.elapsed_time(b) * 1e3)
+        lat.sort()
+        latency = dict(us=round(lat[len(lat) // 2], 2), us_p10=round(lat[2], 2), us_p90=round(lat[-3], 2),
+                       note="one grouped launch of the sweep into an idle GPU, event to event on the launch stream "
+                            "(includes the launch itself and the idle clock)")
 
     # ---------------- the same step as ten separate calls; per-call figures ----------------
     per_call = []
     single = None
     if not args.no_per_call:
-        ms_single = timed(step, args.steps) / args.steps
+        st = timed(step, args.steps)
+        ms_single = st["ms"] / args.steps
         single = dict(ms_per_step=round(ms_single, 5), GBps=round(step_bytes / ms_single / 1e6, 1),
-                      hbm_frac=round(step_bytes / ms_single / 1e6 / HBM_PEAK_GBS, 4))
+                      hbm_frac=round(step_bytes / ms_single / 1e6 / HBM_PEAK_GBS, 4),
+                      ms_p10=round(st["p10"] / args.steps, 5), ms_p90=round(st["p90"] / args.steps, 5),
+                      note="ten tl_ternary_gemm calls per step: what a chain of dependent layers gets")
     for name, M in ([] if args.no_per_call else calls):
-        us = timed(lambda: launch(name, M), args.steps) * 1e3 / args.steps
+        st = timed(lambda: launch(name, M), args.steps)
+        us = per_unit(st, args.steps)[0]
         N = layers[name]["N"]
         b = algorithmic_bytes(M, N, K)
-        per_call.append(dict(layer=name, M=M, N=N, K=K, us=round(us, 3), GBps=round(b / us / 1e3, 1),
+        pus = probe_us(b, args.steps)
+        per_call.append(dict(layer=name, M=M, N=N, K=K, **us_row(st, args.steps), GBps=round(b / us / 1e3, 1),
                              hbm_frac=round(b / us / 1e3 / HBM_PEAK_GBS, 4),
-                             TFLOPs=round(2.0 * M * N * K / us / 1e6, 3)))
+                             TFLOPs=round(2.0 * M * N * K / us / 1e6, 3),
+                             read_only_probe_us=round(pus, 3), kernel_vs_probe=round(pus / us, 4)))
 
-    # large M: the LDS-tiled MFMA kernel against the dense fp16 MFMA peak; and the batch sizes
-    # in between with whichever kernel the library picks
+    # large M: the LDS-tiled MFMA kernel against the dense fp16 MFMA peak, and against a kernel that
+    # only issues the same matrix instruction on the same kind of operands; and the batch sizes in
+    # between with whichever kernel the library picks
     prefill, mid_batch = [], []
+    mfma_probe = None
+    if not args.no_per_call:
+        fsink = torch.zeros(4, dtype=torch.float32, device=dev)
+        wp0 = layers[pre_name]["ring"][0]
+        flops_box = [0.0]
+
+        def probe_mfma_step():
+            flops_box[0] = tl.tl_probe_mfma(pre_x, pre_x.numel(), wp0, wp0.numel(), 4096, fsink, stream)
+
+        reps = max(1, min(args.steps, 20))
+        st = timed(probe_mfma_step, reps)
+        pus = per_unit(st, reps)[0]
+        mfma_probe = dict(kernel="probe_mfma_kernel: v_mfma_f32_32x32x16_f16 only, 8 accumulators per wave, two waves per SIMD, "
+                                 "activations x ternary weights as operands",
+                          **us_row(st, reps), TFLOPs=round(flops_box[0] / pus / 1e6, 1),
+                          frac_of_peak=round(flops_box[0] / pus / 1e6 / MFMA_PEAK_TFLOPS, 4))
     for M in ([] if args.no_per_call else pre_M):
         reps = max(1, min(args.steps, 40))
-        us = timed(lambda: launch_prefill(M), reps) * 1e3 / reps
+        st = timed(lambda: launch_prefill(M), reps)
+        us = per_unit(st, reps)[0]
         fl = 2.0 * M * pre_N * K
         which = {tl.TL_PATH_GEMV: "small-M kernel", tl.TL_PATH_MFMA: "mfma_kernel",
                  tl.TL_PATH_GENERIC: "generic kernel"}[tl.tl_ternary_gemm_which(M, pre_N, K)]
-        us_auto = us if which == "mfma_kernel" else timed(lambda: launch_prefill(M, tl.TL_PATH_AUTO), reps) * 1e3 / reps
-        prefill.append(dict(layer=pre_name, M=M, N=pre_N, K=K, kernel="mfma_kernel", us=round(us, 2),
+        us_auto = us if which == "mfma_kernel" else per_unit(timed(lambda: launch_prefill(M, tl.TL_PATH_AUTO), reps), reps)[0]
+        prefill.append(dict(layer=pre_name, M=M, N=pre_N, K=K, kernel="mfma_kernel", **us_row(st, reps),
                             TFLOPs=round(fl / us / 1e6, 1), mfma_frac=round(fl / us / 1e6 / MFMA_PEAK_TFLOPS, 4),
+                            kernel_vs_mfma_probe=round(fl / us / 1e6 / mfma_probe["TFLOPs"], 4),
                             tl_ternary_gemm=dict(kernel=which, us=round(us_auto, 2), TFLOPs=round(fl / us_auto / 1e6, 1),
                                                  mfma_frac=round(fl / us_auto / 1e6 / MFMA_PEAK_TFLOPS, 4))))
     for M in ([] if args.no_per_call else (32, 64, 128, 256, 512)):
         reps = max(1, min(args.steps, 40))
-        us = timed(lambda: launch_prefill(M, tl.TL_PATH_AUTO), reps) * 1e3 / reps
+        st = timed(lambda: launch_prefill(M, tl.TL_PATH_AUTO), reps)
+        us = per_unit(st, reps)[0]
         fl = 2.0 * M * pre_N * K
-        mid_batch.append(dict(layer=pre_name, M=M, N=pre_N, K=K, kernel="picked by tl_ternary_gemm", us=round(us, 2),
+        mid_batch.append(dict(layer=pre_name, M=M, N=pre_N, K=K, kernel="picked by tl_ternary_gemm", **us_row(st, reps),
                               TFLOPs=round(fl / us / 1e6, 1), GBps=round(algorithmic_bytes(M, pre_N, K) / us / 1e3, 1)))
 
     # the linears of a block (QKV, O, gate+up, down) as one grouped call: the unit the paper's
@@ -268,13 +376,16 @@ def main():
                     raise tl.TlError(st, "tl_ternary_gemm_grouped")
 
             reps = max(1, min(args.steps, 60))
-            us = timed(block_step, reps) * 1e3 / reps
+            st = timed(block_step, reps)
+            us = per_unit(st, reps)[0]
             bb = sum(algorithmic_bytes(M, l["N"], l["K"]) for l in blay)
-            block.append(dict(M=M, layers=[l["name"] for l in blay], algorithmic_bytes=bb, us=round(us, 2),
+            block.append(dict(M=M, layers=[l["name"] for l in blay], algorithmic_bytes=bb, **us_row(st, reps),
                               GBps=round(bb / us / 1e3, 1), hbm_frac=round(bb / us / 1e3 / HBM_PEAK_GBS, 4)))
         del blay
 
-    # the 1.6-bit format and per-group scales beside the 2-bit, single-gamma kernel (one call each)
+    # the 1.6-bit formats (plain base 3, decoded through a table; the paper's fixed-point code of
+    # Sec. 3.2, same kernel with the table filled from that code) and per-group scales beside the
+    # 2-bit, single-gamma kernel (one call each)
     formats = []
     if not args.no_per_call:
         frng = np.random.default_rng(si.SEEDS["c5"])
@@ -282,11 +393,15 @@ def main():
             lay = layers[name]
             N = lay["N"]
             W3 = tl.tl_pack_1p6bit(lay["W"])
+            W3fx = tl.tl_pack_1p6bit_fx(lay["W"])
             copies3 = max(2, min(24, (512 << 20) // W3.nbytes))
             ring3 = torch.empty((copies3,) + W3.shape, dtype=torch.uint8, device=dev)
+            ring3fx = torch.empty((copies3,) + W3.shape, dtype=torch.uint8, device=dev)
             ring3[0].copy_(torch.from_numpy(W3))
+            ring3fx[0].copy_(torch.from_numpy(W3fx))
             for i in range(1, copies3):
                 ring3[i].copy_(ring3[0])
+                ring3fx[i].copy_(ring3fx[0])
             group = 256
             sc = torch.from_numpy(si.group_scales(frng, K // group, N).view(np.int16)).to(dev)
             sc128 = torch.from_numpy(si.group_scales(frng, K // 128, N).view(np.int16)).to(dev)
@@ -294,13 +409,12 @@ def main():
                 cur = [0]
                 fy = torch.empty((M, N), dtype=torch.int16, device=dev)    # the sweep's outputs stay as they are
 
-                def call3():
+                def call3(fn=L.tl_ternary_gemm_1p6, ring=ring3, what="tl_ternary_gemm_1p6"):
                     i = cur[0]
                     cur[0] = (i + 1) % copies3
-                    st = L.tl_ternary_gemm_1p6(xd[M].data_ptr(), ring3[i].data_ptr(), lay["gbits"],
-                                               fy.data_ptr(), M, N, K, stream)
+                    st = fn(xd[M].data_ptr(), ring[i].data_ptr(), lay["gbits"], fy.data_ptr(), M, N, K, stream)
                     if st != tl.TL_OK:
-                        raise tl.TlError(st, "tl_ternary_gemm_1p6")
+                        raise tl.TlError(st, what)
 
                 def call_gs(scales=sc, grp=group):
                     i = cursor[name]
@@ -311,51 +425,57 @@ def main():
                         raise tl.TlError(st, "tl_ternary_gemm_gs")
 
                 reps = max(1, min(args.steps, 200))
-                us2 = timed(lambda: launch(name, M), reps) * 1e3 / reps
-                us3 = timed(call3, reps) * 1e3 / reps
-                usg = timed(call_gs, reps) * 1e3 / reps
-                usg128 = timed(lambda: call_gs(sc128, 128), reps) * 1e3 / reps
+                us2 = per_unit(timed(lambda: launch(name, M), reps), reps)[0]
+                us3 = per_unit(timed(call3, reps), reps)[0]
+                us3fx = per_unit(timed(lambda: call3(L.tl_ternary_gemm_1p6_fx, ring3fx, "tl_ternary_gemm_1p6_fx"), reps), reps)[0]
+                usg = per_unit(timed(call_gs, reps), reps)[0]
+                usg128 = per_unit(timed(lambda: call_gs(sc128, 128), reps), reps)[0]
                 b2 = algorithmic_bytes(M, N, K)
                 b3 = N * W3.shape[1] + 2 * M * K + 2 * M * N
                 formats.append(dict(layer=name, M=M, N=N, K=K,
                                     two_bit=dict(us=round(us2, 3), GBps=round(b2 / us2 / 1e3, 1)),
-                                    one_point_six_bit=dict(us=round(us3, 3), GBps=round(b3 / us3 / 1e3, 1)),
+                                    one_point_six_bit=dict(us=round(us3, 3), GBps=round(b3 / us3 / 1e3, 1),
+                                                           time_vs_two_bit=round(us3 / us2, 3)),
+                                    one_point_six_bit_fixed_point_code=dict(us=round(us3fx, 3), GBps=round(b3 / us3fx / 1e3, 1),
+                                                                            time_vs_two_bit=round(us3fx / us2, 3)),
                                     two_bit_group_scales_256=dict(us=round(usg, 3), GBps=round((b2 + 2 * (K // group) * N) / usg / 1e3, 1)),
                                     two_bit_group_scales_128=dict(us=round(usg128, 3), GBps=round((b2 + 2 * (K // 128) * N) / usg128 / 1e3, 1))))
-            del ring3
+            del ring3, ring3fx
 
-    # dominant kernel: the small-M kernel in its grouped launch; one launch = one step
+    # dominant kernel: the small-M kernel in its grouped launch; one launch = one step.  Counter
+    # figures come from the rocprofv3 runs summarised under profiles/; they are quoted only while
+    # the kernel source is the one they were measured on.
     us_launch = ms_per_step * 1e3
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.txt")     # figure from the rocprofv3 --pmc runs
+    valu_per_weight = None
+    counters_note = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
     if os.path.exists(tpath):
+        import hashlib
+        kv = {}
         for line in open(tpath):
-            if line.startswith("grouped_sweep_bytes_per_launch"):
-                traffic = float(line.split("=")[1])
-    # the same number of bytes read by a kernel that does nothing else (one launch per step,
-    # from the largest weight ring, a different stretch each time): what the memory system
-    # gives a single launch of this size
-    big = max(layers.values(), key=lambda l: l["ring"].numel())["ring"].view(-1)
-    probe_bytes = (step_bytes + 15) // 16 * 16
-    slots = max(1, big.numel() * 4 // probe_bytes)
-    sink = torch.zeros(4, dtype=torch.int32, device=dev)
-    pc = [0]
-
-    def probe_step():
-        off = (pc[0] % slots) * probe_bytes
-        pc[0] += 1
-        st = L.tl_probe_read(big.data_ptr() + off, probe_bytes, sink.data_ptr(), stream)
-        if st != tl.TL_OK:
-            raise tl.TlError(st, "tl_probe_read")
-
-    us_probe = timed(probe_step, args.steps) * 1e3 / args.steps
-    roofline = dict(bound="hbm", kernel="gemv_stream_kernel<3, true, false, 1, 0>, grouped launch of the ten GEMMs of a step",
+            if "=" in line and not line.startswith("#"):
+                k_, v_ = line.split("=", 1)
+                kv[k_.strip()] = v_.strip()
+        src_hash = hashlib.sha256(open(os.path.join(ROOT, "paper_2506_23025_amd", "csrc", "tl_gemv.hip"), "rb").read()).hexdigest()
+        if kv.get("kernel_source_sha256") == src_hash:
+            traffic = float(kv["grouped_sweep_bytes_per_launch"])
+            weights = sum(layers[name]["N"] * K for name, _ in calls)
+            if "grouped_sweep_valu_insts_per_launch" in kv:
+                # wave instructions x 64 lanes / weights of a step (MFMA issues not included)
+                valu_per_weight = round(float(kv["grouped_sweep_valu_insts_per_launch"]) * 64 / weights, 4)
+        else:
+            counters_note = "profiles/hbm_traffic.txt was measured on another version of tl_gemv.hip: counter figures withheld"
+    roofline = dict(bound="hbm", kernel="gemv_lean_kernel<3>, grouped launch of the ten GEMMs of a step",
                     achieved=round(step_bytes / us_launch / 1e3, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(step_bytes / us_launch / 1e3 / HBM_PEAK_GBS, 4),
-                    bytes_per_launch=step_bytes, us_per_launch=round(us_launch, 3), traffic=traffic,
+                    bytes_per_launch=step_bytes, us_per_launch=round(us_launch, 3),
+                    us_per_launch_p10=round(head["p10"] / args.steps * 1e3, 3), us_per_launch_p90=round(head["p90"] / args.steps * 1e3, 3),
+                    timed_batches=head["batches"], traffic=traffic,
+                    valu_lane_ops_per_weight=valu_per_weight, counters_note=counters_note,
                     read_only_probe=dict(kernel="probe_read_kernel: the same bytes, loads only, one launch",
-                                         us_per_launch=round(us_probe, 3), GBps=round(probe_bytes / us_probe / 1e3, 1),
-                                         frac_of_peak=round(probe_bytes / us_probe / 1e3 / HBM_PEAK_GBS, 4),
+                                         us_per_launch=round(us_probe, 3), GBps=round(step_bytes / us_probe / 1e3, 1),
+                                         frac_of_peak=round(step_bytes / us_probe / 1e3 / HBM_PEAK_GBS, 4),
                                          kernel_vs_probe=round(us_probe / us_launch, 4)))
 
     # ---------------- CPU oracle on the same sweep (reported baseline, not a target) -------
@@ -391,7 +511,11 @@ def main():
                    "gemms_per_step": len(calls), "launches_per_step": 1, "weight_ring_copies": {n: layers[n]["copies"] for n in layers},
                    "algorithmic_bytes_per_step": step_bytes},
         "hbm_frac_of_peak": round(value / HBM_PEAK_GBS, 4),
-        "roofline": roofline, "cpu_baseline": cpu, "single_calls": single, "per_call": per_call, "prefill": prefill, "mid_batch": mid_batch, "block": block, "formats": formats,
+        "ms_per_step_p10": round(head["p10"] / args.steps, 5), "ms_per_step_p90": round(head["p90"] / args.steps, 5),
+        "timing": {"batches": head["batches"], "steps_per_batch": args.steps, "figure": "median batch", "untimed_load_before_timing_ms": WARM_MS},
+        "roofline": roofline, "cpu_baseline": cpu, "single_calls": single, "warm_same_buffer": warm_same,
+        "single_launch_latency_us": latency, "per_call": per_call, "mfma_probe": mfma_probe, "prefill": prefill,
+        "mid_batch": mid_batch, "block": block, "formats": formats,
         "launch_mode": "eager" if args.eager else "hip_graph_replay",
         "host_wall_ms_timed_region_incl_capture": round(wall_ms, 2), "context": PAPER_CONTEXT,
     }

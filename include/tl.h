@@ -248,6 +248,21 @@ tl_status tl_probe_copy(void* dst, const void* src, size_t bytes, void* stream);
  */
 tl_status tl_probe_read(const void* src, size_t bytes, void* sink, void* stream);
 
+/*
+ * Matrix-pipe ceiling for the large-batch regime (Sec. 3.3: beyond the critical batch the product
+ * is compute-bound; App. G: the dequantised weights feed the matrix units): a kernel whose waves
+ * do nothing but fp16 matrix instructions (v_mfma_f32_32x32x16_f16, 8 independent accumulators
+ * per wave, two waves per SIMD of a 256-CU device) for `iters` rounds.  The operands are real data,
+ * since what the chip sustains depends on it: activations read from `x` (device, fp16, x_elems >= 1
+ * of them, reused cyclically) against ternary weights decoded to -1 / 0 / +1 from `Wpacked`
+ * (device, 2-bit words, w_words >= 1).  `*flops` (host, may be NULL) receives the floating-point
+ * operations of the launch; `sink` is a device pointer to 4 writable bytes (written only if the
+ * fold of all sums equals one particular value).  Not part of the method: the benchmark times it
+ * beside the large-M kernel.
+ */
+tl_status tl_probe_mfma(const void* x, int64_t x_elems, const void* Wpacked, int64_t w_words, int64_t iters,
+                        void* sink, double* flops, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

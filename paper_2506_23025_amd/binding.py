@@ -28,6 +28,7 @@ EXPORTS = (
     "tl_init",
     "tl_probe_copy",
     "tl_probe_read",
+    "tl_probe_mfma",
 )
 
 
@@ -94,6 +95,8 @@ def _load():
     L.tl_probe_copy.restype = ci
     L.tl_probe_read.argtypes = [vp, sz, vp, vp]
     L.tl_probe_read.restype = ci
+    L.tl_probe_mfma.argtypes = [vp, i64, vp, i64, i64, vp, ctypes.POINTER(ctypes.c_double), vp]
+    L.tl_probe_mfma.restype = ci
     return L
 
 
@@ -263,3 +266,11 @@ def tl_probe_copy(dst, src, nbytes, stream=None):
 
 def tl_probe_read(src, nbytes, sink, stream=None):
     _check(_lib.tl_probe_read(_ptr(src), nbytes, _ptr(sink), _stream(stream)), "tl_probe_read")
+
+
+def tl_probe_mfma(x, x_elems, Wpacked, w_words, iters, sink, stream=None):
+    """Returns the floating-point operations of the launch."""
+    flops = ctypes.c_double(0.0)
+    _check(_lib.tl_probe_mfma(_ptr(x), x_elems, _ptr(Wpacked), w_words, iters, _ptr(sink), ctypes.byref(flops),
+                              _stream(stream)), "tl_probe_mfma")
+    return flops.value

@@ -280,4 +280,15 @@ tl_status tl_probe_read(const void* src, size_t bytes, void* sink, void* stream)
     return tl::from_hip(tl::launch_probe_read(src, bytes, sink, static_cast<hipStream_t>(stream)));
 }
 
+tl_status tl_probe_mfma(const void* x, int64_t x_elems, const void* Wpacked, int64_t w_words, int64_t iters,
+                        void* sink, double* flops, void* stream)
+{
+    if (!x || !Wpacked || !sink) return TL_ERR_NULL;
+    if (x_elems < 1 || w_words < 1 || iters < 1 || iters > (int64_t(1) << 24)) return TL_ERR_SHAPE;
+    if ((reinterpret_cast<uintptr_t>(x) & 1u) || (reinterpret_cast<uintptr_t>(Wpacked) & 3u) ||
+        (reinterpret_cast<uintptr_t>(sink) & 3u)) return TL_ERR_ALIGN;
+    return tl::from_hip(tl::launch_probe_mfma(static_cast<const __half*>(x), x_elems, static_cast<const uint32_t*>(Wpacked),
+                                              w_words, iters, static_cast<float*>(sink), flops, static_cast<hipStream_t>(stream)));
+}
+
 }  // extern "C"

@@ -278,6 +278,48 @@ gemm3_generic_kernel(const __half* __restrict__ x, const uint8_t* __restrict__ W
     }
 }
 
+// ---- matrix-pipe ceiling: waves that only issue v_mfma_f32_32x32x16_f16 -----------------------
+// 8 independent accumulators per wave, two waves per SIMD (256 workgroups of 8 waves), no memory,
+// LDS or vector-ALU work inside the loop.  The operands are real data, because the data decides
+// what the chip can sustain: one operand holds activations as they are, the other ternary weights
+// decoded to fp16 -1 / 0 / +1 from packed words (Sec. 3.1), as the large-M kernel feeds them.
+constexpr int kProbeMfmaGroups = 256, kProbeMfmaThreads = 512, kProbeMfmaAcc = 8;
+
+__global__ void __launch_bounds__(kProbeMfmaThreads)
+probe_mfma_kernel(const __half* __restrict__ x, int64_t x_elems, const uint32_t* __restrict__ Wp, int64_t w_words,
+                  int64_t iters, float* __restrict__ sink)
+{
+    const int64_t t = int64_t(blockIdx.x) * kProbeMfmaThreads + threadIdx.x;
+    f16x8 a[2], b[2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const uint32_t word = Wp[(2 * t + q) % w_words];          // 16 codes; 8 of them are used
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            a[q][e] = static_cast<_Float16>(__half2float(x[((2 * t + q) * 8 + e) % x_elems]));
+            int c = int((word >> (2 * e)) & 3u);
+            if (c == 3) c = 1;                                    // (never packed) counts as weight 0
+            b[q][e] = static_cast<_Float16>(float(c - 1));
+        }
+    }
+    f32x16 acc[kProbeMfmaAcc];
+#pragma unroll
+    for (int q = 0; q < kProbeMfmaAcc; ++q)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[q][r] = 0.f;
+    for (int64_t it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int q = 0; q < kProbeMfmaAcc; ++q)
+            acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[q & 1], b[(q >> 1) & 1], acc[q], 0, 0, 0);
+    }
+    float fold = 0.f;
+#pragma unroll
+    for (int q = 0; q < kProbeMfmaAcc; ++q)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) fold += acc[q][r];
+    if (fold == 1.2345678e30f) sink[0] = fold;                    // keeps the loop alive
+}
+
 inline unsigned blocks_for(int64_t items, int per_block)
 {
     return static_cast<unsigned>((items + per_block - 1) / per_block);
@@ -310,6 +352,14 @@ hipError_t launch_probe_copy(void* dst, const void* src, size_t bytes, hipStream
     if (blocks > 256 * 32) blocks = 256 * 32;
     hipLaunchKernelGGL(probe_copy_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s,
                        static_cast<u32x4*>(dst), static_cast<const u32x4*>(src), n16);
+    return hipGetLastError();
+}
+
+hipError_t launch_probe_mfma(const __half* x, int64_t x_elems, const uint32_t* Wp, int64_t w_words,
+                             int64_t iters, float* sink, double* flops, hipStream_t s)
+{
+    if (flops) *flops = double(kProbeMfmaGroups) * (kProbeMfmaThreads / 64) * double(iters) * kProbeMfmaAcc * (2.0 * 32 * 32 * 16);
+    hipLaunchKernelGGL(probe_mfma_kernel, dim3(kProbeMfmaGroups), dim3(kProbeMfmaThreads), 0, s, x, x_elems, Wp, w_words, iters, sink);
     return hipGetLastError();
 }
 

@@ -24,6 +24,8 @@ hipError_t launch_unpack3(const uint8_t* packed, int64_t N, int64_t K, int64_t s
                           bool fx, hipStream_t s);
 hipError_t launch_probe_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
 hipError_t launch_probe_read(const void* src, size_t bytes, void* sink, hipStream_t s);
+hipError_t launch_probe_mfma(const __half* x, int64_t x_elems, const uint32_t* Wp, int64_t w_words,
+                             int64_t iters, float* sink, double* flops, hipStream_t s);
 
 // Plain VALU kernel: any M, N, K.
 hipError_t launch_gemm_generic(const __half* x, const uint32_t* Wp, float gamma, __half* y,

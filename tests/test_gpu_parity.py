@@ -704,6 +704,14 @@ def test_probe_kernels_run_and_leave_memory_alone():
     torch.cuda.synchronize()
     assert torch.equal(dst, src)
     assert sink.tolist() == [7, 7, 7, 7]          # the fold of 0..n-1 is not the value that triggers the store
+    # the matrix-pipe probe: reports its flops, touches nothing but (possibly) the sink
+    x = to_dev(si.activations(np.random.default_rng(5), 1, 4096).view(np.int16))
+    wp = dev_u32(tl.tl_pack_2bit(si.ternary_weights(np.random.default_rng(6), 4, 4096)))
+    fsink = torch.full((4,), 3.0, dtype=torch.float32, device="cuda")
+    flops = tl.tl_probe_mfma(x, 4096, wp, 1024, 10, fsink)
+    torch.cuda.synchronize()
+    assert flops == 256 * 8 * 10 * 8 * 2 * 32 * 32 * 16
+    assert fsink.tolist() == [3.0, 3.0, 3.0, 3.0]
 
 
 def test_init_is_idempotent_and_calls_work_after_it():

@@ -185,6 +185,10 @@ def test_error_codes():
     assert L.tl_probe_read(16, 24, 16, None) == tl.TL_ERR_SHAPE
     assert L.tl_probe_read(16, 32, None, None) == tl.TL_ERR_NULL
     assert L.tl_probe_read(16, 32, 18, None) == tl.TL_ERR_ALIGN
+    assert L.tl_probe_mfma(None, 8, 16, 8, 1, 16, None, None) == tl.TL_ERR_NULL
+    assert L.tl_probe_mfma(16, 0, 16, 8, 1, 16, None, None) == tl.TL_ERR_SHAPE
+    assert L.tl_probe_mfma(16, 8, 16, 8, 0, 16, None, None) == tl.TL_ERR_SHAPE
+    assert L.tl_probe_mfma(16, 8, 18, 8, 1, 16, None, None) == tl.TL_ERR_ALIGN
     for s in range(8):
         assert tl.tl_status_str(s)
 
