@@ -47,11 +47,15 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--mode", choices=("sweep", "dominant", "copy", "prefill"), default="sweep",
-                    help="sweep: the benchmark; dominant / copy / prefill: run only the dominant kernel, "
-                         "only the plain copy probe, or only the large-M kernel at M = 2048, `steps` times "
-                         "(for rocprofv3 counter collection)")
+    ap.add_argument("--mode", choices=("sweep", "dominant", "copy", "prefill", "one_point_six", "mfma_probe"), default="sweep",
+                    help="sweep: the benchmark; the others run one kernel `steps` times for rocprofv3: dominant (the "
+                         "grouped sweep launch), copy (the plain copy probe), prefill (the large-M kernel at M = 2048), "
+                         "one_point_six (the 1.6-bit kernel, 4096 -> 14336 at M = 1), mfma_probe (tl_probe_mfma)")
     ap.add_argument("--no-per-call", action="store_true", help="skip the ten-separate-calls measurements")
+    ap.add_argument("--weights", choices=("workload", "pm1", "zero"), default="workload",
+                    help="weight values: the workload's iid ternary draw (default); +-1 only (no zeros: codes 0 and 2); "
+                         "all zero (constant words).  Same bytes and instructions, other data: the time of the "
+                         "sweep depends on it (the chip's power management answers to the switching in the matrix pipes)")
     ap.add_argument("--eager", action="store_true",
                     help="launch every call from the host instead of replaying a captured HIP graph")
     args = ap.parse_args()
@@ -97,6 +101,10 @@ def main():
     for name, k, N in shapes:
         assert k == K
         W = si.ternary_weights(rng, N, K)
+        if args.weights == "pm1":
+            W = np.where(W == 0, np.int8(1), W).astype(np.int8)
+        elif args.weights == "zero":
+            W = np.zeros_like(W)
         g = si.gamma_uniform(rng)
         Wp = tl.tl_pack_2bit(W)
         copies = max(2 * len(Ms), min(96, RING_BYTES // Wp.nbytes // len(shapes)))
@@ -161,6 +169,32 @@ def main():
                                     pre_y.data_ptr(), M, pre_N, K, stream, path)
         if st != tl.TL_OK:
             raise tl.TlError(st, "tl_ternary_gemm_path")
+
+    if args.mode == "mfma_probe":
+        fsink = torch.zeros(4, dtype=torch.float32, device=dev)
+        wp0 = layers[pre_name]["ring"][0]
+        for _ in range(args.steps):
+            flops = tl.tl_probe_mfma(pre_x, pre_x.numel(), wp0, wp0.numel(), 4096, fsink, stream)
+        torch.cuda.synchronize()
+        print(json.dumps({"mode": "mfma_probe", "launches": args.steps, "flops_per_launch": flops}))
+        return
+
+    if args.mode == "one_point_six":
+        lay = layers[pre_name]
+        W3 = tl.tl_pack_1p6bit(lay["W"])
+        copies3 = 24
+        ring3 = torch.empty((copies3,) + W3.shape, dtype=torch.uint8, device=dev)
+        for i in range(copies3):
+            ring3[i].copy_(torch.from_numpy(W3))
+        fy = torch.empty((1, pre_N), dtype=torch.int16, device=dev)
+        for i in range(args.steps):
+            st = L.tl_ternary_gemm_1p6(xd[1].data_ptr(), ring3[i % copies3].data_ptr(), lay["gbits"], fy.data_ptr(), 1, pre_N, K, stream)
+            if st != tl.TL_OK:
+                raise tl.TlError(st, "tl_ternary_gemm_1p6")
+        torch.cuda.synchronize()
+        print(json.dumps({"mode": "one_point_six", "launches": args.steps, "M": 1, "N": pre_N, "K": K,
+                          "algorithmic_bytes_per_launch": pre_N * W3.shape[1] + 2 * K + 2 * pre_N}))
+        return
 
     if args.mode == "prefill":
         for _ in range(args.steps):
@@ -516,7 +550,7 @@ def main():
         "roofline": roofline, "cpu_baseline": cpu, "single_calls": single, "warm_same_buffer": warm_same,
         "single_launch_latency_us": latency, "per_call": per_call, "mfma_probe": mfma_probe, "prefill": prefill,
         "mid_batch": mid_batch, "block": block, "formats": formats,
-        "launch_mode": "eager" if args.eager else "hip_graph_replay",
+        "launch_mode": "eager" if args.eager else "hip_graph_replay", "weights": args.weights,
         "host_wall_ms_timed_region_incl_capture": round(wall_ms, 2), "context": PAPER_CONTEXT,
     }
     print(json.dumps(out))
