@@ -421,7 +421,9 @@ def main():
     # Sec. 3.2, same kernel with the table filled from that code) and per-group scales beside the
     # 2-bit, single-gamma kernel (one call each)
     formats = []
+    grouped_formats = None
     if not args.no_per_call:
+        rings3, scales256 = {}, {}
         frng = np.random.default_rng(si.SEEDS["c5"])
         for name in si.DECODE_SWEEP_SHAPES:
             lay = layers[name]
@@ -474,7 +476,51 @@ def main():
                                                                             time_vs_two_bit=round(us3fx / us2, 3)),
                                     two_bit_group_scales_256=dict(us=round(usg, 3), GBps=round((b2 + 2 * (K // group) * N) / usg / 1e3, 1)),
                                     two_bit_group_scales_128=dict(us=round(usg128, 3), GBps=round((b2 + 2 * (K // 128) * N) / usg128 / 1e3, 1))))
-            del ring3, ring3fx
+            rings3[name] = (ring3, copies3, W3.shape[1])
+            scales256[name] = sc
+            del ring3fx
+        # the sweep as ONE grouped launch in the other weight forms (tl_ternary_gemm_1p6_grouped,
+        # tl_ternary_gemm_gs_grouped), beside the 2-bit headline
+        gy = {(name, M): torch.empty((M, layers[name]["N"]), dtype=torch.int16, device=dev) for name, M in calls}
+        cur3 = {name: 0 for name in rings3}
+
+        def step_grouped_1p6():
+            jobs = []
+            for name, M in calls:
+                ring, copies3, _ = rings3[name]
+                i = cur3[name]
+                cur3[name] = (i + 1) % copies3
+                jobs.append((xd[M], ring[i], layers[name]["gbits"], gy[(name, M)], M, layers[name]["N"], K))
+            arr = tl.make_jobs(jobs)
+            st = L.tl_ternary_gemm_1p6_grouped(arr, len(arr), tl.TL_FMT_1P6BIT, stream)
+            if st != tl.TL_OK:
+                raise tl.TlError(st, "tl_ternary_gemm_1p6_grouped")
+
+        def step_grouped_gs():
+            jobs = []
+            for name, M in calls:
+                lay = layers[name]
+                i = cursor[name]
+                cursor[name] = (i + 1) % lay["copies"]
+                jobs.append((xd[M], lay["ring"][i], scales256[name], 256, gy[(name, M)], M, lay["N"], K))
+            arr = tl.make_gs_jobs(jobs)
+            st = L.tl_ternary_gemm_gs_grouped(arr, len(arr), stream)
+            if st != tl.TL_OK:
+                raise tl.TlError(st, "tl_ternary_gemm_gs_grouped")
+
+        reps = max(1, min(args.steps, 200))
+        us3g = per_unit(timed(step_grouped_1p6, reps), reps)[0]
+        usgg = per_unit(timed(step_grouped_gs, reps), reps)[0]
+        b3g = sum(layers[name]["N"] * rings3[name][2] + 2 * M * K + 2 * M * layers[name]["N"] for name, M in calls)
+        bgg = step_bytes + sum(2 * (K // 256) * layers[name]["N"] for name, M in calls)
+        grouped_formats = dict(
+            note="the decode sweep as one grouped launch in the other weight forms; two_bit is the headline",
+            two_bit=dict(us=round(ms_per_step * 1e3, 3), GBps=round(step_bytes / ms_per_step / 1e6, 1)),
+            one_point_six_bit=dict(us=round(us3g, 3), GBps=round(b3g / us3g / 1e3, 1), algorithmic_bytes=b3g,
+                                   time_vs_two_bit=round(us3g / (ms_per_step * 1e3), 3)),
+            two_bit_group_scales_256=dict(us=round(usgg, 3), GBps=round(bgg / usgg / 1e3, 1), algorithmic_bytes=bgg,
+                                          time_vs_two_bit=round(usgg / (ms_per_step * 1e3), 3)))
+        del rings3, gy
 
     # dominant kernel: the small-M kernel in its grouped launch; one launch = one step.  Counter
     # figures come from the rocprofv3 runs summarised under profiles/; they are quoted only while
@@ -549,7 +595,7 @@ def main():
         "timing": {"batches": head["batches"], "steps_per_batch": args.steps, "figure": "median batch", "untimed_load_before_timing_ms": WARM_MS},
         "roofline": roofline, "cpu_baseline": cpu, "single_calls": single, "warm_same_buffer": warm_same,
         "single_launch_latency_us": latency, "per_call": per_call, "mfma_probe": mfma_probe, "prefill": prefill,
-        "mid_batch": mid_batch, "block": block, "formats": formats,
+        "mid_batch": mid_batch, "block": block, "formats": formats, "grouped_formats": grouped_formats,
         "launch_mode": "eager" if args.eager else "hip_graph_replay", "weights": args.weights,
         "host_wall_ms_timed_region_incl_capture": round(wall_ms, 2), "context": PAPER_CONTEXT,
     }

@@ -231,6 +231,38 @@ tl_status tl_ternary_gemm_gs(const void* x, const void* Wpacked, const void* sca
                              void* y, int64_t M, int64_t N, int64_t K, void* stream);
 
 /*
+ * tl_ternary_gemm_grouped for the other two weight forms: several independent products in one
+ * call, enqueued in as few kernel launches as possible (the launch costs as much as streaming
+ * several megabytes, and the paper's kernel benchmark is quoted on all linears of a block,
+ * App. G).  Jobs must not alias each other's outputs; `jobs` is host memory, read before the
+ * call returns; each job has the contract of the single call it stands for.
+ *
+ * tl_ternary_gemm_1p6_grouped: weights in the 1.6-bit layout (Sec. 3.2), all jobs in the same
+ * byte code: `format` is TL_FMT_1P6BIT (tl_pack_1p6bit) or TL_FMT_1P6BIT_FX (tl_pack_1p6bit_fx),
+ * anything else is TL_ERR_VALUE.  Jobs with K % 8 == 0 and K <= 4480 share launches (32 blocks
+ * of 16 activation rows per launch); the others run as tl_ternary_gemm_1p6 / _fx would run them.
+ */
+tl_status tl_ternary_gemm_1p6_grouped(const tl_gemm_job* jobs, int64_t count, tl_format format,
+                                      void* stream);
+
+/*
+ * tl_ternary_gemm_gs_grouped: 2-bit weights with per-group scales (Sec. 3.3; App. G), one group
+ * size per job.  Jobs that tl_ternary_gemm_gs would run in the weight-streaming kernel share
+ * launches (groups that are multiples of 256 weights among themselves, odd multiples of 128
+ * among themselves); the others run one by one.
+ */
+typedef struct tl_gemm_gs_job {
+    const void* x;            /* device, fp16 [M][K]                         */
+    const void* Wpacked;      /* device, TL_FMT_2BIT                         */
+    const void* scales;       /* device, fp16 [ceil(K / group)][N]           */
+    void* y;                  /* device, fp16 [M][N]                         */
+    int64_t M, N, K;
+    int64_t group;            /* weights per scale along K, multiple of 16   */
+} tl_gemm_gs_job;
+
+tl_status tl_ternary_gemm_gs_grouped(const tl_gemm_gs_job* jobs, int64_t count, void* stream);
+
+/*
  * Bandwidth calibration: a plain streaming copy dst[i] = src[i] of `bytes` bytes
  * (multiple of 16, both device pointers 16-byte aligned).  Not part of the
  * method; it gives the HBM counters and timers a kernel of known traffic.

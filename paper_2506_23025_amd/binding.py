@@ -23,7 +23,7 @@ EXPORTS = (
     "tl_status_str", "tl_row_stride_bytes", "tl_packed_bytes", "tl_quantize", "tl_pack_2bit", "tl_pack_1p6bit",
     "tl_pack_1p6bit_fx", "tl_unpack_1p6bit_fx", "tl_unpack", "tl_unpack_dev", "tl_ternary_gemm",
     "tl_ternary_gemm_path", "tl_ternary_gemm_grouped", "tl_ternary_gemm_1p6", "tl_ternary_gemm_1p6_fx",
-    "tl_ternary_gemm_gs",
+    "tl_ternary_gemm_gs", "tl_ternary_gemm_1p6_grouped", "tl_ternary_gemm_gs_grouped",
     "tl_ternary_gemm_which",
     "tl_init",
     "tl_probe_copy",
@@ -37,6 +37,13 @@ class tl_gemm_job(ctypes.Structure):
     _fields_ = [("x", ctypes.c_void_p), ("Wpacked", ctypes.c_void_p), ("y", ctypes.c_void_p),
                 ("M", ctypes.c_int64), ("N", ctypes.c_int64), ("K", ctypes.c_int64),
                 ("gamma_fp16_bits", ctypes.c_uint16)]
+
+
+class tl_gemm_gs_job(ctypes.Structure):
+    """Mirror of struct tl_gemm_gs_job in include/tl.h."""
+    _fields_ = [("x", ctypes.c_void_p), ("Wpacked", ctypes.c_void_p), ("scales", ctypes.c_void_p),
+                ("y", ctypes.c_void_p),
+                ("M", ctypes.c_int64), ("N", ctypes.c_int64), ("K", ctypes.c_int64), ("group", ctypes.c_int64)]
 
 
 class TlError(RuntimeError):
@@ -87,6 +94,10 @@ def _load():
     L.tl_ternary_gemm_1p6_fx.restype = ci
     L.tl_ternary_gemm_gs.argtypes = [vp, vp, vp, i64, vp, i64, i64, i64, vp]
     L.tl_ternary_gemm_gs.restype = ci
+    L.tl_ternary_gemm_1p6_grouped.argtypes = [ctypes.POINTER(tl_gemm_job), i64, ci, vp]
+    L.tl_ternary_gemm_1p6_grouped.restype = ci
+    L.tl_ternary_gemm_gs_grouped.argtypes = [ctypes.POINTER(tl_gemm_gs_job), i64, vp]
+    L.tl_ternary_gemm_gs_grouped.restype = ci
     L.tl_ternary_gemm_which.argtypes = [i64, i64, i64]
     L.tl_ternary_gemm_which.restype = ci
     L.tl_init.argtypes = []
@@ -258,6 +269,27 @@ def tl_ternary_gemm_which(M, N, K):
 def tl_ternary_gemm_gs(x, Wpacked, scales, group, y, M, N, K, stream=None):
     _check(_lib.tl_ternary_gemm_gs(_ptr(x), _ptr(Wpacked), _ptr(scales), group, _ptr(y), M, N, K,
                                    _stream(stream)), "tl_ternary_gemm_gs")
+
+
+def tl_ternary_gemm_1p6_grouped(jobs, fmt=TL_FMT_1P6BIT, stream=None):
+    """jobs: list of (x, Wpacked, gamma_fp16_bits, y, M, N, K) with 1.6-bit weights, or an array made by make_jobs."""
+    arr = jobs if isinstance(jobs, ctypes.Array) else make_jobs(jobs)
+    _check(_lib.tl_ternary_gemm_1p6_grouped(arr, len(arr), fmt, _stream(stream)), "tl_ternary_gemm_1p6_grouped")
+
+
+def make_gs_jobs(jobs):
+    """[(x, Wpacked, scales, group, y, M, N, K), ...] -> ctypes array of tl_gemm_gs_job."""
+    arr = (tl_gemm_gs_job * len(jobs))()
+    for a, (x, Wp, sc, group, y, M, N, K) in zip(arr, jobs):
+        a.x, a.Wpacked, a.scales, a.y = _ptr(x), _ptr(Wp), _ptr(sc), _ptr(y)
+        a.M, a.N, a.K, a.group = M, N, K, group
+    return arr
+
+
+def tl_ternary_gemm_gs_grouped(jobs, stream=None):
+    """jobs: list of (x, Wpacked, scales, group, y, M, N, K), or an array made by make_gs_jobs."""
+    arr = jobs if isinstance(jobs, ctypes.Array) else make_gs_jobs(jobs)
+    _check(_lib.tl_ternary_gemm_gs_grouped(arr, len(arr), _stream(stream)), "tl_ternary_gemm_gs_grouped")
 
 
 def tl_probe_copy(dst, src, nbytes, stream=None):

@@ -256,6 +256,81 @@ tl_status tl_ternary_gemm_gs(const void* x, const void* Wpacked, const void* sca
     return tl::from_hip(tl::launch_gemm_generic_gs(xh, wp, sh, group, yh, M, N, K, s));
 }
 
+tl_status tl_ternary_gemm_1p6_grouped(const tl_gemm_job* jobs, int64_t count, tl_format format, void* stream)
+{
+    if (count == 0) return TL_OK;
+    if (!jobs) return TL_ERR_NULL;
+    if (count < 0 || count > 4096) return TL_ERR_SHAPE;
+    if (format != TL_FMT_1P6BIT && format != TL_FMT_1P6BIT_FX) return TL_ERR_VALUE;
+    for (int64_t i = 0; i < count; ++i) {
+        const tl_gemm_job& j = jobs[i];
+        if (!j.x || !j.Wpacked || !j.y) return TL_ERR_NULL;
+        if (!tl::dims_ok(j.M, j.N, j.K)) return TL_ERR_SHAPE;
+        if (!tl::aligned16(j.x) || !tl::aligned16(j.Wpacked) || !tl::aligned16(j.y)) return TL_ERR_ALIGN;
+    }
+    const bool fx = format == TL_FMT_1P6BIT_FX;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // Jobs whose K fits one pass of the stream form share launches; the others go one by one.
+    tl::Gemm3Desc fused[64];
+    int nf = 0;
+    auto flush = [&]() -> tl_status {
+        if (nf == 0) return TL_OK;
+        const hipError_t e = tl::launch_gemv3_jobs(fused, nf, fx, s);
+        nf = 0;
+        return tl::from_hip(e);
+    };
+    for (int64_t i = 0; i < count; ++i) {
+        const tl_gemm_job& j = jobs[i];
+        if (tl::gemv3_groups(j.M, j.N, j.K)) {
+            fused[nf++] = tl::Gemm3Desc{static_cast<const __half*>(j.x), static_cast<const uint8_t*>(j.Wpacked),
+                                        static_cast<__half*>(j.y), tl::half_bits_to_float(j.gamma_fp16_bits),
+                                        j.M, j.N, j.K, static_cast<int64_t>(tl_row_stride_bytes(TL_FMT_1P6BIT, j.K))};
+            if (nf == 64) { const tl_status st = flush(); if (st != TL_OK) return st; }
+        } else {
+            const tl_status st = gemm_1p6(j.x, j.Wpacked, j.gamma_fp16_bits, j.y, j.M, j.N, j.K, stream, fx);
+            if (st != TL_OK) return st;
+        }
+    }
+    return flush();
+}
+
+tl_status tl_ternary_gemm_gs_grouped(const tl_gemm_gs_job* jobs, int64_t count, void* stream)
+{
+    if (count == 0) return TL_OK;
+    if (!jobs) return TL_ERR_NULL;
+    if (count < 0 || count > 4096) return TL_ERR_SHAPE;
+    for (int64_t i = 0; i < count; ++i) {
+        const tl_gemm_gs_job& j = jobs[i];
+        if (!j.x || !j.Wpacked || !j.scales || !j.y) return TL_ERR_NULL;
+        if (!tl::dims_ok(j.M, j.N, j.K)) return TL_ERR_SHAPE;
+        if (j.group < 16 || j.group % 16 != 0) return TL_ERR_SHAPE;
+        if (!tl::aligned16(j.x) || !tl::aligned16(j.Wpacked) || !tl::aligned16(j.scales) || !tl::aligned16(j.y)) return TL_ERR_ALIGN;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // Jobs the weight-streaming kernel takes share launches; the others go one by one.
+    tl::GemmGsDesc fused[64];
+    int nf = 0;
+    auto flush = [&]() -> tl_status {
+        if (nf == 0) return TL_OK;
+        const hipError_t e = tl::launch_gemv_gs_jobs(fused, nf, s);
+        nf = 0;
+        return tl::from_hip(e);
+    };
+    for (int64_t i = 0; i < count; ++i) {
+        const tl_gemm_gs_job& j = jobs[i];
+        if (tl::gemv_gs_supports(j.M, j.N, j.K, j.group)) {
+            fused[nf++] = tl::GemmGsDesc{static_cast<const __half*>(j.x), static_cast<const uint32_t*>(j.Wpacked),
+                                         static_cast<const __half*>(j.scales), static_cast<__half*>(j.y),
+                                         j.M, j.N, j.K, j.group};
+            if (nf == 64) { const tl_status st = flush(); if (st != TL_OK) return st; }
+        } else {
+            const tl_status st = tl_ternary_gemm_gs(j.x, j.Wpacked, j.scales, j.group, j.y, j.M, j.N, j.K, stream);
+            if (st != TL_OK) return st;
+        }
+    }
+    return flush();
+}
+
 tl_status tl_init(void)
 {
     hipError_t e = tl::gemv_init();

@@ -38,6 +38,7 @@
 //    general form (gemv_kernel) loops a wave over slices and a workgroup over items of any
 //    job; it takes lone calls with long K.
 #include "tl_internal.hpp"
+#include "tl_deal.hpp"
 
 #include <cstddef>
 #include <type_traits>
@@ -1231,65 +1232,23 @@ hipError_t launch_stream(GemvBatch& b, int max_slices, int nb, hipStream_t s, in
     // workgroups, so that a CU still runs 8 waves (K = 1024: 1024 workgroups of 2 waves).
     const int64_t g_max = int64_t(pol.stream_groups) * (kStreamWaves / NW);
     const int G = total_tiles < g_max ? int(total_tiles) : int(g_max);
-    // Time of a workgroup of job j with w groups, in tile units: passes x (run time + start-up).
-    // The start-up of a pass is fetching the activation slice (1 KB per row and wave through the
-    // same address path as the weights) and building the operands: measured about 0.15 tiles per
+    // Time of a workgroup in tile units: passes x (run time + start-up), see tl_deal.hpp.  The
+    // start-up of a pass is fetching the activation slice (1 KB per row and wave through the same
+    // address path as the weights) and building the operands: measured about 0.15 tiles per
     // activation row; a job of several passes pays part of that round trip in every pass but the
-    // first (pass_start tiles).  Bisection on the common finishing time gives the group counts.
-    auto start_up = [&](int j) {
+    // first (pass_start tiles).  A run is worked off in items of up to t_max tiles, and an item
+    // costs its latency and barrier once: measured (block launch, runs of 15 ... 19 tiles) 1.0 us
+    // for the first tile of an item and 0.2 us for each further one, i.e. 2.1 and 0.43 in units
+    // of an average tile.
+    const DealModel model{(nb == 2 || gs == 4) ? 2 : 3, pol.item_cost != 0, pol.item_first, pol.tile_extra};
+    DealJob dj[kMaxJobs];
+    for (int j = 0; j < b.count; ++j) {
         const int rows = b.job[j].Mrem < 16 * nb ? b.job[j].Mrem : 16 * nb;
-        return pol.start_up_per_row * double(rows) + (passes(j) > 1 ? pol.pass_start : 0.0);
-    };
-    // A run is worked off in items of up to t_max tiles (4 tiles: 2 + 2), and an item costs its
-    // latency and barrier once: measured (block launch, runs of 15 ... 19 tiles) 1.0 us for the
-    // first tile of an item and 0.2 us for each further one, i.e. 2.1 and 0.43 in units of an average tile.
-    const int t_max = (nb == 2 || gs == 4) ? 2 : 3;
-    auto run_time = [&](int run) {
-        if (!pol.item_cost) return double(run);
-        const int items = run <= t_max ? 1 : ((t_max == 3 && run == 4) ? 2 : (run + t_max - 1) / t_max);
-        return pol.item_first * double(items) + pol.tile_extra * double(run - items);
-    };
-    auto run_cost = [&](int j, int w) {
-        return double(passes(j)) * (run_time((b.job[j].tiles + w - 1) / w) + start_up(j));
-    };
-    auto groups_for = [&](int j, double tau) {            // fewest groups that finish job j by tau
-        const double per = tau / double(passes(j)) - start_up(j);
-        // longest run that fits: from the estimate with whole items, a few steps up or down
-        const double per_tile = pol.item_cost ? (pol.item_first + pol.tile_extra * double(t_max - 1)) / double(t_max) : 1.0;
-        int run = int(per / per_tile);
-        if (run < 1) run = 1;
-        if (run > b.job[j].tiles) run = b.job[j].tiles;
-        while (run > 1 && run_time(run) > per) --run;
-        while (run < b.job[j].tiles && run_time(run + 1) <= per) ++run;
-        if (run_time(run) > per) return b.job[j].tiles;
-        const int w = (b.job[j].tiles + run - 1) / run;
-        return w < 1 ? 1 : (w > b.job[j].tiles ? b.job[j].tiles : w);
-    };
-    double lo = 0.0, hi = 0.0;
-    for (int j = 0; j < b.count; ++j) { const double c = run_cost(j, 1); if (c > hi) hi = c; }
-    for (int it = 0; it < 24; ++it) {
-        const double mid = 0.5 * (lo + hi);
-        int need = 0;
-        for (int j = 0; j < b.count; ++j) need += groups_for(j, mid);
-        if (need <= G) hi = mid; else lo = mid;
+        dj[j] = DealJob{b.job[j].tiles, passes(j),
+                        pol.start_up_per_row * double(rows) + (passes(j) > 1 ? pol.pass_start : 0.0)};
     }
     int wg[kMaxJobs];
-    int used = 0;
-    for (int j = 0; j < b.count; ++j) { wg[j] = groups_for(j, hi); used += wg[j]; }
-    while (used < G) {                                     // spare groups: shorten the costliest run
-        int best = -1;
-        for (int j = 0; j < b.count; ++j)
-            if (wg[j] < b.job[j].tiles && (best < 0 || run_cost(j, wg[j]) > run_cost(best, wg[best]))) best = j;
-        if (best < 0) break;
-        ++wg[best]; ++used;
-    }
-    while (used > G) {                                     // cannot happen unless there are more jobs than groups
-        int best = -1;
-        for (int j = 0; j < b.count; ++j)
-            if (wg[j] > 1 && (best < 0 || run_cost(j, wg[j]) < run_cost(best, wg[best]))) best = j;
-        if (best < 0) break;
-        --wg[best]; --used;
-    }
+    deal_workgroups(model, dj, b.count, G, wg);
     int run = 1;                                           // longest run of tiles of a workgroup
     for (int j = 0; j < b.count; ++j) {
         const int r = (b.job[j].tiles + wg[j] - 1) / wg[j];
@@ -1547,38 +1506,73 @@ bool gemv_gs_supports(int64_t M, int64_t N, int64_t K, int64_t group)
            (slices <= kStreamWaves || (N + 15) / 16 <= int64_t(256) * kStreamMaxRun);
 }
 
+hipError_t launch_gemv_gs_jobs(const GemmGsDesc* jobs, int count, hipStream_t s)
+{
+    for (int i = 0; i < count; ++i)
+        if (!gemv_gs_supports(jobs[i].M, jobs[i].N, jobs[i].K, jobs[i].group)) return hipErrorInvalidValue;
+    // Jobs whose groups are multiples of 256 weights and jobs with odd multiples of 128 run in
+    // different instances of the kernel; each kind shares launches, kMaxJobs blocks of 16
+    // activation rows per launch.  A launch whose runs would not fit the LDS of a multi-pass
+    // workgroup (launch_stream says so without launching) goes out as one launch per job.
+    for (int units = 2; units <= 4; units += 2) {
+        GemvBatch b;
+        b.count = 0;
+        int max_slices = 1;
+        auto flush = [&]() -> hipError_t {
+            if (b.count == 0) return hipSuccess;
+            hipError_t e = launch_stream(b, max_slices, 1, s, units);
+            if (e == hipErrorInvalidValue && b.count > 1) {
+                // one launch per row block; a block alone fits by gemv_gs_supports
+                e = hipSuccess;
+                for (int q = 0; q < b.count && e == hipSuccess; ++q) {
+                    GemvBatch one;
+                    one.count = 1;
+                    one.job[0] = b.job[q];
+                    e = launch_stream(one, one.job[0].slices, 1, s, units);
+                }
+            }
+            b.count = 0;
+            max_slices = 1;
+            return e;
+        };
+        for (int i = 0; i < count; ++i) {
+            const GemmGsDesc& d = jobs[i];
+            if ((d.group % 256 == 0 ? 2 : 4) != units) continue;
+            const int slices = int((d.K + kSliceK - 1) / kSliceK);
+            const int hpg = int(d.group / (kSliceK / units));
+            for (int64_t m0 = 0; m0 < d.M; m0 += 16) {
+                GemvJob j;
+                j.x = d.x + m0 * d.K;
+                j.W = d.W;
+                j.y = d.y + m0 * d.N;
+                j.gamma = 1.f;
+                j.Mrem = int(d.M - m0 < 16 ? d.M - m0 : 16);
+                j.N = int(d.N); j.K = int(d.K);
+                j.tiles = int((d.N + 15) / 16);
+                j.items = 0;
+                j.slices = slices;
+                j.mr = pow2_at_least(j.Mrem);
+                j.run = j.plus = 0;
+                j.scales = d.scales; j.hpg = hpg; j.reserved = 0;
+                b.job[b.count++] = j;
+                if (slices > max_slices) max_slices = slices;
+                if (b.count == kMaxJobs) {
+                    const hipError_t e = flush();
+                    if (e != hipSuccess) return e;
+                }
+            }
+        }
+        const hipError_t e = flush();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
 hipError_t launch_gemv_gs(const __half* x, const uint32_t* Wp, const __half* scales, int64_t group,
                           __half* y, int64_t M, int64_t N, int64_t K, hipStream_t s)
 {
-    if (!gemv_gs_supports(M, N, K, group)) return hipErrorInvalidValue;
-    const int slices = int((K + kSliceK - 1) / kSliceK);
-    // scale units per slice: 2 of 256 weights when the groups allow, else 4 of 128; hpg = units per group
-    const int units = group % 256 == 0 ? 2 : 4;
-    const int hpg = int(group / (kSliceK / units));
-    GemvBatch b;
-    b.count = 0;
-    for (int64_t m0 = 0; m0 < M; m0 += 16) {
-        GemvJob j;
-        j.x = x + m0 * K;
-        j.W = Wp;
-        j.y = y + m0 * N;
-        j.gamma = 1.f;
-        j.Mrem = int(M - m0 < 16 ? M - m0 : 16);
-        j.N = int(N); j.K = int(K);
-        j.tiles = int((N + 15) / 16);
-        j.items = 0;
-        j.slices = slices;
-        j.mr = pow2_at_least(j.Mrem);
-        j.run = j.plus = 0;
-        j.scales = scales; j.hpg = hpg; j.reserved = 0;
-        b.job[b.count++] = j;
-        if (b.count == kMaxJobs || m0 + 16 >= M) {
-            const hipError_t e = launch_stream(b, slices, 1, s, units);
-            if (e != hipSuccess) return e;
-            b.count = 0;
-        }
-    }
-    return hipSuccess;
+    const GemmGsDesc d{x, Wp, scales, y, M, N, K, group};
+    return launch_gemv_gs_jobs(&d, 1, s);
 }
 
 hipError_t launch_gemv(const __half* x, const uint32_t* Wp, float gamma, __half* y,

@@ -9,10 +9,12 @@
 //
 //  * A slice is 128 packed bytes = 640 weights per row; a lane's 16 bytes hold 80 weights.
 //  * Decode is a table look-up: a 256-entry table of 8-byte entries in LDS maps a byte to its
-//    five digits c = w + 1 as fp16 (subnormal) pairs: word 0 = c0 << 4 | c2 << 8 | c3 << 20,
-//    word 1 = c1 << 4 | c4 << 20.  The two words of two neighbouring bytes, with c2 masked out
+//    five digits c = w + 1 as fp16 (subnormal) pairs: word 0 = c0 << 6 | c2 << 8 | c3 << 22,
+//    word 1 = c1 << 6 | c4 << 22 (every digit at bit 6 or above of its half: the matrix
+//    instruction aligns products by exponent field, and subnormals with only their lowest bits set
+//    lose low-order product bits).  The two words of two neighbouring bytes, with c2 masked out
 //    of the first word of each, are one A operand of v_mfma_f32_16x16x32_f16 as they stand:
-//    (c0, c3) 2^-20, (c1, c4) 2^-20 per byte, against the activation pairs (x[5b], x[5b+3]) and
+//    (c0, c3) 2^-18, (c1, c4) 2^-18 per byte, against the activation pairs (x[5b], x[5b+3]) and
 //    (x[5b+1], x[5b+4]); the c2 digits of four bytes, masked out the other way, are a third
 //    operand (c2, 0) 2^-16 against (x[5b+2], 0).  Per 5 weights: 1 address operation (a shift
 //    with a byte select), 1 LDS read, 2 ANDs; all sixteen look-ups of a half tile are issued
@@ -26,6 +28,7 @@
 //    keeps its slice, a workgroup walks a run of tiles in items with the next item's weights in
 //    flight.  gemv3_kernel (longer K): waves loop over slices, one item per workgroup.
 #include "tl_internal.hpp"
+#include "tl_deal.hpp"
 
 #include <type_traits>
 
@@ -99,7 +102,7 @@ __device__ __forceinline__ void fill_table(u32x2* lut, bool fx)
 #pragma unroll
             for (int i = 0; i < 5; ++i) { c[i] = v % 3u; v /= 3u; }
         }
-        lut[b] = u32x2{(c[0] << 4) | (c[2] << 8) | (c[3] << 20), (c[1] << 4) | (c[4] << 20)};
+        lut[b] = u32x2{(c[0] << 6) | (c[2] << 8) | (c[3] << 22), (c[1] << 6) | (c[4] << 22)};
     }
 }
 
@@ -134,11 +137,11 @@ __device__ __forceinline__ void build_operands(const unsigned char* row, int mg,
     }
 }
 
-// -2^-20 sum_k x over the slice, in accumulator layout (constant 16-row operand)
+// -2^-18 sum_k x over the slice, in accumulator layout (constant 16-row operand)
 __device__ __forceinline__ f32x4 seed_from(const u32x4 (&bop)[2][4][3])
 {
     f32x4 nsx = f32x4{0.f, 0.f, 0.f, 0.f};
-    const uint32_t c = 0x80108010u;
+    const uint32_t c = 0x80408040u;
     const u32x4 a = u32x4{c, c, c, c};
 #pragma unroll
     for (int h = 0; h < 2; ++h)
@@ -173,14 +176,14 @@ __device__ __forceinline__ f32x4 tile_sum(const unsigned char* reg_t, uint32_t w
             // bytes 0,1 and 2,3 of the dword: the two table words of a byte pair are an operand
             // as they stand once c2 is masked out of the first word of each
             const u32x4 a2 = u32x4{e[d][0][0] & 0x300u, e[d][1][0] & 0x300u, e[d][2][0] & 0x300u, e[d][3][0] & 0x300u};
-            const u32x4 a01 = u32x4{e[d][0][0] & 0x00300030u, e[d][0][1], e[d][1][0] & 0x00300030u, e[d][1][1]};
-            const u32x4 a23 = u32x4{e[d][2][0] & 0x00300030u, e[d][2][1], e[d][3][0] & 0x00300030u, e[d][3][1]};
+            const u32x4 a01 = u32x4{e[d][0][0] & 0x00c000c0u, e[d][0][1], e[d][1][0] & 0x00c000c0u, e[d][1][1]};
+            const u32x4 a23 = u32x4{e[d][2][0] & 0x00c000c0u, e[d][2][1], e[d][3][0] & 0x00c000c0u, e[d][3][1]};
             acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(a01), as_h8(bop[h][d][0]), acc[0], 0, 0, 0);
             acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(a23), as_h8(bop[h][d][1]), acc[1], 0, 0, 0);
             acc[2] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(a2), as_h8(bop[h][d][2]), acc[2], 0, 0, 0);
         }
     }
-    return (acc[0] + acc[1]) * 1048576.f + acc[2] * 65536.f;
+    return (acc[0] + acc[1]) * 262144.f + acc[2] * 65536.f;
 }
 
 template <int T>
@@ -330,9 +333,30 @@ gemv3_kernel(Gemv3Params p)
 // a tile's registers are free, two alternating sets of partial sums and one LDS-only barrier
 // per item -- the organisation of the 2-bit stream kernel (tl_gemv.hip) with this file's
 // decode.  Params::groups workgroups; workgroup g takes tiles [g per + min(g, extra), ...).
+// What a workgroup of the stream form works on: one block of at most 16 activation rows of one
+// GEMM and a run of consecutive tiles of its matrix.  x and y point at the block's first row.
+struct Run3 {
+    const unsigned char* W;   // the matrix (first row)
+    const unsigned char* x;
+    __half* y;
+    float gamma;
+    int K, N;
+    int stride;               // bytes per packed row
+    int Mrem;                 // activation rows, 1..16
+    int tile0, tile_end;      // the run
+    int slices;               // waves with a slice of K (the others idle along)
+    int fx;                   // which byte code the table is filled for
+};
+static_assert(sizeof(Run3) == 64, "one record per 64-byte line");
+
+constexpr int kRec3Max = 256;  // records (workgroups) of a grouped launch: 16 KB of kernel arguments
+
+struct Rec3Batch {
+    Run3 rec[kRec3Max];
+};
+
 template <int T>
-__global__ void __launch_bounds__(512)
-gemv3_stream_kernel(Gemv3Params p)
+__device__ __forceinline__ void gemv3_stream_body(const Run3& p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     const int lane = threadIdx.x & 63;
@@ -342,18 +366,15 @@ gemv3_stream_kernel(Gemv3Params p)
     unsigned char* const my_lds = lds_raw + kLutBytes + wave * kWave3Lds;
     auto lut_at = [](uint32_t off) { return *(const __attribute__((address_space(3))) u32x2*)(uintptr_t(off)); };
 
-    const int m0 = blockIdx.y * 16;
-    const int Mrem = (p.M - m0 < 16) ? (p.M - m0) : 16;
+    const int Mrem = p.Mrem;
     int MR = 1;
     while (MR < Mrem) MR *= 2;
     const int K = p.K, N = p.N;
     const uint32_t stride = uint32_t(p.stride);
     const int chunks = p.stride >> 4;
-    const int tiles = p.tiles;
-    const int per = tiles / p.groups, extra = tiles % p.groups;
-    const int g = blockIdx.x;
-    const int tile0 = g * per + (g < extra ? g : extra);
-    const int tile_end = tile0 + per + (g < extra ? 1 : 0);
+    const int tiles = (N + 15) >> 4;
+    const int tile0 = p.tile0;
+    const int tile_end = p.tile_end;
     const int n_items = (tile_end - tile0 + T - 1) / T;
 
     const int lr = lane >> 3, lc = lane & 7;
@@ -364,7 +385,7 @@ gemv3_stream_kernel(Gemv3Params p)
     const uint32_t wr_off1 = uint32_t(mi) * 128u + (uint32_t((4 + mg) ^ (mi & 7)) << 4);
 
     const unsigned char* const Wb = p.W;
-    const unsigned char* const xb = reinterpret_cast<const unsigned char*>(p.x + size_t(m0) * K);
+    const unsigned char* const xb = p.x;
     const bool active = wave < p.slices;
     uint32_t col_off;
     {
@@ -455,7 +476,7 @@ gemv3_stream_kernel(Gemv3Params p)
             const int n = tile * 16 + 4 * (l >> 4);
             if (tile < tile_end && (l & 15) < Mrem) {
                 typedef __attribute__((address_space(1))) __half* gh_ptr;
-                gh_ptr dst = (gh_ptr)(p.y + size_t(m0 + (l & 15)) * N + n);
+                gh_ptr dst = (gh_ptr)(p.y + size_t(l & 15) * N + n);
                 const float gamma = p.gamma;
                 if (n + 3 < N && (N & 3) == 0) {           // four consecutive n: one 8-byte store
                     const f16x2 lo = {(_Float16)(gamma * s[0]), (_Float16)(gamma * s[1])};
@@ -473,6 +494,36 @@ gemv3_stream_kernel(Gemv3Params p)
     int i = 0;
     for (; i + 1 < n_items; ++i) item(std::true_type{}, tile0 + i * T, i & 1);
     item(std::false_type{}, tile0 + i * T, i & 1);
+}
+
+// One GEMM: blockIdx.y is the block of 16 activation rows, the tiles are split evenly over gridDim.x.
+template <int T>
+__global__ void __launch_bounds__(512)
+gemv3_stream_kernel(Gemv3Params p)
+{
+    const int m0 = blockIdx.y * 16;
+    const int per = p.tiles / p.groups, extra = p.tiles % p.groups;
+    const int g = blockIdx.x;
+    Run3 r;
+    r.W = p.W;
+    r.x = reinterpret_cast<const unsigned char*>(p.x + size_t(m0) * p.K);
+    r.y = p.y + size_t(m0) * p.N;
+    r.gamma = p.gamma;
+    r.K = p.K; r.N = p.N; r.stride = p.stride;
+    r.Mrem = (p.M - m0 < 16) ? (p.M - m0) : 16;
+    r.tile0 = g * per + (g < extra ? g : extra);
+    r.tile_end = r.tile0 + per + (g < extra ? 1 : 0);
+    r.slices = p.slices;
+    r.fx = p.fx;
+    gemv3_stream_body<T>(r);
+}
+
+// Several GEMMs: the host has dealt out the workgroups and written one record for each.
+template <int T>
+__global__ void __launch_bounds__(512)
+gemv3_grouped_kernel(Rec3Batch b)
+{
+    gemv3_stream_body<T>(b.rec[blockIdx.x]);
 }
 
 using Kernel3Fn = void (*)(Gemv3Params);
@@ -496,6 +547,19 @@ Kernel3Fn pick3_stream(int T)
     }
 }
 
+using Grouped3Fn = void (*)(Rec3Batch);
+
+Grouped3Fn pick3_grouped(int T)
+{
+    switch (T) {
+        case 1: return gemv3_grouped_kernel<1>;
+        case 2: return gemv3_grouped_kernel<2>;
+        default: return gemv3_grouped_kernel<3>;
+    }
+}
+
+constexpr int kMaxBlocks3 = 32;          // blocks of 16 activation rows per grouped launch
+
 }  // namespace
 
 hipError_t gemv3_init()
@@ -507,6 +571,9 @@ hipError_t gemv3_init()
         if (e == hipSuccess && T <= 3)
             e = hipFuncSetAttribute(reinterpret_cast<const void*>(pick3_stream(T)),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, kNW3Max * kWave3Lds + kLutBytes);
+        if (e == hipSuccess && T <= 3)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(pick3_grouped(T)),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kNW3Max * kWave3Lds + kLutBytes);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
@@ -516,6 +583,94 @@ bool gemv3_supports(int64_t M, int64_t N, int64_t K)
 {
     return M >= 1 && N >= 1 && K >= 8 && (K % 8) == 0 && K <= (int64_t(1) << 24) &&
            N <= (int64_t(1) << 24) && (M + 15) / 16 <= 65535;
+}
+
+bool gemv3_groups(int64_t M, int64_t N, int64_t K)
+{
+    // K in one pass of the stream form: at most kNW3Max slices of 128 packed bytes
+    return gemv3_supports(M, N, K) && (K + 4) / 5 <= int64_t(kNW3Max) * 128;
+}
+
+// Several GEMMs in one launch of the stream form: every block of 16 activation rows of every GEMM
+// is a job, the 256 workgroups are dealt out to the jobs (tl_deal.hpp; the cost model is the one
+// measured for the 2-bit kernel, whose item structure this kernel shares), and each workgroup
+// gets a record with its run.
+hipError_t launch_gemv3_jobs(const Gemm3Desc* jobs, int count, bool fx, hipStream_t s)
+{
+    for (int i = 0; i < count; ++i)
+        if (!gemv3_groups(jobs[i].M, jobs[i].N, jobs[i].K)) return hipErrorInvalidValue;
+    struct Block { int job; int64_t m0; int rows; };
+    Block blk[kMaxBlocks3];
+    int nb = 0;
+    static bool lds_raised[kMaxDevices][4];
+    auto flush = [&]() -> hipError_t {
+        if (nb == 0) return hipSuccess;
+        DealJob dj[kMaxBlocks3];
+        int NW = 1;
+        int64_t total_tiles = 0;
+        for (int q = 0; q < nb; ++q) {
+            const Gemm3Desc& d = jobs[blk[q].job];
+            const int tiles = int((d.N + 15) / 16);
+            const int slices = int((d.stride + 127) / 128);
+            dj[q] = DealJob{tiles, 1, 0.15 * double(blk[q].rows)};
+            total_tiles += tiles;
+            if (slices > NW) NW = slices;
+        }
+        const int G = total_tiles < kRec3Max ? int(total_tiles) : kRec3Max;
+        const DealModel model{3, true, 2.1, 0.43};
+        int wg[kMaxBlocks3];
+        deal_workgroups(model, dj, nb, G, wg);
+        int run = 1, grid = 0;
+        for (int q = 0; q < nb; ++q) {
+            const int r = (dj[q].tiles + wg[q] - 1) / wg[q];
+            if (r > run) run = r;
+            grid += wg[q];
+        }
+        if (grid > kRec3Max) return hipErrorInvalidValue;   // more jobs than workgroups: cannot happen with kMaxBlocks3 <= kRec3Max
+        int T = run <= 3 ? run : (run == 4 ? 2 : 3);
+        if (T > NW) T = NW;                                // the epilogue gives every thread at most one output quad
+        Rec3Batch rb;
+        int g = 0;
+        for (int q = 0; q < nb; ++q) {
+            const Gemm3Desc& d = jobs[blk[q].job];
+            const int per = dj[q].tiles / wg[q], plus = dj[q].tiles % wg[q];
+            for (int w = 0; w < wg[q]; ++w) {
+                Run3& r = rb.rec[g++];
+                r.W = d.W;
+                r.x = reinterpret_cast<const unsigned char*>(d.x + blk[q].m0 * d.K);
+                r.y = d.y + blk[q].m0 * d.N;
+                r.gamma = d.gamma;
+                r.K = int(d.K); r.N = int(d.N); r.stride = int(d.stride);
+                r.Mrem = blk[q].rows;
+                r.tile0 = w * per + (w < plus ? w : plus);
+                r.tile_end = r.tile0 + per + (w < plus ? 1 : 0);
+                r.slices = int((d.stride + 127) / 128);
+                r.fx = fx ? 1 : 0;
+            }
+        }
+        Grouped3Fn fn = pick3_grouped(T);
+        const int dev = device_slot();
+        if (dev < 0 || !lds_raised[dev][T]) {
+            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                     kNW3Max * kWave3Lds + kLutBytes);
+            if (e != hipSuccess) return e;
+            if (dev >= 0) lds_raised[dev][T] = true;
+        }
+        hipLaunchKernelGGL(fn, dim3(grid), dim3(NW * 64), size_t(NW) * kWave3Lds + kLutBytes, s, rb);
+        nb = 0;
+        return hipGetLastError();
+    };
+    for (int i = 0; i < count; ++i) {
+        for (int64_t m0 = 0; m0 < jobs[i].M; m0 += 16) {
+            blk[nb++] = Block{i, m0, int(jobs[i].M - m0 < 16 ? jobs[i].M - m0 : 16)};
+            if (nb == kMaxBlocks3) {
+                const hipError_t e = flush();
+                if (e != hipSuccess) return e;
+            }
+        }
+    }
+    return flush();
 }
 
 hipError_t launch_gemv3(const __half* x, const uint8_t* Wp, int64_t stride, float gamma, __half* y,

@@ -72,6 +72,15 @@ hipError_t launch_gemv_jobs(const GemmDesc* jobs, int count, hipStream_t s);
 bool gemv_gs_supports(int64_t M, int64_t N, int64_t K, int64_t group);
 hipError_t launch_gemv_gs(const __half* x, const uint32_t* Wp, const __half* scales, int64_t group,
                           __half* y, int64_t M, int64_t N, int64_t K, hipStream_t s);
+// Several such GEMMs (each passing gemv_gs_supports) in as few launches as possible.
+struct GemmGsDesc {
+    const __half* x;
+    const uint32_t* W;
+    const __half* scales;
+    __half* y;
+    int64_t M, N, K, group;
+};
+hipError_t launch_gemv_gs_jobs(const GemmGsDesc* jobs, int count, hipStream_t s);
 // Plain VALU kernel with per-group scales: any M, N, K; group % 16 == 0.
 hipError_t launch_gemm_generic_gs(const __half* x, const uint32_t* Wp, const __half* scales,
                                   int64_t group, __half* y, int64_t M, int64_t N, int64_t K,
@@ -81,6 +90,17 @@ hipError_t launch_gemm_generic_gs(const __half* x, const uint32_t* Wp, const __h
 bool gemv3_supports(int64_t M, int64_t N, int64_t K);
 hipError_t launch_gemv3(const __half* x, const uint8_t* Wp, int64_t stride, float gamma, __half* y,
                         int64_t M, int64_t N, int64_t K, bool fx, hipStream_t s);
+// Several 1.6-bit GEMMs (each passing gemv3_groups: K in one pass of the stream form) in as few
+// launches as possible; all in the same byte code (fx).
+struct Gemm3Desc {
+    const __half* x;
+    const uint8_t* W;
+    __half* y;
+    float gamma;
+    int64_t M, N, K, stride;
+};
+bool gemv3_groups(int64_t M, int64_t N, int64_t K);
+hipError_t launch_gemv3_jobs(const Gemm3Desc* jobs, int count, bool fx, hipStream_t s);
 
 // LDS-tiled MFMA prefill kernel (2-bit).  Needs K % 64 == 0.
 bool mfma_supports(int64_t M, int64_t N, int64_t K);
