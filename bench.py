@@ -373,6 +373,32 @@ def main():
                             kernel_vs_mfma_probe=round(fl / us / 1e6 / mfma_probe["TFLOPs"], 4),
                             tl_ternary_gemm=dict(kernel=which, us=round(us_auto, 2), TFLOPs=round(fl / us_auto / 1e6, 1),
                                                  mfma_frac=round(fl / us_auto / 1e6 / MFMA_PEAK_TFLOPS, 4))))
+    if prefill:
+        # The same launch on operands that switch nothing in the matrix pipes (x = 0, every weight 0):
+        # the instruction stream is identical, so the difference to the row above is what the chip's
+        # power management takes at the workload's data, and this figure is what the kernel's own
+        # structure (waits, tile rounds) allows.
+        M = max(pre_M)
+        zx = torch.zeros_like(pre_x)
+        zw = torch.from_numpy(tl.tl_pack_2bit(np.zeros((pre_N, K), dtype=np.int8)).view(np.int32)).to(dev)
+        zrings = [zw.clone() for _ in range(4)]
+        zc = [0]
+
+        def launch_zero():
+            i = zc[0]
+            zc[0] = (i + 1) % len(zrings)
+            st_ = L.tl_ternary_gemm_path(zx.data_ptr(), zrings[i].data_ptr(), layers[pre_name]["gbits"],
+                                         pre_y.data_ptr(), M, pre_N, K, stream, tl.TL_PATH_MFMA)
+            if st_ != tl.TL_OK:
+                raise tl.TlError(st_, "tl_ternary_gemm_path")
+
+        reps = max(1, min(args.steps, 40))
+        st = timed(launch_zero, reps)
+        us = per_unit(st, reps)[0]
+        fl = 2.0 * M * pre_N * K
+        prefill[-1]["same_kernel_zero_operands"] = dict(**us_row(st, reps), TFLOPs=round(fl / us / 1e6, 1),
+                                                        mfma_frac=round(fl / us / 1e6 / MFMA_PEAK_TFLOPS, 4))
+        del zx, zw, zrings
     for M in ([] if args.no_per_call else (32, 64, 128, 256, 512)):
         reps = max(1, min(args.steps, 40))
         st = timed(lambda: launch_prefill(M, tl.TL_PATH_AUTO), reps)
