@@ -181,6 +181,23 @@ def test_error_codes():
     assert L.tl_ternary_gemm_gs(16, 16, 16, 24, 16, 1, 1, 16, None) == tl.TL_ERR_SHAPE
     assert L.tl_ternary_gemm_gs(16, 16, 16, 0, 16, 1, 1, 16, None) == tl.TL_ERR_SHAPE
     assert L.tl_ternary_gemm_gs(16, 16, 8, 256, 16, 1, 1, 16, None) == tl.TL_ERR_ALIGN
+    # the grouped forms check every job before anything is launched
+    ok = tl.make_jobs([(16, 16, 0, 32, 1, 16, 64)])
+    assert L.tl_ternary_gemm_1p6_grouped(None, 0, tl.TL_FMT_1P6BIT, None) == tl.TL_OK
+    assert L.tl_ternary_gemm_1p6_grouped(None, 2, tl.TL_FMT_1P6BIT, None) == tl.TL_ERR_NULL
+    assert L.tl_ternary_gemm_1p6_grouped(ok, 1, tl.TL_FMT_2BIT, None) == tl.TL_ERR_VALUE
+    assert L.tl_ternary_gemm_1p6_grouped(ok, 1, 7, None) == tl.TL_ERR_VALUE
+    assert L.tl_ternary_gemm_1p6_grouped(ok, -1, tl.TL_FMT_1P6BIT_FX, None) == tl.TL_ERR_SHAPE
+    assert L.tl_ternary_gemm_1p6_grouped(tl.make_jobs([(16, 16, 0, 32, 1, 16, 64), (16, 16, 0, 0, 1, 16, 64)]), 2,
+                                         tl.TL_FMT_1P6BIT, None) == tl.TL_ERR_NULL
+    assert L.tl_ternary_gemm_1p6_grouped(tl.make_jobs([(16, 24, 0, 32, 1, 16, 64)]), 1, tl.TL_FMT_1P6BIT, None) == tl.TL_ERR_ALIGN
+    assert L.tl_ternary_gemm_1p6_grouped(tl.make_jobs([(16, 16, 0, 32, 1, 0, 64)]), 1, tl.TL_FMT_1P6BIT, None) == tl.TL_ERR_SHAPE
+    assert L.tl_ternary_gemm_gs_grouped(None, 0, None) == tl.TL_OK
+    assert L.tl_ternary_gemm_gs_grouped(None, 2, None) == tl.TL_ERR_NULL
+    assert L.tl_ternary_gemm_gs_grouped(tl.make_gs_jobs([(16, 16, 0, 256, 32, 1, 16, 64)]), 1, None) == tl.TL_ERR_NULL
+    assert L.tl_ternary_gemm_gs_grouped(tl.make_gs_jobs([(16, 16, 24, 256, 32, 1, 16, 64)]), 1, None) == tl.TL_ERR_ALIGN
+    assert L.tl_ternary_gemm_gs_grouped(tl.make_gs_jobs([(16, 16, 32, 24, 48, 1, 16, 64)]), 1, None) == tl.TL_ERR_SHAPE
+    assert L.tl_ternary_gemm_gs_grouped(tl.make_gs_jobs([(16, 16, 32, 256, 48, 1, 16, 64)]), 5000, None) == tl.TL_ERR_SHAPE
     assert L.tl_probe_copy(16, 16, 24, None) == tl.TL_ERR_SHAPE
     assert L.tl_probe_read(16, 24, 16, None) == tl.TL_ERR_SHAPE
     assert L.tl_probe_read(16, 32, None, None) == tl.TL_ERR_NULL
