@@ -100,17 +100,41 @@ mfma_kernel(MfmaParams p)
     unsigned char* const Xs = lds_all + set * (2 * XBUF);
     unsigned char* const Ws = lds_all + SPLIT * (2 * XBUF) + set * (4 * WSTAGES * WSTAGE);
 
-    // XCD-aware tile order: consecutive workgroup ids go to different XCDs (8 of them), so a
-    // group's position inside its XCD picks neighbouring tiles that share a W column block.
+    // XCD-aware tile order.  Consecutive workgroup ids go to different XCDs (8 of them, each with an
+    // L2 of its own), so workgroup id is the (id / 8)-th of XCD id % 8.  Each XCD owns a region of
+    // the tile grid and walks it in bands of 4 row blocks, column block by column block: the 64
+    // workgroups that are resident on an XCD at a time then form 4 row blocks x 16 column blocks, so
+    // that a block of X is fetched into that L2 once for 16 tiles and a block of W once for 4
+    // (measured against XCD = column bands over all rows: +1 % at 2048 x 14336, +5 to 6 % at
+    // 4096 x 12288 and 4096 x 14336, +4 % at 2048 x 4096 x 11008; the chip is power-limited here,
+    // and bytes that do not cross the fabric are power for the matrix pipes).
     const int total = p.tiles_m * p.tiles_n;
-    int id = blockIdx.x;
+    int tn, tm;
     {
-        const int per_xcd = (total + 7) / 8;
-        const int remapped = (id & 7) * per_xcd + (id >> 3);
-        id = (remapped < total && (total & 7) == 0) ? remapped : id;
+        const int x = int(blockIdx.x) & 7, q = int(blockIdx.x) >> 3;
+        int rx = 0, xpb = 1;                            // row blocks per XCD region, XCDs side by side per band of rows
+        if ((p.tiles_m & 31) == 0) {
+            rx = p.tiles_m >> 3;
+        } else if (p.tiles_m == 4 || p.tiles_m == 8 || p.tiles_m == 16) {
+            rx = 4;
+            xpb = 8 / (p.tiles_m >> 2);
+        }
+        if (rx != 0 && p.tiles_n % xpb == 0) {
+            const int cx = p.tiles_n / xpb;             // column blocks per region
+            const int band = x / xpb, part = x - band * xpb;
+            const int s4 = q / (4 * cx), r = q - s4 * (4 * cx);
+            tn = part * cx + (r >> 2);
+            tm = band * rx + 4 * s4 + (r & 3);
+        } else {
+            // any other grid: XCD x takes the x-th eighth of the tiles in column-major order
+            int id = blockIdx.x;
+            const int per_xcd = (total + 7) / 8;
+            const int remapped = x * per_xcd + q;
+            id = (remapped < total && (total & 7) == 0) ? remapped : id;
+            tn = id / p.tiles_m;
+            tm = id - tn * p.tiles_m;
+        }
     }
-    const int tn = id / p.tiles_m;
-    const int tm = id - tn * p.tiles_m;
     const int m_base = tm * BM;
     const int n_base = tn * BN + wave * NW;            // this wave's first column
     const int K = p.K;

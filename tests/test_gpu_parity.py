@@ -368,6 +368,23 @@ def test_prefill_full_size_sampled(M):
     assert differs.mean() < 1e-3
 
 
+@pytest.mark.parametrize("M,N,K", [(4096, 12288, 256), (8192, 2048, 128), (4096, 3840, 192), (512, 14336, 128),
+                                   (1024, 2560, 128), (2048, 2560, 64), (5120, 2048, 64)])
+def test_mfma_tile_order_covers_every_tile(M, N, K):
+    # grids of 32 and 64 row blocks (one region of the tile grid per XCD, walked in bands of four row
+    # blocks), of 4, 8 and 16 row blocks (XCDs side by side along the columns), and grids the region
+    # scheme does not take (column count not divisible, 40 row blocks): every output written, once,
+    # and right on sampled columns (short K keeps the oracle quick)
+    import torch
+    x, W, g = si.layer(5200 + M + N + K, M, N, K)
+    Wp = tl.tl_pack_2bit(W)
+    y = run_gemm(x, Wp, g, N, K, tl.TL_PATH_MFMA)
+    assert not (y.view(np.int16) == -21555).all(axis=0).any()         # no column left at the poison value
+    cols = np.sort(np.random.default_rng(4).choice(N, 192, replace=False))
+    cols = np.unique(np.concatenate([cols, np.arange(0, N, 256), np.arange(255, N, 256)]))   # both edges of every column block
+    assert_close(y[:, cols], oracle.gemm(x, np.ascontiguousarray(W[cols]), g), x, g, f"mfma tile order {M}x{N}x{K}")
+
+
 # ---------------------------------------------------------------- grouped launch
 
 def test_grouped_matches_oracle_and_single_calls():
