@@ -238,14 +238,16 @@ def main():
                 if n_w % 4 == 0:
                     side.synchronize()
             side.synchronize()
-            ts = []
-            for _ in range(N_BATCH):
-                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                a.record(side)
+            # the timed batches are enqueued back to back with an event between them and waited for
+            # once, so that the GPU does not idle (and clock down) between batches and the host's
+            # launch of a batch overlaps the batch before it; a batch is the interval between two events
+            evs = [torch.cuda.Event(enable_timing=True) for _ in range(N_BATCH + 1)]
+            evs[0].record(side)
+            for i in range(N_BATCH):
                 batch()
-                b.record(side)
-                side.synchronize()
-                ts.append(a.elapsed_time(b))
+                evs[i + 1].record(side)
+            side.synchronize()
+            ts = [evs[i].elapsed_time(evs[i + 1]) for i in range(N_BATCH)]
         stream = torch.cuda.current_stream().cuda_stream
         ts.sort()
         return dict(ms=ts[len(ts) // 2], p10=ts[len(ts) // 10], p90=ts[-1 - len(ts) // 10], batches=len(ts))
