@@ -165,6 +165,36 @@ def test_gs_grouped_block_with_long_k():
     _run_gs_grouped(specs, 12300, check_single=False, sample=192)
 
 
+def test_gs_grouped_runs_too_long_for_one_launch_go_out_job_by_job():
+    # two jobs with two passes over K (K = 4608) and 6250 tiles each: in one launch a workgroup's run
+    # would not fit the LDS that keeps its sums between the passes, so the jobs are launched one by one
+    import torch
+    M, N, K, group = 2, 100000, 4608, 256
+    rng = np.random.default_rng(12500)
+    jobs, keep = [], []
+    for i in range(2):
+        W = si.ternary_weights(rng, N, K)
+        x = si.activations(rng, M, K)
+        sc = si.group_scales(rng, K // group, N)
+        Wp = tl.tl_pack_2bit(W)
+        cols = np.sort(rng.choice(N, 96, replace=False))
+        ref = oracle.gemm_packed2_group_scales(x, np.ascontiguousarray(Wp[cols]), np.ascontiguousarray(sc[:, cols]), group, K)
+        xd, wd, sd = to_dev(x.view(np.int16)), dev_u32(Wp), to_dev(sc.view(np.int16))
+        yd = torch.full((M, N), POISON, dtype=torch.int16, device="cuda")
+        jobs.append((xd, wd, sd, group, yd, M, N, K))
+        keep.append((x, sc, cols, ref, yd))
+        del W, Wp
+    tl.tl_ternary_gemm_gs_grouped(jobs)
+    torch.cuda.synchronize()
+    for x, sc, cols, ref, yd in keep:
+        y = yd.cpu().numpy().view(np.float16)
+        # a tile that was never written would leave 16 neighbouring columns at the poison value (a
+        # genuine output may equal that bit pattern here and there)
+        hit = (y.view(np.int16) == POISON)
+        assert not (hit[:, :-1] & hit[:, 1:]).any()
+        assert_close(y[:, cols], ref, x, float(sc.max()), "group scales grouped, job by job")
+
+
 def test_gs_grouped_random_calls():
     rng = np.random.default_rng(12400)
     for call in range(6):
