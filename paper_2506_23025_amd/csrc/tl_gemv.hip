@@ -997,7 +997,7 @@ gemv_lean_kernel(LeanBatch b)
     const uint32_t ww_off = uint32_t(lr) * 128u + (uint32_t(lc ^ lr) << 4);
     const uint32_t wr_off0 = uint32_t(mi) * 128u + (uint32_t((mg) ^ (mi & 7)) << 4);
     const uint32_t wr_off1 = uint32_t(mi) * 128u + (uint32_t((4 + mg) ^ (mi & 7)) << 4);
-    const float gamma = R.gamma;
+    const float gamma = R.gamma * 65536.f;               // times the 2^16 left in the partial sums
     typedef __attribute__((address_space(1))) __half* gh_ptr;
     // the output quad this thread owns in an item's epilogue: tile t = threadIdx.x / 64 of the item
     const int ot = int(threadIdx.x) >> 6;
@@ -1045,7 +1045,10 @@ gemv_lean_kernel(LeanBatch b)
                     acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), as_f16x8(bb), c0, 0, 0, 0);
                 }
             }
-            part[t] = acc[0] * 1048576.f + acc[1] * 262144.f + acc[2] * 65536.f;
+            // the three classes carry 2^-20, 2^-18 and 2^-16: two fused multiply-adds leave the sum at
+            // 2^-16, and that power of two goes into the scale of the epilogue (exact, same roundings)
+            part[t] = __builtin_elementwise_fma(__builtin_elementwise_fma(acc[0], f32x4{4.f, 4.f, 4.f, 4.f}, acc[1]),
+                                                f32x4{4.f, 4.f, 4.f, 4.f}, acc[2]);
         }
         // split-K: partial sums into this wave's set `parity`, one LDS-only barrier, fixed-order sum
         unsigned char* const red = my_lds + 4096 + parity * (T * 1024);
