@@ -238,6 +238,24 @@ def test_header_is_plain_c_and_the_library_links_from_c(tmp_path):
     assert r.returncode == 0 and r.stdout.strip() == "ok", (r.returncode, r.stdout, r.stderr)
 
 
+def test_workgroup_allocator_invariants(tmp_path):
+    # csrc/tl_deal.hpp is host logic without an entry point of its own: a small C++ program checks its
+    # invariants (every job served, counts add up, monotone in cost, no single move helps)
+    import os
+    import shutil
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    cxx = shutil.which("g++") or shutil.which("c++")
+    assert cxx, "no C++ compiler"
+    exe = str(tmp_path / "deal_host")
+    cmd = [cxx, "-std=c++17", "-O1", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(root, "paper_2506_23025_amd", "csrc"),
+           os.path.join(root, "tests", "c", "deal_host.cpp"), "-o", exe]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([exe], capture_output=True, text=True)
+    assert r.returncode == 0 and r.stdout.strip() == "ok", (r.returncode, r.stdout, r.stderr)
+
+
 def test_kernel_choice_is_a_pure_function_of_the_shape():
     # decode batch sizes stream the weights; the prefill sizes of the workloads use the tiled MFMA
     # kernel; shapes neither fast kernel takes fall back; invalid sizes give no path
