@@ -342,6 +342,41 @@ def main():
                              TFLOPs=round(2.0 * M * N * K / us / 1e6, 3),
                              read_only_probe_us=round(pus, 3), kernel_vs_probe=round(pus / us, 4)))
 
+    # lone calls with long K: the down projections that close a block (11008 -> 4096, 14336 -> 4096),
+    # which a decode step issues on their own; their own weights, cycled as above
+    long_k_calls = []
+    if not args.no_per_call:
+        lrng = np.random.default_rng(si.SEEDS["c3"] + 17)
+        for lk, lN in ((11008, 4096), (14336, 4096)):
+            lWp = tl.tl_pack_2bit(si.ternary_weights(lrng, lN, lk))
+            lcopies = max(4, min(32, (400 << 20) // lWp.nbytes))
+            lring = torch.empty((lcopies,) + lWp.shape, dtype=torch.int32, device=dev)
+            lring[0].copy_(torch.from_numpy(lWp.view(np.int32)))
+            for i in range(1, lcopies):
+                lring[i].copy_(lring[0])
+            lg = si.gamma_bits(si.gamma_uniform(lrng))
+            for M in (1, 16):
+                lx = torch.from_numpy(si.activations(lrng, M, lk).view(np.int16)).to(dev)
+                ly = torch.empty((M, lN), dtype=torch.int16, device=dev)
+                lcur = [0]
+
+                def call_long():
+                    i = lcur[0]
+                    lcur[0] = (i + 1) % lcopies
+                    st_ = L.tl_ternary_gemm(lx.data_ptr(), lring[i].data_ptr(), lg, ly.data_ptr(), M, lN, lk, stream)
+                    if st_ != tl.TL_OK:
+                        raise tl.TlError(st_, "tl_ternary_gemm")
+
+                reps = max(1, min(args.steps, 200))
+                st = timed(call_long, reps)
+                us = per_unit(st, reps)[0]
+                b = algorithmic_bytes(M, lN, lk)
+                pus = probe_us(b, reps)
+                long_k_calls.append(dict(M=M, N=lN, K=lk, **us_row(st, reps), GBps=round(b / us / 1e3, 1),
+                                         hbm_frac=round(b / us / 1e3 / HBM_PEAK_GBS, 4),
+                                         read_only_probe_us=round(pus, 3), kernel_vs_probe=round(pus / us, 4)))
+            del lring
+
     # large M: the LDS-tiled MFMA kernel against the dense fp16 MFMA peak, and against a kernel that
     # only issues the same matrix instruction on the same kind of operands; and the batch sizes in
     # between with whichever kernel the library picks
@@ -622,7 +657,7 @@ def main():
         "ms_per_step_p10": round(head["p10"] / args.steps, 5), "ms_per_step_p90": round(head["p90"] / args.steps, 5),
         "timing": {"batches": head["batches"], "steps_per_batch": args.steps, "figure": "median batch", "untimed_load_before_timing_ms": WARM_MS},
         "roofline": roofline, "cpu_baseline": cpu, "single_calls": single, "warm_same_buffer": warm_same,
-        "single_launch_latency_us": latency, "per_call": per_call, "mfma_probe": mfma_probe, "prefill": prefill,
+        "single_launch_latency_us": latency, "per_call": per_call, "long_k_calls": long_k_calls, "mfma_probe": mfma_probe, "prefill": prefill,
         "mid_batch": mid_batch, "block": block, "formats": formats, "grouped_formats": grouped_formats,
         "launch_mode": "eager" if args.eager else "hip_graph_replay", "weights": args.weights,
         "host_wall_ms_timed_region_incl_capture": round(wall_ms, 2), "context": PAPER_CONTEXT,

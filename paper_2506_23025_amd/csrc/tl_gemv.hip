@@ -1082,6 +1082,232 @@ gemv_lean_kernel(LeanBatch b)
     else item(std::integral_constant<int, T>{}, std::false_type{}, i * T, i & 1);
 }
 
+// ------------------------------------------------------------------------------------------
+// Long-K form of the lean kernel: 4096 < K <= 16384 and at most T tiles per workgroup, i.e. the
+// lone down projection of a block at decode batch sizes (11008 -> 4096, 14336 -> 4096), where a
+// workgroup's whole share is one or two tiles and the time is a chain of memory round trips unless
+// they overlap.  Wave w owns the K slices w, w + 8, w + 16, w + 24 ("passes").  All of a pass's
+// data -- the activation slice by LDS-DMA, the T tile slices of weights into one of two register
+// sets -- is requested while the pass before it is decoded, so the chain is one round trip plus
+// the decodes:
+//     x(0), W(0), W(1) | build(0) | x(1) | decode(0) | wait all | build(1) | W(2), x(2) | decode(1) | ...
+// The accumulators of the T tiles stay in registers over all passes (three position classes each),
+// the -sum(x) seeds of the passes add up in one accumulator, and the waves exchange partial sums
+// once, at the end.  The LDS-DMA requests are inline assembly: for a transfer it knows of, the
+// compiler drains the memory pipeline before every later LDS access, which would undo the overlap;
+// every wait for them is an explicit s_waitcnt (and since the compiler's own count of outstanding
+// loads starts afresh at each of those, the weight loads issued after it are waited for exactly).
+constexpr int kLongMaxPasses = 4;
+constexpr int kLongWaveLds = kWaveLds + 2048;     // 16 KB of activation staging + one tile slice
+
+template <int T>
+__global__ void __launch_bounds__(512)
+gemv_longk_kernel(LeanBatch b)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int NW = blockDim.x >> 6;
+    unsigned char* const my_lds = lds_raw + wave * kLongWaveLds;
+    unsigned char* const tile_buf = my_lds + kWaveLds;
+    typedef const __attribute__((address_space(1))) unsigned char* gbytes;
+
+    const WgRec& R = b.rec[blockIdx.x];
+    const int K = R.K, N = R.N, rows = R.Mrem, ntiles = R.ntiles;
+    const int slices = (K + kSliceK - 1) / kSliceK;
+    const int P = __builtin_amdgcn_readfirstlane((slices - wave + NW - 1) / NW);   // passes of this wave, >= 1
+    const uint32_t row_bytes = uint32_t(K) >> 2;
+    const uint32_t tile_bytes = 16u * row_bytes;
+
+    const int lr = lane >> 3, lc = lane & 7;   // load mapping: row of the half tile, chunk of the slice
+    const int mi = lane & 15, mg = lane >> 4;  // MFMA mapping: row / activation column, k group
+
+    // ---- activations of slice wave + NW * p -> staging, swizzled (lane l fetches piece l ^ (r & 7) of row r)
+    const uint32_t stage_addr = uint32_t(uintptr_t((const __attribute__((address_space(3))) unsigned char*)my_lds));
+    auto dma16 = [&](gbytes src, uint32_t lds_base) {       // lane l: 16 bytes from src (per lane) to lds_base + 16 l
+        const uint32_t base = __builtin_amdgcn_readfirstlane(lds_base);
+        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(base) : "memory");
+    };
+    auto stage_x = [&](int p) {
+        const int sl = wave + NW * p;
+        const size_t row_stride = size_t(K) * 2;
+        gbytes src = (gbytes)(R.x + size_t(sl) * (kSliceK * 2));
+        if ((sl + 1) * kSliceK <= K) {                      // the whole slice lies inside K
+            const uint32_t lane16 = uint32_t(lane) << 4;
+#pragma unroll 1
+            for (int r = 0; r < rows; ++r) {
+                dma16(src + (lane16 ^ (uint32_t(r & 7) << 4)), stage_addr + uint32_t(r) * 1024u);
+                src += row_stride;
+            }
+        } else {
+#pragma unroll 1
+            for (int r = 0; r < rows; ++r) {
+                const int kk = (lane ^ (r & 7)) << 3;      // first of this lane's 8 activations within the slice
+                if (sl * kSliceK + kk < K) {
+                    dma16(src + uint32_t(kk) * 2u, stage_addr + uint32_t(r) * 1024u);
+                } else {
+                    *reinterpret_cast<u32x4*>(my_lds + r * 1024 + (uint32_t(lane) << 4)) = u32x4{0u, 0u, 0u, 0u};
+                }
+                src += row_stride;
+            }
+        }
+    };
+
+    // ---- weights: the T tile slices of a pass into register set `set`
+    const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(R.W), 0, uint32_t(ntiles) * tile_bytes, 0x00020000);
+    u32x4 wreg[2][T][2];
+    auto issue_w = [&](auto set_tag, int p) {
+        constexpr int SET = decltype(set_tag)::value;
+        uint32_t chunk = uint32_t(wave + NW * p) * 8u + uint32_t(lc);
+        if (chunk >= (uint32_t(K) >> 6)) chunk = 0;        // past K: multiplied by zero activations
+        const uint32_t voff0 = uint32_t(lr) * row_bytes + chunk * 16u;
+        const uint32_t voff1 = voff0 + 8u * row_bytes;
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            const uint32_t so = uint32_t(t < ntiles ? t : ntiles - 1) * tile_bytes;   // past the run: its last tile again
+            wreg[SET][t][0] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(wres, voff0, so, 2));   // 2: nt
+            wreg[SET][t][1] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(wres, voff1, so, 2));
+        }
+    };
+
+    // ---- staged activations -> MFMA B operands (as in gemv_lean_kernel); the pass's -sum(x) goes into nsx
+    uint32_t breg[2][4][8];
+    f32x4 nsx = f32x4{0.f, 0.f, 0.f, 0.f};
+    int mr = 1;
+    while (mr < rows) mr *= 2;
+    const int xrow = mi & (mr - 1);
+    const uint32_t xr_off = uint32_t(xrow) * 1024u + uint32_t(mg) * 128u;
+    const uint32_t sw = uint32_t(xrow & 7);
+    const bool live = mi < rows;
+    const uint32_t sel_lo = live ? 0x05040100u : 0x0c0c0c0cu;
+    const uint32_t sel_hi = live ? 0x07060302u : 0x0c0c0c0cu;
+    auto build = [&]() {
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int wd = 0; wd < 4; ++wd) {
+                const u32x4 lo = *reinterpret_cast<const u32x4*>(my_lds + xr_off + h * 512 + ((uint32_t(2 * wd) ^ sw) << 4));
+                const u32x4 hi = *reinterpret_cast<const u32x4*>(my_lds + xr_off + h * 512 + ((uint32_t(2 * wd + 1) ^ sw) << 4));
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    breg[h][wd][2 * r] = __builtin_amdgcn_perm(hi[r], lo[r], sel_lo);
+                    breg[h][wd][2 * r + 1] = __builtin_amdgcn_perm(hi[r], lo[r], sel_hi);
+                }
+            }
+        const uint32_t c = 0x80108010u;                   // fp16 pair of -2^-20
+        const u32x4 a = u32x4{c, c, c, c};
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const u32x4 bb = u32x4{breg[h][0][e], breg[h][1][e], breg[h][2][e], breg[h][3][e]};
+                nsx = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), as_f16x8(bb), nsx, 0, 0, 0);
+            }
+        // the staging area may be written again: every read above has returned
+        __builtin_amdgcn_s_waitcnt(0xF | (0x3 << 14) | (0x7 << 4));      // lgkmcnt(0)
+    };
+
+    // ---- one pass of the T tiles from register set `set` into the tiles' accumulators
+    const uint32_t ww_off = uint32_t(lr) * 128u + (uint32_t(lc ^ lr) << 4);
+    const uint32_t wr_off0 = uint32_t(mi) * 128u + (uint32_t((mg) ^ (mi & 7)) << 4);
+    const uint32_t wr_off1 = uint32_t(mi) * 128u + (uint32_t((4 + mg) ^ (mi & 7)) << 4);
+    f32x4 acc[T][3];
+#pragma unroll
+    for (int t = 0; t < T; ++t)
+#pragma unroll
+        for (int j = 0; j < 3; ++j) acc[t][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    auto decode = [&](auto set_tag) {
+        constexpr int SET = decltype(set_tag)::value;
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            *reinterpret_cast<u32x4*>(tile_buf + ww_off) = wreg[SET][t][0];
+            *reinterpret_cast<u32x4*>(tile_buf + 1024 + ww_off) = wreg[SET][t][1];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const u32x4 wv = *reinterpret_cast<const u32x4*>(tile_buf + (h ? wr_off1 : wr_off0));
+                // element e of each half-word sits at bits 2e, 2e+1; the mantissa bits 4..9 (classes
+                // 0..2 -> accumulators) hold e = 2,3,4 as loaded, e = 0,1 after << 4 and e = 5,6,7 after >> 6
+                const u32x4 sh[3] = {wv << 4, wv, wv >> 6};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int src = e < 2 ? 0 : (e < 5 ? 1 : 2);
+                    const int j = e < 2 ? e : (e < 5 ? e - 2 : e - 5);
+                    const uint32_t mask = 0x00300030u << (2 * j);
+                    const u32x4 a = sh[src] & mask;
+                    const u32x4 bb = u32x4{breg[h][0][e], breg[h][1][e], breg[h][2][e], breg[h][3][e]};
+                    acc[t][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), as_f16x8(bb), acc[t][j], 0, 0, 0);
+                }
+            }
+        }
+    };
+    using Set0 = std::integral_constant<int, 0>;
+    using Set1 = std::integral_constant<int, 1>;
+
+    // ---- prologue: x(0), W(0), W(1) requested at once
+    stage_x(0);
+    issue_w(Set0{}, 0);
+    if (P > 1) {
+        issue_w(Set1{}, 1);
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(4 * T));      // x(0) is in
+        build();
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * T));      // W(0) is in
+        stage_x(1);
+    } else {
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * T));
+        build();
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    }
+    for (int p = 0; p < P; p += 2) {
+        decode(Set0{});                                    // pass p
+        if (p + 1 < P) {
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));      // x(p + 1) and W(p + 1) are in
+            build();
+            if (p + 2 < P) {
+                issue_w(Set0{}, p + 2);
+                stage_x(p + 2);
+            }
+            decode(Set1{});                                // pass p + 1
+            if (p + 2 < P) {
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+                build();
+                if (p + 3 < P) {
+                    issue_w(Set1{}, p + 3);
+                    stage_x(p + 3);
+                }
+            }
+        }
+    }
+
+    // ---- split-K: partial sums (at 2^-16, see gemv_lean_kernel) into the staging area, one barrier, fixed-order sum
+    const float gamma = R.gamma * 65536.f;
+    typedef __attribute__((address_space(1))) __half* gh_ptr;
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+        const f32x4 four = f32x4{4.f, 4.f, 4.f, 4.f};
+        const f32x4 part = __builtin_elementwise_fma(__builtin_elementwise_fma(acc[t][0] + nsx, four, acc[t][1]), four, acc[t][2]);
+        reinterpret_cast<f32x4*>(my_lds + t * 1024)[lane] = part;
+    }
+    __builtin_amdgcn_s_waitcnt(0xF | (0x3 << 14) | (0x7 << 4));
+    __builtin_amdgcn_s_barrier();
+    const int ot = int(threadIdx.x) >> 6;
+    if (ot < T && ot < ntiles) {
+        f32x4 v[8];
+#pragma unroll
+        for (int w = 0; w < 8; ++w)
+            v[w] = (w < NW) ? reinterpret_cast<const f32x4*>(lds_raw + w * kLongWaveLds + ot * 1024)[lane]
+                            : f32x4{0.f, 0.f, 0.f, 0.f};
+        const f32x4 s = ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
+        if (mi < rows) {
+            gh_ptr const yrow = (gh_ptr)(R.y + size_t(mi) * size_t(N));
+            const uint32_t ycol = uint32_t(R.tile0 + ot) * 16u + 4u * uint32_t(mg);
+            const f16x2 lo = {(_Float16)(gamma * s[0]), (_Float16)(gamma * s[1])};
+            const f16x2 hi = {(_Float16)(gamma * s[2]), (_Float16)(gamma * s[3])};
+            *(__attribute__((address_space(1))) u32x2*)(yrow + ycol) =
+                u32x2{__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
+        }
+    }
+}
+
 using KernelFn = void (*)(GemvBatch);
 
 template <bool MULTI>
@@ -1163,6 +1389,7 @@ struct GemvPolicy {
     int t_stream = 0;                   // stream form: cap on tiles per item (0: none)
     int long_k_min_run = 3;             // K > 4096 streams if the call averages this many tile passes per workgroup
     int lean = 1;                       // launches the lean kernel can take go to it
+    int longk = 1;                      // lone calls with 4096 < K <= 16384 and at most two tiles per workgroup: long-K form
 };
 const GemvPolicy g_policy{};   // fixed in the library; development builds patch this line to try other values
 
@@ -1214,6 +1441,64 @@ hipError_t launch_lean(const GemvBatch& b, const int* wg, int NW, int T, hipStre
     }
     hipLaunchKernelGGL(fn, dim3(grid), dim3(NW * 64), size_t(NW) * stream_wave_lds(T), s, lb);
     return hipGetLastError();
+}
+
+LeanFn pick_longk(int T)
+{
+    return T == 1 ? gemv_longk_kernel<1> : gemv_longk_kernel<2>;
+}
+
+// Calls in which every GEMM has 4096 < K <= 16384 and N a multiple of 16, and which hold at most two
+// tiles per workgroup in all (the lone down projection of a block: 11008 -> 4096, 14336 -> 4096):
+// the long-K form of the lean kernel, one record per workgroup with its one or two tiles.  Returns
+// false, and launches nothing, for any other call.
+bool launch_longk(const GemmDesc* jobs, int count, hipStream_t s, hipError_t* err)
+{
+    int64_t tiles_total = 0;
+    for (int i = 0; i < count; ++i) {
+        const GemmDesc& d = jobs[i];
+        const int64_t slices = (d.K + kSliceK - 1) / kSliceK;
+        if (slices <= kStreamWaves || slices > int64_t(kStreamWaves) * kLongMaxPasses || (d.N & 15) != 0) return false;
+        tiles_total += ((d.M + 15) / 16) * (d.N / 16);
+        if (tiles_total > 2 * kLeanMaxGroups) return false;
+    }
+    const int T = tiles_total <= kLeanMaxGroups ? 1 : 2;
+    int64_t groups = 0;
+    for (int i = 0; i < count; ++i) groups += ((jobs[i].M + 15) / 16) * ((jobs[i].N / 16 + T - 1) / T);
+    if (groups > kLeanMaxGroups) return false;
+    LeanBatch lb;
+    int grid = 0;
+    for (int i = 0; i < count; ++i) {
+        const GemmDesc& d = jobs[i];
+        const int tiles = int(d.N / 16);
+        const size_t tile_bytes = size_t(16) * (size_t(d.K) / 4);
+        for (int64_t m0 = 0; m0 < d.M; m0 += 16) {
+            for (int t0 = 0; t0 < tiles; t0 += T) {
+                WgRec& r = lb.rec[grid++];
+                r.tile0 = t0;
+                r.ntiles = tiles - t0 < T ? tiles - t0 : T;
+                r.W = reinterpret_cast<const unsigned char*>(d.W) + size_t(t0) * tile_bytes;
+                r.x = reinterpret_cast<const unsigned char*>(d.x + m0 * d.K);
+                r.y = d.y + m0 * d.N;
+                r.gamma = d.gamma;
+                r.K = int(d.K); r.N = int(d.N);
+                r.Mrem = int(d.M - m0 < 16 ? d.M - m0 : 16);
+                r.pad[0] = r.pad[1] = r.pad[2] = r.pad[3] = 0;
+            }
+        }
+    }
+    LeanFn fn = pick_longk(T);
+    static bool lds_raised[kMaxDevices][3];
+    const int dev = device_slot();
+    if (dev < 0 || !lds_raised[dev][T]) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kStreamWaves * kLongWaveLds);
+        if (e != hipSuccess) { *err = e; return true; }
+        if (dev >= 0) lds_raised[dev][T] = true;
+    }
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(kStreamWaves * 64), size_t(kStreamWaves) * kLongWaveLds, s, lb);
+    *err = hipGetLastError();
+    return true;
 }
 
 // Stream form: one job per workgroup, a run of consecutive tiles each.  Workgroups are dealt
@@ -1397,6 +1682,10 @@ hipError_t gemv_init()
     auto raise = [](KernelFn fn, int bytes) {
         return hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
     };
+    for (int T = 1; T <= 2; ++T) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(pick_longk(T)), hipFuncAttributeMaxDynamicSharedMemorySize, kStreamWaves * kLongWaveLds);
+        if (e != hipSuccess) return e;
+    }
     for (int T = 1; T <= 3; ++T) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(pick_lean(T)), hipFuncAttributeMaxDynamicSharedMemorySize, 8 * stream_wave_lds(3));
         if (e != hipSuccess) return e;
@@ -1423,6 +1712,10 @@ bool gemv_supports(int64_t M, int64_t N, int64_t K)
 
 hipError_t launch_gemv_jobs(const GemmDesc* jobs, int count, hipStream_t s)
 {
+    if (g_policy.longk) {
+        hipError_t e = hipSuccess;
+        if (launch_longk(jobs, count, s, &e)) return e;
+    }
     // A user job with M > 16 becomes ceil(M / 16) kernel jobs (blocks of 16 activation rows).
     int64_t blocks_total = 0;
     for (int i = 0; i < count; ++i) blocks_total += (jobs[i].M + 15) / 16;

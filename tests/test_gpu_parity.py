@@ -103,6 +103,31 @@ def test_gemv_matches_oracle(M, N, K):
     assert_close(y, oracle.gemm_packed2(x, Wp, g, K), x, g, f"gemv {M}x{N}x{K}")
 
 
+LONGK_SHAPES = [
+    # lone calls with 4096 < K <= 16384 and at most two tiles per workgroup: the long-K form (passes of a
+    # wave one slice of 512 apart in blocks of 8).  Two, three and four passes, a ninth slice of 64
+    # weights only, a ragged last slice, one and two tiles per workgroup, several blocks of 16 rows,
+    # and the sizes around its limits (8192 columns; 16384 = 32 slices; beyond both the other kernels)
+    (1, 4096, 11008), (16, 4096, 14336), (3, 272, 4160), (5, 16, 4608), (1, 8192, 8192), (16, 8192, 5120),
+    (7, 4112, 8192), (40, 1024, 11008), (2, 512, 16384), (4, 8208, 8192), (9, 64, 16448), (16, 4096, 16384),
+    (33, 2048, 12288), (1, 48, 12352),
+]
+
+
+@pytest.mark.parametrize("M,N,K", LONGK_SHAPES)
+def test_gemv_long_k_lone_calls(M, N, K):
+    x, W, g = si.layer(5600 + M + N + K, M, N, K)
+    Wp = tl.tl_pack_2bit(W)
+    y = run_gemm(x, Wp, g, N, K, tl.TL_PATH_GEMV)
+    if N * K <= 4096 * 4096:
+        assert_close(y, oracle.gemm_packed2(x, Wp, g, K), x, g, f"long K {M}x{N}x{K}")
+    else:
+        cols = np.sort(np.random.default_rng(5).choice(N, 384, replace=False))
+        cols = np.unique(np.concatenate([cols, np.arange(0, N, 16), np.arange(15, N, 16)[:64]]))[:640]
+        assert_close(y[:, cols], oracle.gemm(x, np.ascontiguousarray(W[cols]), g), x, g, f"long K {M}x{N}x{K} sampled")
+        assert not (y.view(np.int16) == -21555).all(axis=0).any()
+
+
 def test_gemv_rejects_k_not_multiple_of_64():
     import torch
     t = torch.zeros(4096, dtype=torch.int16, device="cuda")
