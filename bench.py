@@ -600,8 +600,14 @@ def main():
             if "=" in line and not line.startswith("#"):
                 k_, v_ = line.split("=", 1)
                 kv[k_.strip()] = v_.strip()
-        src_hash = hashlib.sha256(open(os.path.join(ROOT, "paper_2506_23025_amd", "csrc", "tl_gemv.hip"), "rb").read()).hexdigest()
-        if kv.get("kernel_source_sha256") == src_hash:
+        # hash of the code alone: comments and white space do not change what was measured
+        code = []
+        for line in open(os.path.join(ROOT, "paper_2506_23025_amd", "csrc", "tl_gemv.hip")):
+            line = "".join(line.split("//", 1)[0].split())
+            if line:
+                code.append(line)
+        src_hash = hashlib.sha256("\n".join(code).encode()).hexdigest()
+        if kv.get("kernel_code_sha256") == src_hash:
             traffic = float(kv["grouped_sweep_bytes_per_launch"])
             weights = sum(layers[name]["N"] * K for name, _ in calls)
             if "grouped_sweep_valu_insts_per_launch" in kv:

@@ -30,13 +30,17 @@
 //    by gamma, rounded to fp16 (RNE) and stored.  No atomics: results are deterministic.
 //  * One launch can carry up to 32 independent jobs (a job = one matrix and at most 16, in
 //    one variant 32, activation rows); a workgroup finds its job from its index.
-//  * Three forms.  The stream form (gemv_stream_kernel: K up to 8 slices per pass) gives a wave
+//  * Four forms.  The stream form (gemv_stream_kernel: K up to 8 slices per pass) gives a wave
 //    one slice for the whole kernel and a workgroup a run of consecutive tiles of one job, so
 //    activations are staged once and only weights move afterwards.  The lean form
 //    (gemv_lean_kernel) is the stream form cut down to the decode shapes (one pass over K, one
 //    block of 16 rows, one gamma, N a multiple of 16) and is what those launches run.  The
-//    general form (gemv_kernel) loops a wave over slices and a workgroup over items of any
-//    job; it takes lone calls with long K.
+//    long-K form (gemv_longk_kernel) takes lone calls with 4096 < K <= 16384 whose workgroups
+//    get one or two tiles each: a wave walks its up to four slices with the next one's data
+//    already in flight.  The general form (gemv_kernel) loops a wave over slices and a
+//    workgroup over items of any job; it takes the calls with K > 4096 that are too small
+//    for the stream form's passes to pay and that the long-K form does not cover (K > 16384,
+//    N not a multiple of 16, more than 512 tiles).
 #include "tl_internal.hpp"
 #include "tl_deal.hpp"
 
@@ -865,7 +869,7 @@ gemv_stream_kernel(GemvBatch b)
 //  * Every wave is active in every tile (no predicated tile bodies); the last item comes in one
 //    copy per tile count.
 // The vector ALU is what limits the steady state of these kernels (64 ANDs + 16 shifts + 16 MFMA
-// issues + 12 combine operations per wave and tile are 108 of the ~120 issue slots a tile may
+// issues + 8 combine operations per wave and tile are 104 of the ~120 issue slots a tile may
 // take if the loop is to keep up with HBM), so every instruction that is not decode counts.
 constexpr int kLeanMaxGroups = 256;
 
