@@ -1,5 +1,5 @@
-// Device decode (byte-exact twin of the host decoders), the bandwidth probe and the
-// generic VALU GEMM that accepts every shape.
+// Device decode (byte-exact twin of the host decoders), the measurement probes (copy, read-only,
+// bare MFMA loop) and the generic VALU GEMMs that accept every shape.
 #include "tl_internal.hpp"
 
 namespace tl {

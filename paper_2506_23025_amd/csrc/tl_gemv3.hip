@@ -26,7 +26,9 @@
 //    is the same, per byte of packed weights it is 1.25 times the 2-bit kernel's.
 //  * Two forms.  gemv3_stream_kernel (K in one pass of at most 7 slices, K <= 4480): a wave
 //    keeps its slice, a workgroup walks a run of tiles in items with the next item's weights in
-//    flight.  gemv3_kernel (longer K): waves loop over slices, one item per workgroup.
+//    flight; gemv3_grouped_kernel is the same body fed from one record per workgroup, so that
+//    one launch carries several GEMMs.  gemv3_kernel (longer K): waves loop over slices, one
+//    item per workgroup.
 #include "tl_internal.hpp"
 #include "tl_deal.hpp"
 
